@@ -1,0 +1,251 @@
+"""CPU checker for the bubble planner.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, plain reference the tests compare the native planner
+against.  Only tests/, the smoke check and the benchmark's cpu_baseline leg
+may import it; the product path never does.  It shares no code with the
+native library.  All arithmetic is on Python integers (ns, bytes, ppm), so
+"bit-exact" has a plain meaning.
+
+What it follows:
+  * bubble windows of a unidirectional synchronous schedule: the idle
+    fraction (p-1)/(m+p-1) (Sec. 2.1) and the fwd-bwd / fill-drain bubble
+    lengths of the 1F1B and GPipe schedules (Sec. 4.5, "Main job pipeline
+    schedule");
+  * the partitioning procedure of Algorithm 1 (Sec. 4.3), taken in the
+    paper's order: replicate the chain, then pack source nodes greedily
+    into bubbles that cycle;
+  * the choice of the configuration of maximum throughput (Sec. 4.1
+    "Putting together", Sec. 4.3 "Execution plan").
+
+Readings where the paper is silent (each is listed in the design notes):
+  - stages are 0-based; communication, gradient-sync and optimizer time are 0;
+  - time tests are strict (<), the memory test is <=, exactly as in the
+    listing of Algorithm 1; memory is tested per node;
+  - the "fraction of the bubble the Executor tries to fill" (Sec. 6.1) scales
+    every bubble duration by fill_ppm/1e6 with floor division, and a fixed
+    per-bubble switch cost may be subtracted;
+  - a node that fits no bubble would make Algorithm 1 loop forever; here the
+    procedure stops with Infeasible after len(B) consecutive empty partitions;
+  - only bubbles flagged fillable take part; P[i] runs in the
+    ((first + i) mod n)-th fillable bubble of cycle (first + i) div n.
+"""
+from __future__ import annotations
+
+KIND_FWD_BWD = 0
+KIND_GAP = 1
+KIND_FILL_DRAIN = 2
+KIND_EXPLICIT = 3
+
+
+class Infeasible(Exception):
+    """Some node fits no bubble of the cycle (first such node in .node)."""
+
+    def __init__(self, node):
+        super().__init__(f"node {node} fits no bubble")
+        self.node = node
+
+
+def iteration_time(p, m, tf, tb):
+    """Length of one main-job iteration with zero communication: (m+p-1)(t_f+t_b);
+    the per-stage idle time is the fraction (p-1)/(m+p-1) of it (Sec. 2.1)."""
+    return (m + p - 1) * (tf + tb)
+
+
+def windows_1f1b(p, m, s, tf, tb, free_bytes, fill_gaps=True, min_window=0):
+    """Idle windows of stage s in one steady-state cycle of a 1F1B schedule.
+
+    Time origin: the global start of the iteration.  Stage s runs
+    min(p-s, m) forwards back to back from s*t_f, then idles until the first
+    gradient arrives (the fwd-bwd bubble, Sec. 4.5), alternates backward and
+    forward, idles t_f before each cool-down backward (the non-contiguous
+    bubbles of Sec. 4.5), and finally idles s*(t_f+t_b) until its first forward
+    of the next iteration (the fill-drain bubble).
+
+    Returns a list of dicts (start, dur, free, kind, fillable), in time order,
+    zero-length windows dropped.  Contiguous bubbles are always fillable; the
+    t_f-long gaps only when fill_gaps is set and they last >= min_window.
+    """
+    assert p >= 1 and m >= 1 and 0 <= s < p and tf >= 0 and tb >= 0
+    T = iteration_time(p, m, tf, tb)
+    w = min(p - s - 1, m)
+    out = []
+
+    def emit(start, end, kind):
+        dur = end - start
+        if dur <= 0:
+            return
+        if kind == KIND_GAP:
+            fillable = 1 if (fill_gaps and dur >= min_window) else 0
+        else:
+            fillable = 1
+        out.append(dict(start=start, dur=dur, free=free_bytes, kind=kind, fillable=fillable))
+
+    first_b = p * tf + (p - 1 - s) * tb            # start of backward of microbatch 0
+    emit((s + min(p - s, m)) * tf, first_b, KIND_FWD_BWD)
+    j0 = (m - w) if w < m else 1
+    for j in range(j0, m):                          # idle t_f before backward j
+        a = first_b + (j - 1) * (tf + tb) + tb      # end of backward j-1
+        emit(a, a + tf, KIND_GAP)
+    emit(first_b + (m - 1) * (tf + tb) + tb, T + s * tf, KIND_FILL_DRAIN)
+    return out
+
+
+def windows_gpipe(p, m, s, tf, tb, free_bytes):
+    """Idle windows of stage s under GPipe (all forwards, then all backwards):
+    fwd-bwd bubble of (p-s-1)(t_f+t_b) and the same fill-drain bubble as 1F1B
+    (Sec. 4.5)."""
+    assert p >= 1 and m >= 1 and 0 <= s < p
+    T = iteration_time(p, m, tf, tb)
+    out = []
+    fb = (p - s - 1) * (tf + tb)
+    if fb > 0:
+        out.append(dict(start=(s + m) * tf, dur=fb, free=free_bytes, kind=KIND_FWD_BWD, fillable=1))
+    fd = s * (tf + tb)
+    if fd > 0:
+        out.append(dict(start=T + s * tf - fd, dur=fd, free=free_bytes, kind=KIND_FILL_DRAIN, fillable=1))
+    return out
+
+
+def effective_durations(bubbles, fill_ppm=1_000_000, switch_ns=0):
+    """Durations the packing may use: floor(dur*fill_ppm/1e6) - switch_ns, not below 0
+    (the fill-fraction knob of Sec. 6.1)."""
+    eff = []
+    for b in bubbles:
+        e = (b["dur"] * fill_ppm) // 1_000_000 - switch_ns
+        eff.append(e if e > 0 else 0)
+    return eff
+
+
+def partition_fill_job(bubbles, F, fill_ppm=1_000_000, first_bubble=0, switch_ns=0):
+    """Algorithm 1: partition a fill job onto the bubble cycle.
+
+    bubbles: list of dicts with dur, free, fillable.   F: list of (dur, mem).
+    Returns (chunks, replicas) where each chunk is a dict
+    (bubble, cycle, node_begin, node_end, dur, mem); node indices run over the
+    replicated chain F' = F * replicas; bubble is the index into `bubbles`.
+    """
+    idx = [i for i, b in enumerate(bubbles) if b["fillable"]]
+    n = len(idx)
+    if n == 0 or len(F) == 0:
+        raise ValueError("empty bubble cycle or empty chain")
+    if not (0 <= first_bubble < n):
+        raise ValueError("first_bubble out of range")
+    eff_all = effective_durations(bubbles, fill_ppm, switch_ns)
+    B = [eff_all[i] for i in idx]
+    M = [bubbles[i]["free"] for i in idx]
+
+    # replicate while one more copy still fits below the total bubble time
+    dur_F = sum(d for d, _ in F)
+    total_B = sum(B)
+    replicas = 1
+    while replicas * dur_F + dur_F < total_B:
+        replicas += 1
+    Fp = list(F) * replicas
+
+    chunks = []
+    pos = 0
+    i = first_bubble
+    slot = first_bubble
+    empty_run = 0
+    while pos < len(Fp):
+        begin = pos
+        dur = 0
+        mem = 0
+        while pos < len(Fp) and dur + Fp[pos][0] < B[i] and Fp[pos][1] <= M[i]:
+            dur += Fp[pos][0]
+            mem = max(mem, Fp[pos][1])
+            pos += 1
+        chunks.append(dict(bubble=idx[i], cycle=slot // n, node_begin=begin, node_end=pos,
+                           dur=dur, mem=mem))
+        if pos == begin:
+            empty_run += 1
+            if empty_run >= n:
+                raise Infeasible(pos % len(F))
+        else:
+            empty_run = 0
+        i = (i + 1) % n
+        slot += 1
+    return chunks, replicas
+
+
+def plan_cycles(chunks, n_fillable):
+    """Bubble cycles a plan occupies: ceil(len(P) / len(B))."""
+    return -(-len(chunks) // n_fillable)
+
+
+def choose_configuration(bubbles, configs, fill_ppm=1_000_000, first_bubble=0, switch_ns=0):
+    """Plan every configuration and keep the one of maximum throughput
+    samples*replicas / cycles.  configs: list of dicts (F, samples).  Ties go to
+    the smaller peak memory, then to the lower index.  Infeasible configurations
+    are skipped; returns (best_index, plans) with plans[c] = None or
+    (chunks, replicas, cycles)."""
+    n_fill = sum(1 for b in bubbles if b["fillable"])
+    plans = []
+    best = -1
+    best_key = None
+    for c, cfg in enumerate(configs):
+        try:
+            chunks, k = partition_fill_job(bubbles, cfg["F"], fill_ppm, first_bubble, switch_ns)
+        except Infeasible:
+            plans.append(None)
+            continue
+        cyc = plan_cycles(chunks, n_fill)
+        plans.append((chunks, k, cyc))
+        num = cfg["samples"] * k
+        peak = max(ch["mem"] for ch in chunks)
+        if best < 0:
+            best, best_key = c, (num, cyc, peak)
+            continue
+        bn, bc, bp = best_key
+        lhs, rhs = num * bc, bn * cyc          # num/cyc  vs  bn/bc
+        if lhs > rhs or (lhs == rhs and peak < bp):
+            best, best_key = c, (num, cyc, peak)
+    return best, plans
+
+
+# --------------------------------------------------------------------------------------
+# chain of graph nodes for a transformer fill job (Sec. 4.3: "linearizes the computational
+# graph and its profiles, turning it into a sequence of nodes with sequential dependency")
+
+OP_EMBED, OP_LAYER_FWD, OP_FINAL_LN, OP_HEAD_LOSS, OP_LAYER_BWD, OP_OPT = range(6)
+
+
+def layer_param_count(d, f):
+    """Matrices 4d^2 + 2df, biases 3d+d+f+d, LayerNorm 4d."""
+    return 4 * d * d + 2 * d * f + (3 * d + d + f + d) + 4 * d
+
+
+def chain_nodes(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, n_slots, training):
+    """Node list (op, layer, mb_first, mb_count, mem_bytes) of one replica = g microbatches.
+
+    mem_bytes of a node is its peak HBM footprint including everything the job
+    keeps resident between bubbles (Sec. 4.3 tests mem(F[0]) <= M[i] per node).
+    """
+    tokens = batch * seq
+    act = tokens * d * esize
+    lp = layer_param_count(d, f) * esize
+    emb = (vocab * d + seq * d) * esize if vocab > 0 else 0
+    lnf = 2 * d * esize
+    weights = (n_slots if streamed else n_layers) * lp + emb + lnf
+    carried = 2 * g * act
+    ws_fwd = act * 3 + tokens * 3 * d * esize + tokens * f * esize + batch * n_heads * seq * 4
+    persistent = weights + carried
+    if training:
+        n_params = n_layers * layer_param_count(d, f) + vocab * d + seq * d + 2 * d
+        persistent += n_params * 16          # fp32 master, Adam m, v, gradient accumulator
+        persistent += n_layers * lp          # transposed weight copies for the backward GEMMs
+        persistent += n_layers * g * act     # per-layer checkpoints
+    nodes = []
+    if vocab > 0:
+        nodes.append((OP_EMBED, -1, 0, g, persistent))
+    for l in range(n_layers):
+        nodes.append((OP_LAYER_FWD, l, 0, g, persistent + ws_fwd))
+    nodes.append((OP_FINAL_LN, -1, 0, g, persistent + act))
+    if training:
+        ws_bwd = ws_fwd + act * 4 + tokens * 3 * d * esize + tokens * f * esize * 2
+        logits = tokens * vocab * esize
+        nodes.append((OP_HEAD_LOSS, -1, 0, g, persistent + logits + 2 * act))
+        for l in reversed(range(n_layers)):
+            nodes.append((OP_LAYER_BWD, l, 0, g, persistent + ws_bwd))
+        nodes.append((OP_OPT, -1, 0, g, persistent))
+    return nodes

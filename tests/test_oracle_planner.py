@@ -1,0 +1,300 @@
+"""Pins for the planner checker: closed forms and numbers the paper fixes, an independent
+dependency-driven schedule simulation, brute force on tiny instances, invariants of Algorithm 1."""
+import itertools
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import planner as op
+from paper_2410_07192_amd import synth
+
+HERE = os.path.dirname(__file__)
+
+
+# ---------------------------------------------------------------- independent 1F1B simulation
+def simulate_1f1b(p, m, tf, tb):
+    """Event-driven simulation from the dependency rules alone (no closed forms):
+    stage s runs min(p-s-1, m) warm-up forwards, then forward/backward pairs, then the
+    remaining backwards; F(s,j) needs F(s-1,j), B(s,j) needs B(s+1,j) (last stage: its own F).
+    Returns per stage the list of (start, end) busy intervals of one iteration."""
+    order = []
+    for s in range(p):
+        w = min(p - s - 1, m)
+        seq = [("F", j) for j in range(w)]
+        f, b = w, 0
+        while f < m:
+            seq.append(("F", f)); f += 1
+            seq.append(("B", b)); b += 1
+        while b < m:
+            seq.append(("B", b)); b += 1
+        order.append(seq)
+    done = {}
+    ptr = [0] * p
+    free_at = [0] * p
+    busy = [[] for _ in range(p)]
+    progressed = True
+    while progressed:
+        progressed = False
+        for s in range(p):
+            while ptr[s] < len(order[s]):
+                kind, j = order[s][ptr[s]]
+                if kind == "F":
+                    dep = 0 if s == 0 else done.get(("F", s - 1, j))
+                else:
+                    dep = done.get(("F", s, j)) if s == p - 1 else done.get(("B", s + 1, j))
+                if dep is None:
+                    break
+                start = max(free_at[s], dep)
+                end = start + (tf if kind == "F" else tb)
+                done[(kind, s, j)] = end
+                busy[s].append((start, end))
+                free_at[s] = end
+                ptr[s] += 1
+                progressed = True
+    assert all(ptr[s] == len(order[s]) for s in range(p))
+    return busy
+
+
+def idle_from_busy(busy, cycle_start, cycle_end):
+    out = []
+    t = cycle_start
+    for a, b in busy:
+        if a > t:
+            out.append((t, a - t))
+        t = max(t, b)
+    if cycle_end > t:
+        out.append((t, cycle_end - t))
+    return out
+
+
+@pytest.mark.parametrize("tf,tb", [(2, 4), (3, 5), (7, 7), (5, 3)])
+def test_windows_match_dependency_simulation(tf, tb):
+    for p in range(1, 9):
+        for m in range(1, 12):
+            busy = simulate_1f1b(p, m, tf, tb)
+            T = op.iteration_time(p, m, tf, tb)
+            assert max(e for s in range(p) for _, e in busy[s]) == T
+            for s in range(p):
+                want = idle_from_busy(busy[s], s * tf, T + s * tf)
+                got = [(w["start"], w["dur"]) for w in op.windows_1f1b(p, m, s, tf, tb, 1)]
+                assert got == want, (p, m, s)
+
+
+def test_idle_total_and_paper_lengths():
+    for p, m, tf, tb in itertools.product(range(1, 10), range(1, 14), (2, 15), (4, 30)):
+        for s in range(p):
+            w = op.windows_1f1b(p, m, s, tf, tb, 0)
+            assert sum(x["dur"] for x in w) == (p - 1) * (tf + tb)
+            fb = [x for x in w if x["kind"] == op.KIND_FWD_BWD]
+            fd = [x for x in w if x["kind"] == op.KIND_FILL_DRAIN]
+            # Sec. 4.5: 1F1B fwd-bwd bubble, and fill-drain identical in both schedules
+            assert sum(x["dur"] for x in fb) == (p - s - 1) * tb + max(0, p - s - m) * tf
+            assert sum(x["dur"] for x in fd) == s * (tf + tb)
+            g = op.windows_gpipe(p, m, s, tf, tb, 0)
+            assert sum(x["dur"] for x in g) == (p - 1) * (tf + tb)        # same total in both schedules
+            gfb = [x for x in g if x["kind"] == op.KIND_FWD_BWD]
+            assert sum(x["dur"] for x in gfb) == (p - s - 1) * (tf + tb)
+            assert [x["dur"] for x in g if x["kind"] == op.KIND_FILL_DRAIN] == [x["dur"] for x in fd]
+            # windows are ordered, disjoint and inside the stage's cycle
+            T = op.iteration_time(p, m, tf, tb)
+            t = s * tf
+            for x in w:
+                assert x["start"] >= t and x["dur"] > 0
+                t = x["start"] + x["dur"]
+            assert t <= T + s * tf
+
+
+def test_bubble_ratios_printed_in_the_paper():
+    # Sec. 6.1: 16 stages, 8 microbatches -> "65%"; Sec. 6.3: 78.9% (m=4) and 18.9% (m=64)
+    def ratio(p, m, tf=3, tb=7):
+        idle = sum(x["dur"] for x in op.windows_1f1b(p, m, 5, tf, tb, 0))
+        return Fraction(idle, op.iteration_time(p, m, tf, tb))
+    assert ratio(16, 8) == Fraction(15, 23) and round(float(ratio(16, 8)) * 100) == 65
+    assert ratio(16, 4) == Fraction(15, 19) and abs(float(ratio(16, 4)) * 100 - 78.9) < 0.06
+    assert ratio(16, 64) == Fraction(15, 79) and abs(float(ratio(16, 64)) * 100 - 18.9) < 0.1
+
+
+def test_hand_worked_windows_cfg1():
+    rows = []
+    with open(os.path.join(HERE, "golden", "windows_cfg1.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            rows.append(tuple(int(x) for x in line.split()))
+    p, m, tf, tb, free = synth.SCHEDULES["cfg1"]
+    got = []
+    for s in range(p):
+        for w in op.windows_1f1b(p, m, s, tf, tb, free):
+            got.append((s, w["start"] // 1_000_000, (w["start"] + w["dur"]) // 1_000_000, w["kind"]))
+            assert w["free"] == free
+    assert got == rows
+
+
+def test_gap_fillable_flags():
+    w = op.windows_1f1b(4, 8, 0, 2, 4, 1, fill_gaps=False)
+    assert [x["fillable"] for x in w] == [1, 0, 0, 0]
+    w = op.windows_1f1b(4, 8, 0, 2, 4, 1, fill_gaps=True, min_window=3)
+    assert [x["fillable"] for x in w] == [1, 0, 0, 0]
+    w = op.windows_1f1b(4, 8, 0, 2, 4, 1, fill_gaps=True, min_window=2)
+    assert [x["fillable"] for x in w] == [1, 1, 1, 1]
+
+
+# ---------------------------------------------------------------- Algorithm 1
+def mk_bubbles(B, M, fillable=None):
+    return [dict(start=0, dur=b, free=mm, kind=3, fillable=1 if fillable is None else fillable[i])
+            for i, (b, mm) in enumerate(zip(B, M))]
+
+
+def min_partitions_bruteforce(Fp, B, M, first=0):
+    """Fewest partitions (empty ones allowed) over ALL in-order contiguous splittings of Fp
+    in which partition i obeys the tests of Algorithm 1 against bubble (first+i) mod len(B)."""
+    n, nb = len(Fp), len(B)
+    limit = n * nb + nb + 1
+    frontier = {0}
+    for used in range(1, limit + 1):
+        i = (first + used - 1) % nb
+        nxt = set()
+        for pos in frontier:
+            nxt.add(pos)                                   # an empty partition
+            dur, q = 0, pos
+            while q < n and dur + Fp[q][0] < B[i] and Fp[q][1] <= M[i]:
+                dur += Fp[q][0]
+                q += 1
+                nxt.add(q)
+        if n in nxt:
+            return used
+        frontier = nxt
+    return None
+
+
+def test_algorithm1_invariants_and_minimum_bubbles():
+    rng = np.random.default_rng(5)
+    n_infeasible = 0
+    for trial in range(400):
+        nb = int(rng.integers(1, 5))
+        nf = int(rng.integers(1, 7))
+        B, M, F = synth.make_planner_instance(1000 + trial, nf, nb, max_dur=30, max_mem=10)
+        B = [max(1, b // 3) for b in B]
+        first = int(rng.integers(0, nb))
+        bubbles = mk_bubbles(B, M)
+        dur_F = sum(d for d, _ in F)
+        # closed form of the replication loop: largest k with k*dur(F) < sum(B), at least 1
+        k_closed = max(1, (sum(B) - 1) // dur_F)
+        try:
+            chunks, k = op.partition_fill_job(bubbles, F, first_bubble=first)
+        except op.Infeasible as e:
+            n_infeasible += 1
+            d, mm = F[e.node]
+            assert all(not (d < b and mm <= m_) for b, m_ in zip(B, M))
+            assert min_partitions_bruteforce(F * k_closed, B, M, first) is None
+            continue
+        assert k == k_closed
+        Fp = F * k
+        # concatenation of the partitions is F' in order
+        pos = 0
+        for i, ch in enumerate(chunks):
+            assert ch["node_begin"] == pos and ch["node_end"] >= pos
+            pos = ch["node_end"]
+            bi = (first + i) % nb
+            assert ch["bubble"] == bi and ch["cycle"] == (first + i) // nb
+            seg = Fp[ch["node_begin"]:ch["node_end"]]
+            assert ch["dur"] == sum(d for d, _ in seg)
+            assert ch["mem"] == max([mm for _, mm in seg], default=0)
+            # output contract of Algorithm 1
+            assert ch["dur"] <= B[bi] and ch["mem"] <= M[bi]
+            # maximality: the next node fails one of the two tests
+            if ch["node_end"] < len(Fp):
+                d, mm = Fp[ch["node_end"]]
+                assert not (ch["dur"] + d < B[bi] and mm <= M[bi])
+        assert pos == len(Fp)
+        assert len(chunks[-1:]) == 1 and chunks[-1]["node_end"] > chunks[-1]["node_begin"]
+        # greedy uses the minimum number of bubbles of any in-order packing
+        assert len(chunks) == min_partitions_bruteforce(Fp, B, M, first)
+    assert 5 < n_infeasible < 300
+
+
+def test_algorithm1_strict_time_nonstrict_memory():
+    # a node whose duration EQUALS the bubble does not fit (strict <); memory equal fits (<=)
+    with pytest.raises(op.Infeasible):
+        op.partition_fill_job(mk_bubbles([10], [5]), [(10, 5)])
+    chunks, k = op.partition_fill_job(mk_bubbles([11], [5]), [(10, 5)])
+    assert k == 1 and [(c["node_begin"], c["node_end"]) for c in chunks] == [(0, 1)]
+    with pytest.raises(op.Infeasible):
+        op.partition_fill_job(mk_bubbles([11], [4]), [(10, 5)])
+
+
+def test_algorithm1_small_worked_example():
+    # B = [10, 4], F = [3, 3, 3]: sum B = 14, dur F = 9 -> 9+9 < 14 false -> one replica.
+    # bubble 0: 3, 3+3=6, 6+3=9 < 10 -> all three nodes; done.
+    chunks, k = op.partition_fill_job(mk_bubbles([10, 4], [1, 1]), [(3, 1)] * 3)
+    assert k == 1 and [(c["bubble"], c["node_begin"], c["node_end"]) for c in chunks] == [(0, 0, 3)]
+    # B = [7, 4, 30]: sum 41 -> replicas: 9+9<41, 18+9<41, 27+9<41, 36+9<41 false -> 4 replicas
+    # (12 nodes). b0: 3,6 (9<7 fails) -> [0,2); b1: 3 (6<4 fails) -> [2,3); b2: 9 nodes=27<30 -> [3,12)
+    chunks, k = op.partition_fill_job(mk_bubbles([7, 4, 30], [1, 1, 1]), [(3, 1)] * 3)
+    assert k == 4
+    assert [(c["bubble"], c["cycle"], c["node_begin"], c["node_end"]) for c in chunks] == \
+        [(0, 0, 0, 2), (1, 0, 2, 3), (2, 0, 3, 12)]
+    # memory: the middle node needs 5, only bubble 1 has it.  sum B = 10, dur F = 3 -> 3 replicas
+    # (9 nodes).  b0: node 0, then node 1 fails on memory -> [0,1); b1: nodes 1..4 (4 < 5, 5 !< 5)
+    # -> [1,5); b0 again: nodes 5, 6, node 7 fails on memory -> [5,7); b1: [7,9)
+    chunks, k = op.partition_fill_job(mk_bubbles([5, 5], [1, 5]), [(1, 1), (1, 5), (1, 1)])
+    assert k == 3
+    assert [(c["bubble"], c["cycle"], c["node_begin"], c["node_end"]) for c in chunks] == \
+        [(0, 0, 0, 1), (1, 0, 1, 5), (0, 1, 5, 7), (1, 1, 7, 9)]
+    assert [c["mem"] for c in chunks] == [1, 5, 1, 5]
+
+
+def test_fill_fraction_and_switch_cost_and_unfillable():
+    b = mk_bubbles([1000, 50, 1000], [1, 1, 1], fillable=[1, 0, 1])
+    assert op.effective_durations(b, 680_000, 10) == [670, 24, 670]
+    chunks, k = op.partition_fill_job(b, [(100, 1)] * 3, fill_ppm=680_000, switch_ns=10)
+    # sum of effective fillable = 1340; 300k+300 < 1340 -> k = 4 (1200+300 !< 1340)
+    assert k == 4
+    # bubble 0: 6 nodes (600 < 670, 700 !< 670); bubble index 1 is skipped entirely
+    assert [(c["bubble"], c["cycle"], c["node_begin"], c["node_end"]) for c in chunks] == \
+        [(0, 0, 0, 6), (2, 0, 6, 12)]
+    chunks, k = op.partition_fill_job(b, [(100, 1)] * 3, fill_ppm=680_000, switch_ns=10, first_bubble=1)
+    assert [(c["bubble"], c["cycle"], c["node_begin"], c["node_end"]) for c in chunks] == \
+        [(2, 0, 0, 6), (0, 1, 6, 12)]
+
+
+def test_choose_configuration_against_fractions():
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        nb = int(rng.integers(1, 4))
+        B, M, _ = synth.make_planner_instance(5000 + trial, 1, nb, max_dur=40, max_mem=10)
+        bubbles = mk_bubbles(B, M)
+        configs = []
+        for c in range(int(rng.integers(1, 5))):
+            _, _, F = synth.make_planner_instance(7000 + 10 * trial + c, int(rng.integers(1, 6)), 1, 25, 10)
+            configs.append(dict(F=F, samples=int(rng.integers(1, 9))))
+        best, plans = op.choose_configuration(bubbles, configs)
+        scored = []
+        for c, pl in enumerate(plans):
+            if pl is None:
+                with pytest.raises(op.Infeasible):
+                    op.partition_fill_job(bubbles, configs[c]["F"])
+                continue
+            chunks, k, cyc = pl
+            assert cyc == -(-len(chunks) // nb)
+            thr = Fraction(configs[c]["samples"] * k, cyc)
+            scored.append((-thr, max(ch["mem"] for ch in chunks), c))
+        if not scored:
+            assert best == -1
+        else:
+            assert best == min(scored)[2]
+
+
+def test_chain_nodes_shape():
+    s = synth.WORKLOADS["cfg2"]
+    nodes = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2,
+                           g=1, streamed=False, n_slots=0, training=False)
+    assert len(nodes) == 14 and [n[0] for n in nodes] == [0] + [1] * 12 + [2]
+    assert op.layer_param_count(768, 3072) == 7087872       # one BERT-base-shaped layer
+    s = synth.WORKLOADS["cfg4"]
+    nodes = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2,
+                           g=1, streamed=False, n_slots=0, training=True)
+    assert len(nodes) == 1 + 12 + 1 + 1 + 12 + 1
+    assert [n[1] for n in nodes if n[0] == op.OP_LAYER_BWD] == list(range(11, -1, -1))
