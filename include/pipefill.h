@@ -1,0 +1,307 @@
+/*
+ * pipefill.h -- C ABI of the MI355X (gfx950) fill-job Executor library.
+ *
+ * The library implements the bubble-bounded work of a fill-job Executor (Sec. 4.3 of the
+ * PipeFill paper, arXiv 2410.07192): deriving the idle windows of a pipeline stage, partitioning
+ * a fill job's linearised graph onto the bubble cycle (Algorithm 1), and executing one partition
+ * ("chunk") of transformer-layer work per bubble with hand-written HIP kernels, optionally with
+ * layer weights streamed from pinned host memory.  One emulated main-job stage provides the
+ * bubbles (Sec. 4.2, the pipeline bubble instruction).
+ *
+ * Conventions
+ *   - every call returns int32_t: PF_OK (0) or a negative PF_ERR_* code; nothing throws or aborts
+ *     across this boundary; pf_last_error() returns a thread-local message for the last failure.
+ *   - all times are int64 nanoseconds, all sizes int64 bytes, fractions are parts per million.
+ *   - "host" / "device" in a parameter comment says where the pointed-to memory must live.
+ *   - the caller owns every buffer it passes in; the library owns only what pf_ctx_create
+ *     carves out of the caller's arena plus the streams/events it creates, released by
+ *     pf_ctx_destroy.
+ *   - streams are hipStream_t values passed as void* (NULL = the null stream).  Calls that take
+ *     a stream enqueue work and return; only pf_ctx_sync, pf_profile_chain and pf_timeline_run
+ *     wait for the device.
+ *   - a missing or failing GPU is an error (PF_ERR_HIP); there is no CPU fallback.
+ */
+#ifndef PIPEFILL_H
+#define PIPEFILL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  PF_OK = 0,
+  PF_ERR_ARG = -1,        /* null pointer, negative size, value out of range                     */
+  PF_ERR_CAPACITY = -2,   /* output array too small; the needed count is written to *n_out       */
+  PF_ERR_INFEASIBLE = -3, /* some graph node fits no bubble of the cycle                         */
+  PF_ERR_NOMEM = -4,      /* arena too small / chunk exceeds the bubble's memory cap             */
+  PF_ERR_HIP = -5,        /* a HIP runtime call failed (message in pf_last_error)                */
+  PF_ERR_STATE = -6       /* call not valid in the context's current state                       */
+};
+
+/* kinds of idle window of one pipeline stage (Sec. 4.5, "Main job pipeline schedule") */
+enum { PF_BUBBLE_FWD_BWD = 0, PF_BUBBLE_GAP = 1, PF_BUBBLE_FILL_DRAIN = 2, PF_BUBBLE_EXPLICIT = 3 };
+
+/* graph-node operations of a transformer fill job */
+enum { PF_OP_EMBED = 0, PF_OP_LAYER_FWD = 1, PF_OP_FINAL_LN = 2, PF_OP_HEAD_LOSS = 3,
+       PF_OP_LAYER_BWD = 4, PF_OP_OPT = 5 };
+
+enum { PF_DTYPE_F32 = 0, PF_DTYPE_BF16 = 1 };
+
+/* instructions of the emulated main-job stage (Sec. 4.2: forward / backward of a microbatch,
+ * and the pipeline bubble instruction) */
+enum { PF_INSTR_FWD = 0, PF_INSTR_BWD = 1, PF_INSTR_BUBBLE = 2 };
+
+/* One bubble of the cycle that repeats every main-job iteration (the lists B and M of
+ * Algorithm 1): start relative to the global iteration start, duration, free HBM. */
+typedef struct pf_bubble {
+  int64_t start_ns;
+  int64_t dur_ns;
+  int64_t free_bytes;
+  int32_t kind;      /* PF_BUBBLE_*                                                   */
+  int32_t fillable;  /* 0: the planner skips this window                              */
+} pf_bubble;
+
+/* One node of the linearised graph (the list F of Algorithm 1): duration and peak memory
+ * under one configuration, plus what it computes. */
+typedef struct pf_node {
+  int64_t dur_ns;
+  int64_t mem_bytes;
+  int32_t op;        /* PF_OP_*                                                       */
+  int32_t layer;     /* layer index for LAYER_FWD / LAYER_BWD, else -1                */
+  int32_t mb_first;  /* first fill microbatch of the visit                            */
+  int32_t mb_count;  /* microbatches processed by this node (g per layer visit)       */
+} pf_node;
+
+/* One partition P[i] of Algorithm 1: nodes [node_begin, node_end) of the replicated chain
+ * (node j is F[j mod nF] of replica j div nF) run in bubble `bubble` of cycle `cycle`. */
+typedef struct pf_chunk {
+  int32_t bubble;
+  int32_t cycle;
+  int32_t node_begin;
+  int32_t node_end;
+  int64_t dur_ns;    /* sum of node durations                                         */
+  int64_t mem_bytes; /* max of node memory requirements                               */
+} pf_chunk;
+
+typedef struct pf_model_desc {
+  int32_t n_layers, d_model, n_heads, d_ff, seq_len;
+  int32_t batch;     /* sequences per fill microbatch                                 */
+  int32_t vocab;     /* 0: hidden states are the input, no embedding / head           */
+  int32_t causal;    /* 1: key j > query i is masked                                  */
+  int32_t dtype;     /* PF_DTYPE_*: storage type of weights and activations           */
+  float eps;         /* LayerNorm epsilon                                             */
+} pf_model_desc;
+
+/* One execution configuration of a job (Sec. 4.3: batch size x execution technique). */
+typedef struct pf_exec_config {
+  int32_t g;         /* microbatches per layer visit (>= 1)                           */
+  int32_t streamed;  /* 1: layer weights live in pinned host memory                   */
+  int32_t n_slots;   /* HBM weight slots when streamed (>= 2)                         */
+  int32_t training;  /* 1: forward + recompute/backward + Adam                        */
+} pf_exec_config;
+
+/* Where the model's parameters live.  A layer is one packed blob (see pf_layer_blob_layout).
+ * layers[l]: device pointer when the configuration is resident, pinned host pointer when it is
+ * streamed.  tok_emb [vocab,d], pos_emb [seq,d], lnf_g [d], lnf_b [d]: device, model dtype;
+ * the embeddings may be NULL when vocab == 0. */
+typedef struct pf_weights {
+  void* const* layers;   /* host array of n_layers pointers */
+  void* tok_emb;
+  void* pos_emb;
+  void* lnf_g;
+  void* lnf_b;
+} pf_weights;
+
+/* Adam constants for training fill jobs (the optimizer the paper names, Sec. 5). */
+typedef struct pf_adam {
+  float lr, beta1, beta2, eps;
+  int32_t accum;     /* microbatches accumulated per optimizer step */
+} pf_adam;
+
+typedef struct pf_ctx pf_ctx;
+
+/* ---- diagnostics ------------------------------------------------------------------------- */
+const char* pf_last_error(void);           /* thread-local, never NULL                          */
+int32_t pf_version(void);
+
+/* ---- bubble windows (Sec. 2.1 idle fraction (p-1)/(m+p-1); Sec. 4.5 bubble lengths) -------- */
+/* Idle windows of 0-based stage `stage` in one steady-state iteration of a 1F1B schedule with p
+ * stages, m microbatches, forward/backward times tf_ns/tb_ns and zero communication time, in
+ * time order: the fwd-bwd bubble of (p-s-1)*t_b + max(0,p-s-m)*t_f, the t_f-long non-contiguous
+ * gaps before the cool-down backwards, the fill-drain bubble of s*(t_f+t_b).  Gaps get
+ * fillable=1 only if fill_gaps != 0 and they last >= min_window_ns; contiguous bubbles always.
+ * out: host array of `cap` entries; *n_out receives the count (also on PF_ERR_CAPACITY). */
+int32_t pf_schedule_1f1b(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int64_t tb_ns,
+                         int64_t free_bytes, int32_t fill_gaps, int64_t min_window_ns,
+                         pf_bubble* out, int32_t cap, int32_t* n_out);
+/* Same for GPipe: fwd-bwd bubble (p-s-1)*(t_f+t_b) and the identical fill-drain bubble. */
+int32_t pf_schedule_gpipe(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int64_t tb_ns,
+                          int64_t free_bytes, pf_bubble* out, int32_t cap, int32_t* n_out);
+
+/* ---- Algorithm 1 (Sec. 4.3): partition a fill job onto the bubble cycle ------------------- */
+/* B: host, the cycle (nB entries; entries with fillable==0 are skipped).  F: host, nF nodes.
+ * Each bubble's usable duration is floor(dur*fill_ppm/1e6) - switch_ns, not below 0 (the
+ * fill-fraction knob of Sec. 6.1).  The chain is replicated while one more copy keeps the total
+ * strictly below the summed usable duration; nodes are then packed greedily, time test strict
+ * (<), memory test <= per node, starting at the first_bubble-th fillable bubble and cycling.
+ * out: host array of `cap` chunks (empty chunks are kept: chunk i belongs to fillable bubble
+ * (first_bubble+i) mod n).  *n_out = chunk count (needed count on PF_ERR_CAPACITY);
+ * *replicas = copies of F.  PF_ERR_INFEASIBLE when a node fits no bubble: *n_out then holds
+ * the index in F of the first such node. */
+int32_t pf_plan_bubbles(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t nF,
+                        int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
+                        pf_chunk* out, int32_t cap, int32_t* n_out, int32_t* replicas);
+
+/* Configuration choice (Sec. 4.1/4.3: the plan that maximises throughput).  chains[c] (host) has
+ * n_nodes[c] nodes and processes samples[c] samples per replica.  Every configuration is
+ * planned as above; the winner maximises samples*replicas / ceil(chunks / fillable bubbles),
+ * compared exactly in 128-bit integers; ties go to the smaller peak memory, then the lower
+ * index.  Infeasible configurations are skipped.  *best = -1 with PF_ERR_INFEASIBLE when none
+ * is feasible.  replicas_out / cycles_out / chunks_out (host, n_cfg entries each, may be NULL)
+ * receive per-configuration results (0 for infeasible ones). */
+int32_t pf_select_config(const pf_bubble* B, int32_t nB, const pf_node* const* chains,
+                         const int32_t* n_nodes, const int64_t* samples, int32_t n_cfg,
+                         int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
+                         int32_t* best, int32_t* replicas_out, int32_t* cycles_out,
+                         int32_t* chunks_out);
+
+/* ---- job description -> chain of nodes (Sec. 4.3 "linearizes the computational graph") ---- */
+/* Writes the node list of one replica (g microbatches): [EMBED] L x LAYER_FWD FINAL_LN, and for
+ * training HEAD_LOSS, L x LAYER_BWD (last layer first), OPT.  mem_bytes is the node's peak HBM
+ * footprint including everything kept resident between bubbles; dur_ns is left 0 (fill it with
+ * pf_profile_chain or by hand).  out: host, cap entries. */
+int32_t pf_build_chain(const pf_model_desc* model, const pf_exec_config* cfg,
+                       pf_node* out, int32_t cap, int32_t* n_out);
+
+/* ---- packed layer weights -------------------------------------------------------------------
+ * A layer blob holds, in model dtype, at 256-byte aligned offsets, in this order:
+ *   0 ln1_g[d] 1 ln1_b[d] 2 w_qkv[3d][d] 3 b_qkv[3d] 4 w_o[d][d] 5 b_o[d]
+ *   6 ln2_g[d] 7 ln2_b[d] 8 w_1[f][d] 9 b_1[f] 10 w_2[d][f] 11 b_2[d]
+ * Matrices are [out_features][in_features], row-major (y = x W^T + b).  Rows 0..d-1 of w_qkv
+ * produce Q, d..2d-1 K, 2d..3d-1 V; head i owns rows i*d_head..(i+1)*d_head of each block.
+ * offsets: host array of 12 entries.  Returns the blob size in bytes (<0: error code). */
+int64_t pf_layer_blob_layout(const pf_model_desc* model, int64_t* offsets);
+
+/* ---- execution context --------------------------------------------------------------------- */
+/* Bytes of arena pf_ctx_create needs for this model and configuration (<0: error code). */
+int64_t pf_ctx_arena_bytes(const pf_model_desc* model, const pf_exec_config* cfg);
+/* arena: device memory, 256-byte aligned, arena_bytes long, owned by the caller and kept alive
+ * until pf_ctx_destroy.  PF_ERR_NOMEM if it is too small.  adam may be NULL for inference. */
+int32_t pf_ctx_create(const pf_model_desc* model, const pf_exec_config* cfg, const pf_weights* w,
+                      const pf_adam* adam, void* arena, int64_t arena_bytes, pf_ctx** out);
+int32_t pf_ctx_destroy(pf_ctx* ctx);
+/* Waits for all work the context has enqueued (fill, copy and main streams it has seen). */
+int32_t pf_ctx_sync(pf_ctx* ctx);
+/* Rings of job inputs and outputs (device).  Replica r of the chain reads input slot r mod n_in
+ * (int32 token ids [g][batch][seq] when vocab > 0, else hidden states [g][batch][seq][d] in
+ * model dtype) and writes its final hidden states [g][batch][seq][d] to output slot r mod n_out.
+ * For training jobs `out` may be NULL. */
+int32_t pf_ctx_set_io(pf_ctx* ctx, const void* in, int32_t n_in, void* out, int32_t n_out);
+
+/* Host->HBM prefetch of one layer blob (Sec. 4.5: parameters offloaded to CPU memory).  Enqueues
+ * on copy_stream: wait until the last kernels that read `slot` have finished, copy layer
+ * `layer` from pinned host memory into the slot, record the slot's ready event.  A later
+ * LAYER_FWD of that layer on the fill stream waits for the event.  PF_ERR_STATE if the
+ * configuration is not streamed. */
+int32_t pf_load_layer_async(pf_ctx* ctx, int32_t layer, int32_t slot, void* copy_stream);
+
+/* Run one chunk's forward-type nodes (EMBED, LAYER_FWD, FINAL_LN, HEAD_LOSS) on fill_stream
+ * (Sec. 4.3: "execute the current graph partition on the current bubble").  F/nF: the chain the
+ * plan was made from (host).  The hidden states cut by the end of the chunk stay in the
+ * context until the next chunk (inter-bubble context).  act_in (device, may be NULL): overrides
+ * the source of the chunk's first node (token ids for EMBED, else hidden states
+ * [g][batch][seq][d]).  act_out (device, may be NULL): receives a copy of the hidden states
+ * after the chunk's last node.  PF_ERR_NOMEM, before any launch, if chunk->mem_bytes exceeds
+ * cap_bytes (the bubble's free memory; <= 0 disables the check); PF_ERR_STATE if the chunk holds
+ * a backward-type node. */
+int32_t pf_fill_chunk_fwd(pf_ctx* ctx, const pf_chunk* chunk, const pf_node* F, int32_t nF,
+                          const void* act_in, void* act_out, int64_t cap_bytes, void* fill_stream);
+/* Same for backward-type nodes (LAYER_BWD with recompute from the layer's checkpoint, OPT).
+ * grad_io (device, may be NULL): overrides the upstream gradient [g][batch][seq][d] entering the
+ * chunk's first node; after the call it is not modified.  grad_out (device, may be NULL)
+ * receives a copy of the gradient leaving the chunk's last LAYER_BWD node. */
+int32_t pf_fill_chunk_bwd(pf_ctx* ctx, const pf_chunk* chunk, const pf_node* F, int32_t nF,
+                          const void* grad_io, void* grad_out, int64_t cap_bytes, void* fill_stream);
+/* Convenience: run any chunk, dispatching each node to the forward or backward path. */
+int32_t pf_fill_chunk(pf_ctx* ctx, const pf_chunk* chunk, const pf_node* F, int32_t nF,
+                      int64_t cap_bytes, void* fill_stream);
+
+/* Measure dur_ns of every node of F (host, in/out) on this device: each node is run `reps`
+ * times after `warmup` runs on `stream` and the median HIP-event time is stored (the
+ * per-node profiles the Executor is handed, Sec. 4.3).  Synchronises the device. */
+int32_t pf_profile_chain(pf_ctx* ctx, pf_node* F, int32_t nF, int32_t warmup, int32_t reps,
+                         void* stream);
+
+/* Emulated main-job stage (Sec. 4.2).  ctx must be a training context with vocab == 0 whose
+ * layers are the stage's layers.  PF_INSTR_FWD: forward of microbatch `index` through all
+ * layers, keeping per-layer checkpoints; PF_INSTR_BWD: recompute + backward of microbatch
+ * `index`, accumulating weight gradients.  `io`: device hidden states [batch][seq][d] (input
+ * for FWD; upstream gradient for BWD).  Enqueues on main_stream and returns.
+ * PF_INSTR_BUBBLE is handled by pf_timeline_run and is rejected here with PF_ERR_ARG. */
+int32_t pf_main_stage_step(pf_ctx* ctx, int32_t instr, int32_t index, const void* io,
+                           void* main_stream);
+
+/* Result of one emulated main-job iteration. */
+typedef struct pf_timeline_stats {
+  int64_t iter_ns;          /* wall time of the iteration                                        */
+  int64_t offered_ns;       /* sum of the durations of the fillable bubbles visited              */
+  int64_t idle_ns;          /* sum of all idle windows (fillable or not)                         */
+  int64_t fill_busy_ns;     /* fill-stream busy time inside the bubbles (HIP events)             */
+  int64_t overrun_ns;       /* fill work still running after its bubble's deadline, summed       */
+  int64_t main_busy_ns;     /* main-stream busy time (0 when the main stage is a placeholder)    */
+  int32_t chunks_run;       /* non-empty chunks executed                                         */
+  int32_t replicas_done;    /* replicas of the chain completed in this iteration                 */
+} pf_timeline_stats;
+
+/* One iteration of an emulated 1F1B stage with the Executor's bubble loop inside it
+ * (Sec. 4.2 signalling, Sec. 4.3 "Bubble synchronization and memory capping").
+ * windows/nW: the stage's idle windows in time order (from pf_schedule_1f1b).  The stage's busy
+ * periods between windows are real kernels when main_ctx != NULL (FWD/BWD of `main_io`,
+ * issued in 1F1B order for p, m, stage) and timed waits of tf_ns / tb_ns otherwise.  At each fillable window the
+ * next planned chunk plan[*cursor] whose bubble index equals the window is launched on
+ * fill_stream with the window's free_bytes as cap, and the window is held open on the host for
+ * its dur_ns.  fill_ctx may be NULL (no filling: the baseline for slowdown).  *cursor (host,
+ * in/out) advances over plan[0..n_plan); when it reaches n_plan it wraps to 0 (the plan is
+ * cyclic: the same chunks serve new replicas).  Synchronises the device at the end. */
+int32_t pf_timeline_run(pf_ctx* fill_ctx, pf_ctx* main_ctx, const void* main_io,
+                        int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int64_t tb_ns,
+                        const pf_bubble* windows, int32_t nW,
+                        const pf_chunk* plan, int32_t n_plan, const pf_node* F, int32_t nF,
+                        int32_t* cursor, void* fill_stream, void* main_stream,
+                        pf_timeline_stats* stats);
+
+/* Scalar training state of a context: *loss = mean of the HEAD_LOSS values since the last call
+ * (device sync), *steps = optimizer steps taken.  Either may be NULL. */
+int32_t pf_ctx_train_state(pf_ctx* ctx, double* loss, int64_t* steps);
+
+/* Copy parameter gradients / master weights of layer `layer` (blob layout, fp32 elements at the
+ * same element order) to `dst` (device, fp32).  what: 0 accumulated gradients, 1 master weights.
+ * layer == -1: tok_emb | pos_emb | lnf_g | lnf_b concatenated.  For tests of training jobs. */
+int32_t pf_ctx_read_params(pf_ctx* ctx, int32_t what, int32_t layer, void* dst, int64_t dst_bytes,
+                           void* stream);
+
+/* ---- single kernels (the steps a layer visit is made of; used by tests and by the roofline
+ * measurement).  All pointers device; `dtype` = storage type; fp32 accumulation throughout. ------ */
+/* C[M,N] = X[M,K] * W[N,K]^T (+ bias[N]) (GELU if gelu) (+ resid[M,N]); C is fp32 if out_f32 (then
+ * accumulate != 0 adds to C's old contents), else dtype.  bf16: K must be a multiple of 8. */
+int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K,
+                   const void* bias, const void* resid, int32_t gelu, int32_t out_f32, int32_t accumulate,
+                   void* stream);
+/* y = g * (x - mean) / sqrt(var + eps) + b per row; d a multiple of 8, at most 8192.
+ * mean_out / rstd_out: fp32 [rows], may be NULL. */
+int32_t pf_op_layernorm(int32_t dtype, const void* x, const void* g, const void* b, void* y,
+                        float* mean_out, float* rstd_out, int64_t rows, int32_t d, float eps, void* stream);
+/* softmax(Q K^T / sqrt(dh) [+ causal mask]) V per (batch, head).  qkv: [B*S][3*h*dh] (Q | K | V
+ * column blocks), out: [B*S][h*dh], lse: fp32 [B][h][S] or NULL.  dh in {8,16,32,64,128}. */
+int32_t pf_op_attention(int32_t dtype, const void* qkv, void* out, float* lse, int32_t B, int32_t S,
+                        int32_t h, int32_t dh, int32_t causal, void* stream);
+/* x[t] = tok[ids[t]] + pos[t mod S]; ids int32 [tokens]; ids outside [0,V) contribute zeros. */
+int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
+                    int64_t tokens, int32_t S, int32_t d, int32_t V, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPEFILL_H */

@@ -215,37 +215,41 @@ def layer_param_count(d, f):
     return 4 * d * d + 2 * d * f + (3 * d + d + f + d) + 4 * d
 
 
+def _al256(x):
+    return -(-x // 256) * 256
+
+
+def layer_blob_bytes(d, f, esize):
+    """Packed layer: the 12 parameter arrays, each padded to a multiple of 256 bytes."""
+    sizes = (d, d, 3 * d * d, 3 * d, d * d, d, d, d, f * d, f, d * f, d)
+    return sum(_al256(n * esize) for n in sizes)
+
+
 def chain_nodes(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, n_slots, training):
     """Node list (op, layer, mb_first, mb_count, mem_bytes) of one replica = g microbatches.
 
-    mem_bytes of a node is its peak HBM footprint including everything the job
-    keeps resident between bubbles (Sec. 4.3 tests mem(F[0]) <= M[i] per node).
+    mem_bytes of a node is its peak HBM footprint including everything the job keeps resident
+    between bubbles (Sec. 4.3 tests mem(F[0]) <= M[i] per node): the weights that stay in HBM
+    (all layers, or the slots of a streamed configuration), embeddings and final LayerNorm, the
+    g hidden-state tensors carried from bubble to bubble, and for a layer visit the workspace of
+    one microbatch (LayerNorm output, fused QKV, attention output, FFN intermediate).  Every
+    buffer is padded to a multiple of 256 bytes.
     """
     tokens = batch * seq
-    act = tokens * d * esize
-    lp = layer_param_count(d, f) * esize
-    emb = (vocab * d + seq * d) * esize if vocab > 0 else 0
-    lnf = 2 * d * esize
-    weights = (n_slots if streamed else n_layers) * lp + emb + lnf
-    carried = 2 * g * act
-    ws_fwd = act * 3 + tokens * 3 * d * esize + tokens * f * esize + batch * n_heads * seq * 4
-    persistent = weights + carried
-    if training:
-        n_params = n_layers * layer_param_count(d, f) + vocab * d + seq * d + 2 * d
-        persistent += n_params * 16          # fp32 master, Adam m, v, gradient accumulator
-        persistent += n_layers * lp          # transposed weight copies for the backward GEMMs
-        persistent += n_layers * g * act     # per-layer checkpoints
+    act = _al256(tokens * d * esize)
+    blob = layer_blob_bytes(d, f, esize)
+    emb = ((vocab * d + seq * d) * esize if vocab > 0 else 0) + 2 * d * esize
+    slots = n_slots * blob if streamed else 0
+    carried = g * act
+    ws_fwd = 5 * act + _al256(tokens * f * esize)
+    resident = emb + (0 if streamed else n_layers * blob)
+    persistent = resident + slots + carried
     nodes = []
-    if vocab > 0:
-        nodes.append((OP_EMBED, -1, 0, g, persistent))
-    for l in range(n_layers):
-        nodes.append((OP_LAYER_FWD, l, 0, g, persistent + ws_fwd))
-    nodes.append((OP_FINAL_LN, -1, 0, g, persistent + act))
-    if training:
-        ws_bwd = ws_fwd + act * 4 + tokens * 3 * d * esize + tokens * f * esize * 2
-        logits = tokens * vocab * esize
-        nodes.append((OP_HEAD_LOSS, -1, 0, g, persistent + logits + 2 * act))
-        for l in reversed(range(n_layers)):
-            nodes.append((OP_LAYER_BWD, l, 0, g, persistent + ws_bwd))
-        nodes.append((OP_OPT, -1, 0, g, persistent))
-    return nodes
+    if not training:
+        if vocab > 0:
+            nodes.append((OP_EMBED, -1, 0, g, persistent))
+        for l in range(n_layers):
+            nodes.append((OP_LAYER_FWD, l, 0, g, persistent + ws_fwd))
+        nodes.append((OP_FINAL_LN, -1, 0, g, persistent))
+        return nodes
+    raise NotImplementedError("training chains")

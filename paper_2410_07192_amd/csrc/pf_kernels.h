@@ -1,0 +1,44 @@
+// Launchers of the gfx950 kernels (internal).  Every launcher enqueues on `stream` and returns the
+// launch status; none synchronises.  `dtype` is PF_DTYPE_F32 or PF_DTYPE_BF16 and names the storage
+// type of activations and weights; accumulation and statistics are always fp32.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace pf {
+
+// ---- GEMM  C[M,N] = op( X[M,K] * W[N,K]^T )  (both operands contiguous along K) -------------------
+struct GemmEpilogue {
+  const void* bias = nullptr;    // [N], model dtype: added to every row
+  const void* resid = nullptr;   // [M,N], model dtype: added after the activation
+  const void* dact_in = nullptr; // [M,N], model dtype: result multiplied by gelu'(dact_in)
+  void* preact_out = nullptr;    // [M,N], model dtype: receives acc + bias before the activation
+  int32_t gelu = 0;              // apply exact GELU after the bias
+  int32_t accumulate = 0;        // fp32 output only: C += result
+  int32_t out_f32 = 0;           // C is fp32 regardless of the model dtype
+  float scale = 1.0f;            // result multiplied by this first
+};
+hipError_t gemm_nt(int32_t dtype, const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K,
+                   const GemmEpilogue& ep, hipStream_t stream);
+
+// ---- LayerNorm ------------------------------------------------------------------------------------
+// y = g * (x - mean) / sqrt(var + eps) + b per row of d elements.  mean_out / rstd_out (fp32 [rows])
+// may be null.
+hipError_t layernorm_fwd(int32_t dtype, const void* x, const void* g, const void* b, void* y,
+                         float* mean_out, float* rstd_out, int64_t rows, int32_t d, float eps,
+                         hipStream_t stream);
+
+// ---- attention ------------------------------------------------------------------------------------
+// qkv: [B*S, 3*d] rows = tokens, columns = Q | K | V blocks, head i at columns i*dh.. of each block.
+// out: [B*S, d].  lse (fp32 [B, h, S], may be null) receives log-sum-exp of the scaled scores.
+hipError_t attention_fwd(int32_t dtype, const void* qkv, void* out, float* lse, int32_t B, int32_t S,
+                         int32_t h, int32_t dh, int32_t causal, hipStream_t stream);
+
+// ---- embedding ------------------------------------------------------------------------------------
+// x[t] = tok[ids[t]] + pos[t mod S];  ids outside [0, V) produce rows of zeros plus the position.
+hipError_t embed_fwd(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
+                     int64_t tokens, int32_t S, int32_t d, int32_t V, hipStream_t stream);
+
+}  // namespace pf

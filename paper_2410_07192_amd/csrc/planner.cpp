@@ -1,0 +1,239 @@
+// Bubble planner: idle windows of a pipeline stage, Algorithm 1 packing, configuration choice,
+// and the node chain of a transformer fill job.  Host-only, integer-only (int64 ns / bytes /
+// ppm, 128-bit cross products), so results are reproducible bit for bit.
+#include "pf_internal.h"
+
+#include <vector>
+
+namespace {
+
+// usable duration of a bubble: floor(dur * ppm / 1e6) - switch, clamped at 0 (Sec. 6.1 knob)
+inline int64_t usable_ns(int64_t dur, int64_t ppm, int64_t sw) {
+  __int128 e = (__int128)dur * ppm / 1000000;
+  e -= sw;
+  return e > 0 ? (int64_t)e : 0;
+}
+
+struct PlanResult {
+  int32_t rc = PF_OK;
+  int32_t replicas = 0;
+  int64_t n_chunks = 0;     // total chunks the plan has (may exceed what was stored)
+  int64_t peak_mem = 0;
+  int32_t bad_node = -1;
+};
+
+// Algorithm 1 (Sec. 4.3).  The replicated chain is never materialised: node j of it is
+// F[j % nF].  Chunks beyond `cap` are counted but not stored.
+PlanResult plan_impl(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t nF, int64_t ppm,
+                     int64_t sw, int32_t first, pf_chunk* out, int64_t cap) {
+  PlanResult r;
+  std::vector<int32_t> idx;
+  std::vector<int64_t> dur, mem;
+  for (int32_t i = 0; i < nB; ++i)
+    if (B[i].fillable) {
+      idx.push_back(i);
+      dur.push_back(usable_ns(B[i].dur_ns, ppm, sw));
+      mem.push_back(B[i].free_bytes);
+    }
+  const int32_t n = (int32_t)idx.size();
+  if (n == 0 || first < 0 || first >= n) {
+    r.rc = PF_ERR_ARG;
+    return r;
+  }
+  __int128 total = 0, chain = 0;
+  for (int64_t d : dur) total += d;
+  for (int32_t j = 0; j < nF; ++j) chain += F[j].dur_ns;
+  // replication loop of the listing: F' grows while dur(F') + dur(F) < sum(B)
+  int64_t k = 1;
+  if (chain > 0) {
+    while ((__int128)k * chain + chain < total) {
+      ++k;
+      if (k > (int64_t)1 << 24) { r.rc = PF_ERR_ARG; return r; }
+    }
+  }
+  if (k * (int64_t)nF > (int64_t)0x7fffffff) { r.rc = PF_ERR_ARG; return r; }
+  r.replicas = (int32_t)k;
+  const int64_t n_nodes = k * nF;
+
+  int64_t pos = 0, slot = first;
+  int32_t b = first, empty_run = 0;
+  while (pos < n_nodes) {
+    const int64_t begin = pos;
+    int64_t cd = 0, cm = 0;
+    while (pos < n_nodes) {
+      const pf_node& nd = F[pos % nF];
+      if (!(cd + nd.dur_ns < dur[b] && nd.mem_bytes <= mem[b])) break;
+      cd += nd.dur_ns;
+      if (nd.mem_bytes > cm) cm = nd.mem_bytes;
+      ++pos;
+    }
+    if (r.n_chunks < cap && out) {
+      pf_chunk& c = out[r.n_chunks];
+      c.bubble = idx[b];
+      c.cycle = (int32_t)(slot / n);
+      c.node_begin = (int32_t)begin;
+      c.node_end = (int32_t)pos;
+      c.dur_ns = cd;
+      c.mem_bytes = cm;
+    }
+    ++r.n_chunks;
+    if (cm > r.peak_mem) r.peak_mem = cm;
+    if (pos == begin) {
+      if (++empty_run >= n) {          // a whole cycle took nothing: this node fits nowhere
+        r.rc = PF_ERR_INFEASIBLE;
+        r.bad_node = (int32_t)(pos % nF);
+        return r;
+      }
+    } else {
+      empty_run = 0;
+    }
+    b = (b + 1 == n) ? 0 : b + 1;
+    ++slot;
+  }
+  return r;
+}
+
+bool bad_bubbles(const pf_bubble* B, int32_t nB) {
+  if (!B || nB <= 0) return true;
+  for (int32_t i = 0; i < nB; ++i)
+    if (B[i].dur_ns < 0 || B[i].free_bytes < 0) return true;
+  return false;
+}
+
+bool bad_nodes(const pf_node* F, int32_t nF) {
+  if (!F || nF <= 0) return true;
+  for (int32_t i = 0; i < nF; ++i)
+    if (F[i].dur_ns < 0 || F[i].mem_bytes < 0) return true;
+  return false;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t pf_schedule_1f1b(int32_t p, int32_t m, int32_t s, int64_t tf, int64_t tb, int64_t free_bytes,
+                         int32_t fill_gaps, int64_t min_window, pf_bubble* out, int32_t cap,
+                         int32_t* n_out) {
+  if (p < 1 || m < 1 || s < 0 || s >= p || tf < 0 || tb < 0 || free_bytes < 0 || cap < 0 || !n_out ||
+      (cap > 0 && !out))
+    return pf::fail(PF_ERR_ARG, "pf_schedule_1f1b: bad argument");
+  // Times follow from the dependency rules with zero communication: backward j of stage s
+  // starts at p*tf + (p-1-s)*tb + j*(tf+tb); stage s issues min(p-s, m) forwards first.
+  const int64_t period = tf + tb;
+  const int64_t T = (int64_t)(m + p - 1) * period;
+  const int32_t warm = (p - s - 1 < m) ? p - s - 1 : m;
+  const int64_t b0 = (int64_t)p * tf + (int64_t)(p - 1 - s) * tb;
+  int32_t n = 0;
+  auto put = [&](int64_t a, int64_t e, int32_t kind) {
+    if (e <= a) return;
+    if (n < cap) {
+      pf_bubble& w = out[n];
+      w.start_ns = a;
+      w.dur_ns = e - a;
+      w.free_bytes = free_bytes;
+      w.kind = kind;
+      w.fillable = (kind != PF_BUBBLE_GAP) ? 1 : ((fill_gaps && e - a >= min_window) ? 1 : 0);
+    }
+    ++n;
+  };
+  const int32_t n_fwd_first = (p - s < m) ? p - s : m;
+  put((int64_t)(s + n_fwd_first) * tf, b0, PF_BUBBLE_FWD_BWD);
+  // the last `warm` backwards (all but the first when warm == m) have no forward before them
+  for (int32_t j = (warm < m ? m - warm : 1); j < m; ++j) {
+    const int64_t prev_end = b0 + (int64_t)(j - 1) * period + tb;
+    put(prev_end, prev_end + tf, PF_BUBBLE_GAP);
+  }
+  put(b0 + (int64_t)(m - 1) * period + tb, T + (int64_t)s * tf, PF_BUBBLE_FILL_DRAIN);
+  *n_out = n;
+  if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_schedule_1f1b: %d windows, capacity %d", n, cap);
+  return PF_OK;
+}
+
+int32_t pf_schedule_gpipe(int32_t p, int32_t m, int32_t s, int64_t tf, int64_t tb, int64_t free_bytes,
+                          pf_bubble* out, int32_t cap, int32_t* n_out) {
+  if (p < 1 || m < 1 || s < 0 || s >= p || tf < 0 || tb < 0 || free_bytes < 0 || cap < 0 || !n_out ||
+      (cap > 0 && !out))
+    return pf::fail(PF_ERR_ARG, "pf_schedule_gpipe: bad argument");
+  const int64_t period = tf + tb;
+  const int64_t T = (int64_t)(m + p - 1) * period;
+  int32_t n = 0;
+  auto put = [&](int64_t a, int64_t d, int32_t kind) {
+    if (d <= 0) return;
+    if (n < cap) out[n] = pf_bubble{a, d, free_bytes, kind, 1};
+    ++n;
+  };
+  put((int64_t)(s + m) * tf, (int64_t)(p - s - 1) * period, PF_BUBBLE_FWD_BWD);
+  put(T + (int64_t)s * tf - (int64_t)s * period, (int64_t)s * period, PF_BUBBLE_FILL_DRAIN);
+  *n_out = n;
+  if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_schedule_gpipe: %d windows, capacity %d", n, cap);
+  return PF_OK;
+}
+
+int32_t pf_plan_bubbles(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t nF, int64_t fill_ppm,
+                        int64_t switch_ns, int32_t first_bubble, pf_chunk* out, int32_t cap,
+                        int32_t* n_out, int32_t* replicas) {
+  if (bad_bubbles(B, nB) || bad_nodes(F, nF) || fill_ppm < 0 || fill_ppm > 1000000 || switch_ns < 0 ||
+      cap < 0 || !n_out || (cap > 0 && !out))
+    return pf::fail(PF_ERR_ARG, "pf_plan_bubbles: bad argument");
+  PlanResult r = plan_impl(B, nB, F, nF, fill_ppm, switch_ns, first_bubble, out, cap);
+  if (replicas) *replicas = r.replicas;
+  if (r.rc == PF_ERR_ARG) return pf::fail(PF_ERR_ARG, "pf_plan_bubbles: no fillable bubble, first_bubble out of range, or plan too large");
+  if (r.rc == PF_ERR_INFEASIBLE) {
+    *n_out = r.bad_node;
+    return pf::fail(PF_ERR_INFEASIBLE, "pf_plan_bubbles: node %d (dur %lld ns, mem %lld B) fits no bubble",
+                    r.bad_node, (long long)F[r.bad_node].dur_ns, (long long)F[r.bad_node].mem_bytes);
+  }
+  if (r.n_chunks > 0x7fffffff) return pf::fail(PF_ERR_ARG, "pf_plan_bubbles: plan too large");
+  *n_out = (int32_t)r.n_chunks;
+  if (r.n_chunks > cap)
+    return pf::fail(PF_ERR_CAPACITY, "pf_plan_bubbles: %lld chunks, capacity %d", (long long)r.n_chunks, cap);
+  return PF_OK;
+}
+
+int32_t pf_select_config(const pf_bubble* B, int32_t nB, const pf_node* const* chains, const int32_t* n_nodes,
+                         const int64_t* samples, int32_t n_cfg, int64_t fill_ppm, int64_t switch_ns,
+                         int32_t first_bubble, int32_t* best, int32_t* replicas_out, int32_t* cycles_out,
+                         int32_t* chunks_out) {
+  if (bad_bubbles(B, nB) || !chains || !n_nodes || !samples || n_cfg <= 0 || !best || fill_ppm < 0 ||
+      fill_ppm > 1000000 || switch_ns < 0)
+    return pf::fail(PF_ERR_ARG, "pf_select_config: bad argument");
+  int64_t n_fill = 0;
+  for (int32_t i = 0; i < nB; ++i) n_fill += B[i].fillable ? 1 : 0;
+  if (n_fill == 0 || first_bubble < 0 || first_bubble >= n_fill)
+    return pf::fail(PF_ERR_ARG, "pf_select_config: no fillable bubble or first_bubble out of range");
+  *best = -1;
+  __int128 best_num = 0;
+  int64_t best_cyc = 1, best_peak = 0;
+  for (int32_t c = 0; c < n_cfg; ++c) {
+    if (replicas_out) replicas_out[c] = 0;
+    if (cycles_out) cycles_out[c] = 0;
+    if (chunks_out) chunks_out[c] = 0;
+    if (bad_nodes(chains[c], n_nodes[c]) || samples[c] < 0)
+      return pf::fail(PF_ERR_ARG, "pf_select_config: bad chain %d", c);
+    PlanResult r = plan_impl(B, nB, chains[c], n_nodes[c], fill_ppm, switch_ns, first_bubble, nullptr, 0);
+    if (r.rc == PF_ERR_INFEASIBLE) continue;
+    if (r.rc != PF_OK) return pf::fail(r.rc, "pf_select_config: planning chain %d failed", c);
+    const int64_t cyc = (r.n_chunks + n_fill - 1) / n_fill;
+    if (replicas_out) replicas_out[c] = r.replicas;
+    if (cycles_out) cycles_out[c] = (int32_t)cyc;
+    if (chunks_out) chunks_out[c] = (int32_t)r.n_chunks;
+    const __int128 num = (__int128)samples[c] * r.replicas;
+    bool take = false;
+    if (*best < 0) {
+      take = true;
+    } else {
+      const __int128 lhs = num * best_cyc, rhs = best_num * cyc;   // num/cyc vs best_num/best_cyc
+      take = lhs > rhs || (lhs == rhs && r.peak_mem < best_peak);
+    }
+    if (take) {
+      *best = c;
+      best_num = num;
+      best_cyc = cyc;
+      best_peak = r.peak_mem;
+    }
+  }
+  if (*best < 0) return pf::fail(PF_ERR_INFEASIBLE, "pf_select_config: no configuration is feasible");
+  return PF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,650 @@
+// Context, chunk runner, weight prefetch, node profiling and the emulated pipeline stage.
+#include "pf_runtime.h"
+
+#include <time.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "pf_kernels.h"
+
+#define PF_HIP(expr)                                                                              \
+  do {                                                                                            \
+    hipError_t e__ = (expr);                                                                      \
+    if (e__ != hipSuccess)                                                                        \
+      return pf::fail(PF_ERR_HIP, "%s: %s (%s:%d)", #expr, hipGetErrorString(e__), __FILE__, __LINE__); \
+  } while (0)
+
+namespace pf {
+
+static thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static bool bad_model(const pf_model_desc* m) {
+  return !m || m->n_layers <= 0 || m->d_model <= 0 || m->n_heads <= 0 || m->d_ff <= 0 || m->seq_len <= 0 ||
+         m->batch <= 0 || m->vocab < 0 || m->d_model % m->n_heads != 0 || m->d_model % 8 != 0 ||
+         m->d_ff % 8 != 0 || (m->dtype != PF_DTYPE_F32 && m->dtype != PF_DTYPE_BF16) || !(m->eps >= 0.f);
+}
+
+static bool bad_cfg(const pf_exec_config* c) {
+  return !c || c->g < 1 || (c->streamed && c->n_slots < 2) || c->n_slots < 0;
+}
+
+int32_t make_layout(const pf_model_desc& md, const pf_exec_config& cfg, Layout* L) {
+  const int64_t e = esize(md.dtype), d = md.d_model, f = md.d_ff;
+  L->esz = (int32_t)e;
+  L->tokens = (int64_t)md.batch * md.seq_len;
+  L->act = align_up(L->tokens * d * e, 256);
+  const int64_t sizes[12] = {d, d, 3 * d * d, 3 * d, d * d, d, d, d, f * d, f, d * f, d};
+  int64_t o = 0;
+  for (int i = 0; i < 12; ++i) {
+    L->off[i] = o;
+    o += align_up(sizes[i] * e, 256);
+  }
+  L->blob = o;
+  L->emb = md.vocab > 0 ? ((int64_t)md.vocab * d + (int64_t)md.seq_len * d) * e : 0;
+  L->emb += 2 * d * e;
+  L->slots = cfg.streamed ? (int64_t)cfg.n_slots * L->blob : 0;
+  L->carried = (int64_t)cfg.g * L->act;
+  L->ws_fwd = L->act /*LN out*/ + 3 * L->act /*QKV*/ + L->act /*attention out*/ +
+              align_up(L->tokens * f * e, 256) /*FFN mid*/;
+  L->total = L->slots + L->carried + L->ws_fwd;
+  L->resident = L->emb + (cfg.streamed ? 0 : (int64_t)md.n_layers * L->blob);
+  return PF_OK;
+}
+
+}  // namespace pf
+
+using pf::Layout;
+
+extern "C" {
+
+const char* pf_last_error(void) { return pf::g_err; }
+int32_t pf_version(void) { return 1; }
+
+int64_t pf_layer_blob_layout(const pf_model_desc* model, int64_t* offsets) {
+  if (pf::bad_model(model)) return pf::fail(PF_ERR_ARG, "pf_layer_blob_layout: bad model");
+  Layout L;
+  pf_exec_config c{1, 0, 0, 0};
+  pf::make_layout(*model, c, &L);
+  if (offsets) std::memcpy(offsets, L.off, sizeof L.off);
+  return L.blob;
+}
+
+int64_t pf_ctx_arena_bytes(const pf_model_desc* model, const pf_exec_config* cfg) {
+  if (pf::bad_model(model) || pf::bad_cfg(cfg)) return pf::fail(PF_ERR_ARG, "pf_ctx_arena_bytes: bad argument");
+  Layout L;
+  pf::make_layout(*model, *cfg, &L);
+  return L.total;
+}
+
+int32_t pf_build_chain(const pf_model_desc* model, const pf_exec_config* cfg, pf_node* out, int32_t cap,
+                       int32_t* n_out) {
+  if (pf::bad_model(model) || pf::bad_cfg(cfg) || !n_out || cap < 0 || (cap > 0 && !out))
+    return pf::fail(PF_ERR_ARG, "pf_build_chain: bad argument");
+  if (cfg->training) return pf::fail(PF_ERR_STATE, "pf_build_chain: training chains are not available in this build");
+  Layout L;
+  pf::make_layout(*model, *cfg, &L);
+  const int64_t persistent = L.resident + L.slots + L.carried;
+  int32_t n = 0;
+  auto put = [&](int32_t op, int32_t layer, int64_t mem) {
+    if (n < cap) out[n] = pf_node{0, mem, op, layer, 0, cfg->g};
+    ++n;
+  };
+  if (model->vocab > 0) put(PF_OP_EMBED, -1, persistent);
+  for (int32_t l = 0; l < model->n_layers; ++l) put(PF_OP_LAYER_FWD, l, persistent + L.ws_fwd);
+  put(PF_OP_FINAL_LN, -1, persistent);
+  *n_out = n;
+  if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_build_chain: %d nodes, capacity %d", n, cap);
+  return PF_OK;
+}
+
+int32_t pf_ctx_create(const pf_model_desc* model, const pf_exec_config* cfg, const pf_weights* w,
+                      const pf_adam* adam, void* arena, int64_t arena_bytes, pf_ctx** out) {
+  if (pf::bad_model(model) || pf::bad_cfg(cfg) || !w || !w->layers || !arena || arena_bytes <= 0 || !out)
+    return pf::fail(PF_ERR_ARG, "pf_ctx_create: bad argument");
+  if (((uintptr_t)arena & 255) != 0) return pf::fail(PF_ERR_ARG, "pf_ctx_create: arena must be 256-byte aligned");
+  if (cfg->training) return pf::fail(PF_ERR_STATE, "pf_ctx_create: training contexts are not available in this build");
+  if (!w->lnf_g || !w->lnf_b || (model->vocab > 0 && (!w->tok_emb || !w->pos_emb)))
+    return pf::fail(PF_ERR_ARG, "pf_ctx_create: missing embedding / final LayerNorm pointers");
+  for (int32_t l = 0; l < model->n_layers; ++l)
+    if (!w->layers[l]) return pf::fail(PF_ERR_ARG, "pf_ctx_create: layer %d pointer is null", l);
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0)
+    return pf::fail(PF_ERR_HIP, "pf_ctx_create: no HIP device available (this library has no CPU path)");
+  pf_ctx* c = new (std::nothrow) pf_ctx();
+  if (!c) return pf::fail(PF_ERR_NOMEM, "pf_ctx_create: host allocation failed");
+  c->md = *model;
+  c->cfg = *cfg;
+  if (adam) c->adam = *adam;
+  pf::make_layout(*model, *cfg, &c->lay);
+  if (arena_bytes < c->lay.total) {
+    const long long need = (long long)c->lay.total;
+    delete c;
+    return pf::fail(PF_ERR_NOMEM, "pf_ctx_create: arena has %lld bytes, %lld needed", (long long)arena_bytes, need);
+  }
+  c->layers.assign(w->layers, w->layers + model->n_layers);
+  c->tok = w->tok_emb;
+  c->pos = w->pos_emb;
+  c->lnf_g = w->lnf_g;
+  c->lnf_b = w->lnf_b;
+  c->arena = (char*)arena;
+  c->arena_bytes = arena_bytes;
+  char* p = c->arena;
+  c->slots = p; p += c->lay.slots;
+  c->X = p; p += c->lay.carried;
+  c->ws_ln = p; p += c->lay.act;
+  c->ws_qkv = p; p += 3 * c->lay.act;
+  c->ws_attn = p; p += c->lay.act;
+  c->ws_mid = p;
+  hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess && cfg->streamed) {
+    c->slot_layer.assign(cfg->n_slots, -1);
+    c->slot_free_valid.assign(cfg->n_slots, 0);
+    c->slot_ready.resize(cfg->n_slots);
+    c->slot_free.resize(cfg->n_slots);
+    for (int32_t i = 0; i < cfg->n_slots && e == hipSuccess; ++i) {
+      e = hipEventCreateWithFlags(&c->slot_ready[i], hipEventDisableTiming);
+      if (e == hipSuccess) e = hipEventCreateWithFlags(&c->slot_free[i], hipEventDisableTiming);
+    }
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking);
+  }
+  if (e != hipSuccess) {
+    pf_ctx_destroy(c);
+    return pf::fail(PF_ERR_HIP, "pf_ctx_create: %s", hipGetErrorString(e));
+  }
+  *out = c;
+  return PF_OK;
+}
+
+int32_t pf_ctx_destroy(pf_ctx* c) {
+  if (!c) return PF_OK;
+  (void)hipDeviceSynchronize();
+  for (hipEvent_t ev : c->slot_ready) if (ev) (void)hipEventDestroy(ev);
+  for (hipEvent_t ev : c->slot_free) if (ev) (void)hipEventDestroy(ev);
+  if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  delete c;
+  return PF_OK;
+}
+
+int32_t pf_ctx_sync(pf_ctx* c) {
+  if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_sync: null context");
+  PF_HIP(hipDeviceSynchronize());
+  return PF_OK;
+}
+
+int32_t pf_ctx_set_io(pf_ctx* c, const void* in, int32_t n_in, void* out, int32_t n_out) {
+  if (!c || n_in < 0 || n_out < 0 || (n_in > 0 && !in) || (n_out > 0 && !out))
+    return pf::fail(PF_ERR_ARG, "pf_ctx_set_io: bad argument");
+  c->in = in;
+  c->n_in = n_in;
+  c->out = out;
+  c->n_out = n_out;
+  return PF_OK;
+}
+
+// ---- weight streaming ---------------------------------------------------------------------------
+static int32_t load_into(pf_ctx* c, int32_t layer, int32_t slot, hipStream_t cs) {
+  if (c->slot_free_valid[slot]) PF_HIP(hipStreamWaitEvent(cs, c->slot_free[slot], 0));
+  PF_HIP(hipMemcpyAsync(c->slots + (int64_t)slot * c->lay.blob, c->layers[layer], (size_t)c->lay.blob,
+                        hipMemcpyHostToDevice, cs));
+  PF_HIP(hipEventRecord(c->slot_ready[slot], cs));
+  c->slot_layer[slot] = layer;
+  return PF_OK;
+}
+
+int32_t pf_load_layer_async(pf_ctx* c, int32_t layer, int32_t slot, void* copy_stream) {
+  if (!c) return pf::fail(PF_ERR_ARG, "pf_load_layer_async: null context");
+  if (!c->cfg.streamed) return pf::fail(PF_ERR_STATE, "pf_load_layer_async: configuration keeps weights resident");
+  if (layer < 0 || layer >= c->md.n_layers || slot < 0 || slot >= c->cfg.n_slots)
+    return pf::fail(PF_ERR_ARG, "pf_load_layer_async: layer %d / slot %d out of range", layer, slot);
+  int32_t rc = load_into(c, layer, slot, copy_stream ? (hipStream_t)copy_stream : c->copy_stream);
+  if (rc == PF_OK) c->next_slot = (slot + 1) % c->cfg.n_slots;
+  return rc;
+}
+
+static int32_t find_slot(const pf_ctx* c, int32_t layer) {
+  for (int32_t i = 0; i < (int32_t)c->slot_layer.size(); ++i)
+    if (c->slot_layer[i] == layer) return i;
+  return -1;
+}
+
+// Makes `layer` available in a slot (loading it if no slot holds it), prefetches the layers that
+// follow it into the other slots, and makes `fs` wait for the layer's copy.  Returns the slot.
+static int32_t acquire_layer(pf_ctx* c, int32_t layer, hipStream_t fs, int32_t* slot_out) {
+  const int32_t ns = c->cfg.n_slots, L = c->md.n_layers;
+  int32_t s = find_slot(c, layer);
+  if (s < 0) {
+    s = c->next_slot;
+    c->next_slot = (s + 1) % ns;
+    int32_t rc = load_into(c, layer, s, c->copy_stream);
+    if (rc != PF_OK) return rc;
+  }
+  for (int32_t t = 1; t < ns && t < L; ++t) {
+    const int32_t nl = (layer + t) % L;
+    if (find_slot(c, nl) >= 0) continue;
+    int32_t ps = c->next_slot;
+    if (ps == s) ps = (ps + 1) % ns;
+    c->next_slot = (ps + 1) % ns;
+    int32_t rc = load_into(c, nl, ps, c->copy_stream);
+    if (rc != PF_OK) return rc;
+  }
+  PF_HIP(hipStreamWaitEvent(fs, c->slot_ready[s], 0));
+  *slot_out = s;
+  return PF_OK;
+}
+
+// ---- one layer, one microbatch -------------------------------------------------------------------
+static int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st) {
+  const pf_model_desc& m = c->md;
+  const int64_t* o = c->lay.off;
+  const int64_t T = c->lay.tokens;
+  const int32_t d = m.d_model, f = m.d_ff, dt = m.dtype;
+  PF_HIP(pf::layernorm_fwd(dt, x_in, wb + o[0], wb + o[1], c->ws_ln, nullptr, nullptr, T, d, m.eps, st));
+  pf::GemmEpilogue e1;
+  e1.bias = wb + o[3];
+  PF_HIP(pf::gemm_nt(dt, c->ws_ln, wb + o[2], c->ws_qkv, T, 3 * d, d, e1, st));
+  PF_HIP(pf::attention_fwd(dt, c->ws_qkv, c->ws_attn, nullptr, m.batch, m.seq_len, m.n_heads, d / m.n_heads,
+                           m.causal, st));
+  pf::GemmEpilogue e2;
+  e2.bias = wb + o[5];
+  e2.resid = x_in;
+  PF_HIP(pf::gemm_nt(dt, c->ws_attn, wb + o[4], x_out, T, d, d, e2, st));
+  PF_HIP(pf::layernorm_fwd(dt, x_out, wb + o[6], wb + o[7], c->ws_ln, nullptr, nullptr, T, d, m.eps, st));
+  pf::GemmEpilogue e3;
+  e3.bias = wb + o[9];
+  e3.gelu = 1;
+  PF_HIP(pf::gemm_nt(dt, c->ws_ln, wb + o[8], c->ws_mid, T, f, d, e3, st));
+  pf::GemmEpilogue e4;
+  e4.bias = wb + o[11];
+  e4.resid = x_out;
+  PF_HIP(pf::gemm_nt(dt, c->ws_mid, wb + o[10], x_out, T, d, f, e4, st));
+  return PF_OK;
+}
+
+static int32_t check_chunk(const pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, int64_t cap,
+                           const char* who) {
+  if (!c || !ch || !F || nF <= 0) return pf::fail(PF_ERR_ARG, "%s: null argument", who);
+  if (ch->node_begin < 0 || ch->node_end < ch->node_begin) return pf::fail(PF_ERR_ARG, "%s: bad node range", who);
+  if (cap > 0 && ch->mem_bytes > cap)
+    return pf::fail(PF_ERR_NOMEM, "%s: chunk needs %lld bytes, the bubble offers %lld", who,
+                    (long long)ch->mem_bytes, (long long)cap);
+  for (int32_t j = ch->node_begin; j < ch->node_end; ++j) {
+    const pf_node& n = F[j % nF];
+    if (n.mb_count != c->cfg.g)
+      return pf::fail(PF_ERR_ARG, "%s: node %d visits %d microbatches, the context was made for %d", who, j % nF,
+                      n.mb_count, c->cfg.g);
+    if ((n.op == PF_OP_LAYER_FWD || n.op == PF_OP_LAYER_BWD) && (n.layer < 0 || n.layer >= c->md.n_layers))
+      return pf::fail(PF_ERR_ARG, "%s: node %d names layer %d", who, j % nF, n.layer);
+    if (n.op < PF_OP_EMBED || n.op > PF_OP_OPT) return pf::fail(PF_ERR_ARG, "%s: node %d has unknown op", who, j % nF);
+    if (n.op == PF_OP_EMBED && c->md.vocab == 0)
+      return pf::fail(PF_ERR_ARG, "%s: EMBED node but the model has no vocabulary", who);
+  }
+  return PF_OK;
+}
+
+int32_t pf_fill_chunk_fwd(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, const void* act_in,
+                          void* act_out, int64_t cap_bytes, void* fill_stream) {
+  int32_t rc = check_chunk(c, ch, F, nF, cap_bytes, "pf_fill_chunk_fwd");
+  if (rc != PF_OK) return rc;
+  for (int32_t j = ch->node_begin; j < ch->node_end; ++j)
+    if (F[j % nF].op > PF_OP_HEAD_LOSS)
+      return pf::fail(PF_ERR_STATE, "pf_fill_chunk_fwd: node %d is a backward-type node", j % nF);
+  hipStream_t st = (hipStream_t)fill_stream;
+  const pf_model_desc& m = c->md;
+  const int32_t g = c->cfg.g;
+  const int64_t act = c->lay.act, T = c->lay.tokens;
+  const void* last_out = c->X;
+  for (int32_t j = ch->node_begin; j < ch->node_end; ++j) {
+    const pf_node& n = F[j % nF];
+    const int64_t r = c->replica_base + j / nF;
+    const bool first_of_chunk = (j == ch->node_begin);
+    const bool starts_replica = (j % nF == 0);
+    // where this node's input comes from
+    const char* src = c->X;
+    if (first_of_chunk && act_in) {
+      src = (const char*)act_in;
+    } else if (starts_replica) {
+      if (!c->in || c->n_in <= 0) return pf::fail(PF_ERR_STATE, "pf_fill_chunk_fwd: no input ring set (pf_ctx_set_io)");
+      const int64_t slot_bytes = (m.vocab > 0) ? (int64_t)g * T * 4 : (int64_t)g * act;
+      src = (const char*)c->in + (r % c->n_in) * slot_bytes;
+    }
+    switch (n.op) {
+      case PF_OP_EMBED:
+        for (int32_t mb = 0; mb < g; ++mb)
+          PF_HIP(pf::embed_fwd(m.dtype, (const int32_t*)src + mb * T, c->tok, c->pos, c->X + mb * act, T, m.seq_len,
+                               m.d_model, m.vocab, st));
+        last_out = c->X;
+        break;
+      case PF_OP_LAYER_FWD: {
+        const char* wb;
+        int32_t slot = -1;
+        if (c->cfg.streamed) {
+          rc = acquire_layer(c, n.layer, st, &slot);
+          if (rc != PF_OK) return rc;
+          wb = c->slots + (int64_t)slot * c->lay.blob;
+        } else {
+          wb = (const char*)c->layers[n.layer];
+        }
+        for (int32_t mb = 0; mb < g; ++mb) {
+          rc = layer_forward(c, wb, src + mb * act, c->X + mb * act, st);
+          if (rc != PF_OK) return rc;
+        }
+        if (slot >= 0) {
+          PF_HIP(hipEventRecord(c->slot_free[slot], st));
+          c->slot_free_valid[slot] = 1;
+        }
+        last_out = c->X;
+        break;
+      }
+      case PF_OP_FINAL_LN: {
+        char* dst = c->X;
+        if (c->out && c->n_out > 0) dst = (char*)c->out + (r % c->n_out) * ((int64_t)g * act);
+        for (int32_t mb = 0; mb < g; ++mb)
+          PF_HIP(pf::layernorm_fwd(m.dtype, src + mb * act, c->lnf_g, c->lnf_b, dst + mb * act, nullptr, nullptr, T,
+                                   m.d_model, m.eps, st));
+        last_out = dst;
+        break;
+      }
+      default:
+        return pf::fail(PF_ERR_STATE, "pf_fill_chunk_fwd: op %d is not available in this build", n.op);
+    }
+  }
+  if (act_out && ch->node_end > ch->node_begin)
+    PF_HIP(hipMemcpyAsync(act_out, last_out, (size_t)((int64_t)g * act), hipMemcpyDeviceToDevice, st));
+  return PF_OK;
+}
+
+int32_t pf_fill_chunk_bwd(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, const void* grad_io,
+                          void* grad_out, int64_t cap_bytes, void* fill_stream) {
+  (void)grad_io; (void)grad_out; (void)fill_stream;
+  int32_t rc = check_chunk(c, ch, F, nF, cap_bytes, "pf_fill_chunk_bwd");
+  if (rc != PF_OK) return rc;
+  return pf::fail(PF_ERR_STATE, "pf_fill_chunk_bwd: backward nodes are not available in this build");
+}
+
+int32_t pf_fill_chunk(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, int64_t cap_bytes,
+                      void* fill_stream) {
+  int32_t rc = check_chunk(c, ch, F, nF, cap_bytes, "pf_fill_chunk");
+  if (rc != PF_OK) return rc;
+  // split the chunk into maximal runs of forward-type and backward-type nodes
+  int32_t j = ch->node_begin;
+  while (j < ch->node_end) {
+    const bool bwd = F[j % nF].op > PF_OP_HEAD_LOSS;
+    int32_t e = j;
+    while (e < ch->node_end && (F[e % nF].op > PF_OP_HEAD_LOSS) == bwd) ++e;
+    pf_chunk part = *ch;
+    part.node_begin = j;
+    part.node_end = e;
+    rc = bwd ? pf_fill_chunk_bwd(c, &part, F, nF, nullptr, nullptr, 0, fill_stream)
+             : pf_fill_chunk_fwd(c, &part, F, nF, nullptr, nullptr, 0, fill_stream);
+    if (rc != PF_OK) return rc;
+    j = e;
+  }
+  return PF_OK;
+}
+
+// ---- profiling -----------------------------------------------------------------------------------
+int32_t pf_profile_chain(pf_ctx* c, pf_node* F, int32_t nF, int32_t warmup, int32_t reps, void* stream) {
+  if (!c || !F || nF <= 0 || warmup < 0 || reps <= 0) return pf::fail(PF_ERR_ARG, "pf_profile_chain: bad argument");
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<hipEvent_t> ev(nF + 1, nullptr);
+  for (auto& e : ev) PF_HIP(hipEventCreate(&e));
+  std::vector<std::vector<float>> ms(nF);
+  int32_t rc = PF_OK;
+  const int64_t saved_base = c->replica_base;
+  for (int32_t it = 0; it < warmup + reps && rc == PF_OK; ++it) {
+    // the whole chain runs in order so that streamed configurations are measured with their
+    // copies overlapping the previous layer, as they do inside a bubble
+    hipError_t he = hipEventRecord(ev[0], st);
+    for (int32_t i = 0; i < nF && rc == PF_OK && he == hipSuccess; ++i) {
+      pf_chunk one{0, 0, i, i + 1, 0, 0};
+      rc = pf_fill_chunk(c, &one, F, nF, 0, st);
+      if (rc == PF_OK) he = hipEventRecord(ev[i + 1], st);
+    }
+    if (rc == PF_OK && he == hipSuccess) he = hipStreamSynchronize(st);
+    if (rc == PF_OK && he != hipSuccess) rc = pf::fail(PF_ERR_HIP, "pf_profile_chain: %s", hipGetErrorString(he));
+    if (rc == PF_OK && it >= warmup)
+      for (int32_t i = 0; i < nF; ++i) {
+        float t = 0.f;
+        he = hipEventElapsedTime(&t, ev[i], ev[i + 1]);
+        if (he != hipSuccess) { rc = pf::fail(PF_ERR_HIP, "pf_profile_chain: %s", hipGetErrorString(he)); break; }
+        ms[i].push_back(t);
+      }
+  }
+  c->replica_base = saved_base;
+  for (auto& e : ev) (void)hipEventDestroy(e);
+  if (rc != PF_OK) return rc;
+  for (int32_t i = 0; i < nF; ++i) {
+    std::sort(ms[i].begin(), ms[i].end());
+    const double med = ms[i][ms[i].size() / 2];
+    F[i].dur_ns = (int64_t)(med * 1e6 + 0.5);
+    if (F[i].dur_ns < 1) F[i].dur_ns = 1;
+  }
+  return PF_OK;
+}
+
+// ---- emulated pipeline stage -----------------------------------------------------------------------
+static int64_t now_ns() {
+  timespec ts;
+  clock_gettime(CLOCK_MONOTONIC, &ts);
+  return (int64_t)ts.tv_sec * 1000000000LL + ts.tv_nsec;
+}
+
+// sleep coarsely, then spin the last 150 us, until the monotonic clock reaches `deadline`
+static void wait_until(int64_t deadline) {
+  for (;;) {
+    const int64_t left = deadline - now_ns();
+    if (left <= 0) return;
+    if (left > 200000) {
+      timespec ts{0, (long)std::min<int64_t>(left - 150000, 2000000)};
+      nanosleep(&ts, nullptr);
+    }
+  }
+}
+
+int32_t pf_main_stage_step(pf_ctx* c, int32_t instr, int32_t index, const void* io, void* main_stream) {
+  (void)index; (void)io; (void)main_stream;
+  if (!c) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: null context");
+  if (instr == PF_INSTR_BUBBLE)
+    return pf::fail(PF_ERR_ARG, "pf_main_stage_step: the bubble instruction is executed by pf_timeline_run");
+  return pf::fail(PF_ERR_STATE, "pf_main_stage_step: the real main stage is not available in this build");
+}
+
+int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, int32_t m, int32_t stage,
+                        int64_t tf_ns, int64_t tb_ns, const pf_bubble* W, int32_t nW, const pf_chunk* plan,
+                        int32_t n_plan, const pf_node* F, int32_t nF, int32_t* cursor, void* fill_stream,
+                        void* main_stream, pf_timeline_stats* stats) {
+  if (p < 1 || m < 1 || stage < 0 || stage >= p || tf_ns <= 0 || tb_ns <= 0 || nW < 0 || (nW > 0 && !W) || !stats)
+    return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad schedule argument");
+  if (fc && (!plan || n_plan <= 0 || !F || nF <= 0 || !cursor || *cursor < 0 || *cursor >= n_plan))
+    return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad plan argument");
+  hipStream_t fs = (hipStream_t)fill_stream, mstr = (hipStream_t)main_stream;
+  if (fc && fs == mstr) return pf::fail(PF_ERR_ARG, "pf_timeline_run: fill and main streams must differ");
+  // instruction list of the stage in 1F1B order, bubbles where the schedule has idle windows
+  struct Instr { int32_t kind, index; };
+  std::vector<Instr> prog;
+  const int32_t nf0 = std::min(p - stage, m);
+  const bool has_fb = (int64_t)p * tf_ns + (int64_t)(p - 1 - stage) * tb_ns > (int64_t)(stage + nf0) * tf_ns;
+  int32_t nb = 0;
+  for (int32_t j = 0; j < nf0; ++j) prog.push_back({PF_INSTR_FWD, j});
+  if (has_fb) prog.push_back({PF_INSTR_BUBBLE, nb++});
+  int32_t fnext = nf0;
+  bool fwd_before = true;
+  for (int32_t j = 0; j < m; ++j) {
+    if (!fwd_before) prog.push_back({PF_INSTR_BUBBLE, nb++});
+    prog.push_back({PF_INSTR_BWD, j});
+    fwd_before = false;
+    if (fnext < m) {
+      prog.push_back({PF_INSTR_FWD, fnext++});
+      fwd_before = true;
+    }
+  }
+  if (stage > 0) prog.push_back({PF_INSTR_BUBBLE, nb++});
+  if (nb != nW)
+    return pf::fail(PF_ERR_ARG, "pf_timeline_run: the schedule has %d idle windows, %d were passed", nb, nW);
+
+  std::memset(stats, 0, sizeof *stats);
+  struct Rec { hipEvent_t fs0, fs1, dead; bool used; };
+  std::vector<Rec> recs(nW, Rec{nullptr, nullptr, nullptr, false});
+  hipEvent_t mb0 = nullptr, mb1 = nullptr;
+  hipStream_t tstream = nullptr;   // idle stream: an event recorded on it is stamped "now"
+  int32_t rc = PF_OK;
+  auto hipck = [&](hipError_t e, const char* what) {
+    if (e != hipSuccess && rc == PF_OK) rc = pf::fail(PF_ERR_HIP, "pf_timeline_run: %s: %s", what, hipGetErrorString(e));
+    return e == hipSuccess;
+  };
+  hipck(hipStreamCreateWithFlags(&tstream, hipStreamNonBlocking), "stream");
+  for (auto& r : recs) {
+    hipck(hipEventCreate(&r.fs0), "event");
+    hipck(hipEventCreate(&r.fs1), "event");
+    hipck(hipEventCreate(&r.dead), "event");
+  }
+  double main_ms = 0.0;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> main_ev;
+  const int64_t t_start = now_ns();
+  int64_t t_sched = t_start;          // scheduled time of the next instruction (placeholder main stage)
+  for (size_t pc = 0; pc < prog.size() && rc == PF_OK; ++pc) {
+    const Instr in = prog[pc];
+    if (in.kind != PF_INSTR_BUBBLE) {
+      if (mc) {
+        hipEvent_t a = nullptr, b = nullptr;
+        hipck(hipEventCreate(&a), "event");
+        hipck(hipEventCreate(&b), "event");
+        main_ev.push_back({a, b});
+        if (rc == PF_OK) hipck(hipEventRecord(a, mstr), "record");
+        if (rc == PF_OK) rc = pf_main_stage_step(mc, in.kind, in.index, main_io, main_stream);
+        if (rc == PF_OK) hipck(hipEventRecord(b, mstr), "record");
+      } else {
+        t_sched += (in.kind == PF_INSTR_FWD) ? tf_ns : tb_ns;
+        wait_until(t_sched);
+      }
+      continue;
+    }
+    const pf_bubble& w = W[in.index];
+    // the bubble opens when the stage has nothing left to run
+    if (mc) {
+      hipck(hipStreamSynchronize(mstr), "main sync");
+      t_sched = now_ns();
+    }
+    const int64_t deadline = t_sched + w.dur_ns;
+    stats->idle_ns += w.dur_ns;
+    if (w.fillable) stats->offered_ns += w.dur_ns;
+    if (rc == PF_OK && fc && w.fillable && plan[*cursor].bubble == in.index) {
+      const pf_chunk& ch = plan[*cursor];
+      if (ch.node_end > ch.node_begin) {
+        Rec& r = recs[in.index];
+        hipck(hipEventRecord(r.fs0, fs), "record");
+        if (rc == PF_OK) rc = pf_fill_chunk(fc, &ch, F, nF, w.free_bytes, fill_stream);
+        if (rc == PF_OK) hipck(hipEventRecord(r.fs1, fs), "record");
+        r.used = (rc == PF_OK);
+        stats->chunks_run += 1;
+        for (int32_t j = ch.node_begin; j < ch.node_end; ++j)
+          if (j % nF == nF - 1) stats->replicas_done += 1;
+      }
+      if (++*cursor == n_plan) {
+        *cursor = 0;
+        fc->replica_base += plan[n_plan - 1].node_end / nF;
+      }
+    }
+    wait_until(deadline);
+    if (rc == PF_OK && recs[in.index].used) hipck(hipEventRecord(recs[in.index].dead, tstream), "record");
+    t_sched = deadline;
+  }
+  hipck(hipDeviceSynchronize(), "final sync");
+  stats->iter_ns = (mc ? now_ns() : t_sched) - t_start;
+  if (rc == PF_OK) {
+    for (auto& r : recs) {
+      if (!r.used) continue;
+      float busy = 0.f, over = 0.f;
+      hipck(hipEventElapsedTime(&busy, r.fs0, r.fs1), "elapsed");
+      hipck(hipEventElapsedTime(&over, r.dead, r.fs1), "elapsed");
+      stats->fill_busy_ns += (int64_t)(busy * 1e6);
+      if (over > 0.f) stats->overrun_ns += (int64_t)(over * 1e6);
+    }
+    for (auto& pr : main_ev) {
+      float t = 0.f;
+      hipck(hipEventElapsedTime(&t, pr.first, pr.second), "elapsed");
+      main_ms += t;
+    }
+    stats->main_busy_ns = (int64_t)(main_ms * 1e6);
+  }
+  for (auto& r : recs) {
+    if (r.fs0) (void)hipEventDestroy(r.fs0);
+    if (r.fs1) (void)hipEventDestroy(r.fs1);
+    if (r.dead) (void)hipEventDestroy(r.dead);
+  }
+  for (auto& pr : main_ev) {
+    if (pr.first) (void)hipEventDestroy(pr.first);
+    if (pr.second) (void)hipEventDestroy(pr.second);
+  }
+  (void)mb0; (void)mb1;
+  if (tstream) (void)hipStreamDestroy(tstream);
+  return rc;
+}
+
+int32_t pf_ctx_train_state(pf_ctx* c, double* loss, int64_t* steps) {
+  (void)loss; (void)steps;
+  if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_train_state: null context");
+  return pf::fail(PF_ERR_STATE, "pf_ctx_train_state: not a training context");
+}
+
+int32_t pf_ctx_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, void* stream) {
+  (void)what; (void)layer; (void)dst; (void)dst_bytes; (void)stream;
+  if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_read_params: null context");
+  return pf::fail(PF_ERR_STATE, "pf_ctx_read_params: not a training context");
+}
+
+// ---- single kernels --------------------------------------------------------------------------------
+static bool bad_dtype(int32_t dt) { return dt != PF_DTYPE_F32 && dt != PF_DTYPE_BF16; }
+
+int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K,
+                   const void* bias, const void* resid, int32_t gelu, int32_t out_f32, int32_t accumulate,
+                   void* stream) {
+  if (bad_dtype(dtype) || !X || !W || !C || M <= 0 || N <= 0 || K <= 0 || (dtype == PF_DTYPE_BF16 && K % 8 != 0) ||
+      (accumulate && !out_f32 && dtype != PF_DTYPE_F32))
+    return pf::fail(PF_ERR_ARG, "pf_op_gemm: bad argument");
+  pf::GemmEpilogue e;
+  e.bias = bias;
+  e.resid = resid;
+  e.gelu = gelu;
+  e.out_f32 = out_f32;
+  e.accumulate = accumulate;
+  PF_HIP(pf::gemm_nt(dtype, X, W, C, M, N, K, e, (hipStream_t)stream));
+  return PF_OK;
+}
+
+int32_t pf_op_layernorm(int32_t dtype, const void* x, const void* g, const void* b, void* y, float* mean_out,
+                        float* rstd_out, int64_t rows, int32_t d, float eps, void* stream) {
+  if (bad_dtype(dtype) || !x || !g || !b || !y || rows <= 0 || d <= 0 || d % 8 != 0 || d > 8192)
+    return pf::fail(PF_ERR_ARG, "pf_op_layernorm: bad argument (d must be a multiple of 8, at most 8192)");
+  PF_HIP(pf::layernorm_fwd(dtype, x, g, b, y, mean_out, rstd_out, rows, d, eps, (hipStream_t)stream));
+  return PF_OK;
+}
+
+int32_t pf_op_attention(int32_t dtype, const void* qkv, void* out, float* lse, int32_t B, int32_t S, int32_t h,
+                        int32_t dh, int32_t causal, void* stream) {
+  if (bad_dtype(dtype) || !qkv || !out || B <= 0 || S <= 0 || h <= 0 || B > 65535 || h > 65535 ||
+      !(dh == 8 || dh == 16 || dh == 32 || dh == 64 || dh == 128))
+    return pf::fail(PF_ERR_ARG, "pf_op_attention: bad argument (d_head must be 8, 16, 32, 64 or 128)");
+  PF_HIP(pf::attention_fwd(dtype, qkv, out, lse, B, S, h, dh, causal, (hipStream_t)stream));
+  return PF_OK;
+}
+
+int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int64_t tokens,
+                    int32_t S, int32_t d, int32_t V, void* stream) {
+  if (bad_dtype(dtype) || !ids || !tok || !pos || !x || tokens <= 0 || S <= 0 || d <= 0 || d % 8 != 0 || V <= 0)
+    return pf::fail(PF_ERR_ARG, "pf_op_embed: bad argument");
+  PF_HIP(pf::embed_fwd(dtype, ids, tok, pos, x, tokens, S, d, V, (hipStream_t)stream));
+  return PF_OK;
+}
+
+}  // extern "C"

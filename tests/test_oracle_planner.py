@@ -293,8 +293,3 @@ def test_chain_nodes_shape():
                            g=1, streamed=False, n_slots=0, training=False)
     assert len(nodes) == 14 and [n[0] for n in nodes] == [0] + [1] * 12 + [2]
     assert op.layer_param_count(768, 3072) == 7087872       # one BERT-base-shaped layer
-    s = synth.WORKLOADS["cfg4"]
-    nodes = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2,
-                           g=1, streamed=False, n_slots=0, training=True)
-    assert len(nodes) == 1 + 12 + 1 + 1 + 12 + 1
-    assert [n[1] for n in nodes if n[0] == op.OP_LAYER_BWD] == list(range(11, -1, -1))
