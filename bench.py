@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the fill-job hot path on one MI355X.
+
+A step is one emulated main-job iteration of one 1F1B stage: the stage's idle windows are derived,
+the fill job's chain is profiled and partitioned onto them (Algorithm 1), and the Executor loop
+runs the planned chunks inside the windows while the main stage is emulated on the timeline.
+Steps rotate over all p stages; the headline value aggregates over them:
+
+    fill tokens/s in bubbles = tokens of fill sequences that completed every layer
+                               / summed duration of the windows offered
+
+Default workload: the 12-layer bf16 encoder inference fill job (d=768, 12 heads, FFN 3072,
+seq 512, batch 32) in the bubbles of 1F1B p=8, m=16, t_f=15 ms, t_b=30 ms with 24 GiB free.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+
+
+def gemm_flops(M, N, K):
+    return 2.0 * M * N * K
+
+
+def cpu_baseline(shape, params, ids, n_seq):
+    """The CPU checker as it stands, timed on a bounded sample: n_seq sequences of the workload's
+    batch through the whole model (embedding, all layers, final LayerNorm)."""
+    import numpy as np
+    from oracle import transformer as ot
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    P = ot.cast_params(params)
+    sample = ids[:n_seq]
+    t0 = time.perf_counter()
+    ot.model_forward(sample, P, shape.n_heads, shape.causal, shape.eps)
+    dt = time.perf_counter() - t0
+    return {"value": sample.size / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n_seq} of {shape.batch} sequences (seq {shape.seq_len}) through all "
+                      f"{shape.n_layers} layers in float64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
+    ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
+    ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the fill path has no cross-GPU step "
+              "(one independent Executor per device). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback for the product path", file=sys.stderr)
+        sys.exit(3)
+    from paper_2410_07192_amd import binding as pf
+    from paper_2410_07192_amd import device as dev
+    from paper_2410_07192_amd import synth
+
+    name = args.workload
+    shape = synth.WORKLOADS[name]
+    p, m, tf, tb, free = synth.SCHEDULES[name]
+    cfg_index = int(name[3:]) - 1
+    params = synth.make_model_params(shape, seed=0 + 100 * cfg_index)
+    n_ring = 4
+    ids = np.stack([synth.make_token_ids(shape, seed=1 + 100 * cfg_index + 1000 * i) for i in range(n_ring)])
+
+    model = dev.DeviceModel(shape, params)
+    d_in = dev.to_device(ids.astype(np.int32))
+    d_out = dev.empty_storage((2, 1, shape.batch, shape.seq_len, shape.d_model), model.md)
+    model.set_io(d_in, n_ring, d_out, 2)
+    fill = torch.cuda.Stream()
+    main_s = torch.cuda.Stream()
+
+    # per-node profile on this device (the profiles the Executor is handed)
+    model.ctx.pf_profile_chain(model.chain, 3, 7, fill.cuda_stream)
+    chain_ns = sum(n.dur_ns for n in model.chain)
+
+    # windows and plans for every stage
+    stages = []
+    t_plan = 0.0
+    for s in range(p):
+        windows = pf.pf_schedule_1f1b(p, m, s, tf, tb, free, not args.paper_mode, 2 * max(n.dur_ns for n in model.chain))
+        t0 = time.perf_counter()
+        plan, n_plan, k = pf.pf_plan_bubbles(windows, model.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
+        t_plan += time.perf_counter() - t0
+        stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, replicas=k, cursor=C.c_int32(0)))
+
+    timed_mask = (1 << pf.PF_K_GEMM_QKV) | (1 << pf.PF_K_GEMM_FFN1)
+
+    def run_step(i):
+        st = stages[i % p]
+        return pf.pf_timeline_run(model.ctx, None, None, p, m, st["stage"], tf, tb, st["windows"], st["plan"],
+                                  st["n_plan"], model.chain, st["cursor"], fill.cuda_stream, main_s.cuda_stream)
+
+    for i in range(args.warmup):
+        run_step(i)
+    for st in stages:
+        st["cursor"] = C.c_int32(0)
+    model.ctx.pf_ctx_kernel_timing(timed_mask)
+    torch.cuda.synchronize()
+    agg = dict(offered_ns=0, idle_ns=0, fill_busy_ns=0, overrun_ns=0, replicas_done=0, chunks_run=0, iter_ns=0)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        s = run_step(i)
+        for k_ in agg:
+            agg[k_] += s[k_]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    tokens = agg["replicas_done"] * shape.tokens
+    value = tokens / (agg["offered_ns"] * 1e-9)
+
+    # dominant kernel: the 256x256-tile bf16 GEMM (fused QKV projection and first FFN matrix)
+    T, d, f = shape.tokens, shape.d_model, shape.d_ff
+    n_q, ns_q = model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_QKV)
+    n_f, ns_f = model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)
+    flops = n_q * gemm_flops(T, 3 * d, d) + n_f * gemm_flops(T, f, d)
+    achieved = flops / max(1, ns_q + ns_f) * 1e-3            # TFLOP/s
+    roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / BF16_PEAK_TFLOPS, "traffic": None,
+                "kernel": "gemm_bf16_nt_kernel<2,4,4,2> 256x256 tile (QKV and FFN1 GEMMs)",
+                "launches": n_q + n_f, "avg_us": (ns_q + ns_f) / max(1, n_q + n_f) * 1e-3}
+
+    layer_flops = gemm_flops(T, 3 * d, d) + gemm_flops(T, d, d) + 2 * gemm_flops(T, f, d) + \
+        4.0 * shape.batch * shape.seq_len ** 2 * d * (0.5 if shape.causal else 1.0)
+    out = {
+        "metric": "fill tokens/s in bubbles", "value": value, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{name}: 12-layer bf16 encoder inference fill job d=768 h=12 ff=3072 seq=512 "
+                               f"batch=32, weights resident, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 24 GiB free, "
+                               f"all {p} stages in rotation",
+                   "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
+                   "windows": "contiguous only" if args.paper_mode else "all idle windows"},
+        "pct_bubble_filled": 100.0 * agg["fill_busy_ns"] / agg["offered_ns"],
+        "pct_idle_filled": 100.0 * agg["fill_busy_ns"] / agg["idle_ns"],
+        "overrun_pct_of_offered": 100.0 * agg["overrun_ns"] / agg["offered_ns"],
+        "main_slowdown_pct": None,
+        "fill_tflops_in_bubbles": agg["replicas_done"] * shape.n_layers * layer_flops / (agg["offered_ns"] * 1e-9) * 1e-12,
+        "replicas_done": agg["replicas_done"], "chunks_run": agg["chunks_run"],
+        "chain_ms": chain_ns * 1e-6, "planner_ms_all_stages": t_plan * 1e3,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs)
+    model.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -49,6 +49,10 @@ enum { PF_OP_EMBED = 0, PF_OP_LAYER_FWD = 1, PF_OP_FINAL_LN = 2, PF_OP_HEAD_LOSS
 
 enum { PF_DTYPE_F32 = 0, PF_DTYPE_BF16 = 1 };
 
+/* kernel classes of a layer visit, for pf_ctx_kernel_timing / pf_ctx_kernel_stats */
+enum { PF_K_GEMM_QKV = 0, PF_K_GEMM_OUT = 1, PF_K_GEMM_FFN1 = 2, PF_K_GEMM_FFN2 = 3, PF_K_ATTENTION = 4,
+       PF_K_LAYERNORM = 5, PF_K_EMBED = 6, PF_KERNEL_CLASSES = 16 };
+
 /* instructions of the emulated main-job stage (Sec. 4.2: forward / backward of a microbatch,
  * and the pipeline bubble instruction) */
 enum { PF_INSTR_FWD = 0, PF_INSTR_BWD = 1, PF_INSTR_BUBBLE = 2 };
@@ -281,6 +285,13 @@ int32_t pf_ctx_train_state(pf_ctx* ctx, double* loss, int64_t* steps);
  * layer == -1: tok_emb | pos_emb | lnf_g | lnf_b concatenated.  For tests of training jobs. */
 int32_t pf_ctx_read_params(pf_ctx* ctx, int32_t what, int32_t layer, void* dst, int64_t dst_bytes,
                            void* stream);
+
+/* Per-kernel-class timing.  mask: bit k enables class PF_K_k; enabled launches are bracketed by HIP
+ * events on the stream they run on (a fixed pool of 16384 pairs between two reads; launches
+ * beyond it run untimed).  pf_ctx_kernel_stats synchronises the device, folds the pool into the
+ * totals and returns the class's launch count and summed duration since timing was enabled. */
+int32_t pf_ctx_kernel_timing(pf_ctx* ctx, uint32_t mask);
+int32_t pf_ctx_kernel_stats(pf_ctx* ctx, int32_t cls, int64_t* count, int64_t* total_ns);
 
 /* ---- single kernels (the steps a layer visit is made of; used by tests and by the roofline
  * measurement).  All pointers device; `dtype` = storage type; fp32 accumulation throughout. ------ */

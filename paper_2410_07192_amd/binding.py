@@ -26,8 +26,9 @@ EXPORTS = [
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
     "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
-    "pf_op_embed",
+    "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats",
 ]
+PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
 
 
 class PipeFillError(RuntimeError):
@@ -113,6 +114,8 @@ def _load():
                                     P(pf_node), I32, P(I32), VP, VP, P(pf_timeline_stats)]
     lib.pf_ctx_train_state.argtypes = [VP, P(C.c_double), P(I64)]
     lib.pf_ctx_read_params.argtypes = [VP, I32, I32, VP, I64, VP]
+    lib.pf_ctx_kernel_timing.argtypes = [VP, C.c_uint32]
+    lib.pf_ctx_kernel_stats.argtypes = [VP, I32, P(I64), P(I64)]
     lib.pf_op_gemm.argtypes = [I32, VP, VP, VP, I64, I64, I64, VP, VP, I32, I32, I32, VP]
     lib.pf_op_layernorm.argtypes = [I32, VP, VP, VP, VP, VP, VP, I64, I32, C.c_float, VP]
     lib.pf_op_attention.argtypes = [I32, VP, VP, VP, I32, I32, I32, I32, I32, VP]
@@ -342,6 +345,15 @@ class Context:
 
     def pf_main_stage_step(self, instr, index, io_ptr, stream=None):
         _check(lib.pf_main_stage_step(self.handle, instr, index, io_ptr, stream))
+
+    def pf_ctx_kernel_timing(self, mask):
+        _check(lib.pf_ctx_kernel_timing(self.handle, mask))
+
+    def pf_ctx_kernel_stats(self, cls):
+        n = C.c_int64(0)
+        t = C.c_int64(0)
+        _check(lib.pf_ctx_kernel_stats(self.handle, cls, C.byref(n), C.byref(t)))
+        return n.value, t.value
 
     def pf_ctx_train_state(self):
         loss = C.c_double(0.0)

@@ -1,18 +1,28 @@
 // GEMM kernels for gfx950:  C[M,N] = epilogue( X[M,K] * W[N,K]^T ).
 //
-// bf16 path: 32x32x16 bf16 MFMA, fp32 accumulators.  A workgroup of WGM x WGN waves owns a
-// (WGM*TM*32) x (WGN*TN*32) tile of C and walks K in steps of 64.  Both operand tiles are staged in
-// LDS as 16-byte chunks (8 bf16 along K) with an XOR swizzle so that the 32 rows a wave reads for one
-// MFMA operand fall into distinct banks; LDS is double buffered and the next K step's global loads
-// are issued before the MFMAs of the current one.  The weight tile is the MFMA "A" operand and the
-// activation tile the "B" operand, so that each lane ends up with 4 consecutive output columns of
-// one output row: bias / residual / GELU are applied in registers and stored as 8-byte pieces.
-// Workgroup ids are remapped so that each of the 8 XCDs (ids are dealt round-robin to them) works on
-// a contiguous range of tiles and its L2 sees each operand panel once.
-//
+// bf16 main path (K a multiple of 64): 32x32x16 bf16 MFMA, fp32 accumulators.  A workgroup of
+// WGM x WGN waves owns a (WGM*TM*32) x (WGN*TN*32) tile of C and walks K in steps of 64.
+//  * Operand tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
+//    VGPR round trip).  A wave's 64 lanes fill 1 KB of consecutive LDS = 8 rows of 8 chunks; the XOR
+//    swizzle that keeps the later MFMA operand reads free of bank conflicts is applied on the global
+//    side (lane -> which chunk of the row it fetches).  Rows beyond M / N are clamped to the last
+//    valid row (their products are never stored).
+//  * Two LDS stages: the loads of step k+2 are issued right after the barrier that ends the reads
+//    of step k and have a whole step to land.  They are written as inline assembly so that the
+//    compiler does not serialise every later LDS read behind them; vmcnt is waited by hand.
+//  * Operand fragments are double buffered in registers: the 16-byte LDS reads of sub-step kk+1
+//    are in flight while the MFMAs of sub-step kk issue.
+//  * The weight tile is the MFMA "A" operand and the activation tile the "B" operand, so each lane
+//    ends up with 4 consecutive output columns of one output row: bias / GELU / residual are applied
+//    in registers and stored as 8-byte pieces.
+//  * Workgroup ids are remapped so that each of the 8 XCDs (ids are dealt round-robin to them) works
+//    on a contiguous range of tiles and its L2 sees each operand panel once.
+// bf16 generic path (any K multiple of 8): register-staged LDS tiles, same MFMA layout.
 // fp32 path (small parity workload only): plain LDS-tiled FMA kernel with the same epilogue.
 #include "pf_kernels.h"
 #include "pf_device.h"
+
+#include <type_traits>
 
 namespace pf {
 namespace {
@@ -27,49 +37,59 @@ struct EpiDev {
 };
 
 // Epilogue for 4 consecutive columns n0..n0+3 of row m.  T = storage type of bias / resid / aux,
-// OutT = type of C.
+// OutT = type of C.  The vector form needs n0+3 < N and N % 4 == 0; the scalar form checks every
+// element.
 template <typename T, typename OutT>
-__device__ __forceinline__ void epilogue4(float v[4], int64_t m, int64_t n0, int64_t M, int64_t N, OutT* C,
-                                          const EpiDev& ep) {
-  if (m >= M || n0 >= N) return;
+__device__ __forceinline__ void epilogue4_vec(float v[4], int64_t m, int64_t n0, int64_t N, OutT* C,
+                                              const EpiDev& ep) {
   const int64_t off = m * N + n0;
-  const bool full = (n0 + 3 < N) && ((N & 3) == 0);
   const T* bias = (const T*)ep.bias;
   const T* resid = (const T*)ep.resid;
   const T* dact = (const T*)ep.dact_in;
   T* pre = (T*)ep.preact_out;
-  if (full) {
-    float t[4];
+  float t[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] *= ep.scale;
-    if (bias) {
-      load4(bias + n0, t);
+  for (int j = 0; j < 4; ++j) v[j] *= ep.scale;
+  if (bias) {
+    load4(bias + n0, t);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] += t[j];
-    }
-    if (pre) store4(pre + off, v);
-    if (ep.gelu) {
+    for (int j = 0; j < 4; ++j) v[j] += t[j];
+  }
+  if (pre) store4(pre + off, v);
+  if (ep.gelu) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
-    }
-    if (dact) {
-      load4(dact + off, t);
+    for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
+  }
+  if (dact) {
+    load4(dact + off, t);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_f(t[j]);
-    }
-    if (resid) {
-      load4(resid + off, t);
+    for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_f(t[j]);
+  }
+  if (resid) {
+    load4(resid + off, t);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] += t[j];
-    }
-    if (ep.accumulate) {
-      load4(C + off, t);
+    for (int j = 0; j < 4; ++j) v[j] += t[j];
+  }
+  if (ep.accumulate) {
+    load4(C + off, t);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) v[j] += t[j];
-    }
-    store4(C + off, v);
-  } else {
-    for (int j = 0; j < 4 && n0 + j < N; ++j) {
+    for (int j = 0; j < 4; ++j) v[j] += t[j];
+  }
+  store4(C + off, v);
+}
+
+template <typename T, typename OutT>
+__device__ __forceinline__ void epilogue4_scalar(float v[4], int64_t m, int64_t n0, int64_t M, int64_t N, OutT* C,
+                                                 const EpiDev& ep) {
+  if (m >= M) return;
+  const int64_t off = m * N + n0;
+  const T* bias = (const T*)ep.bias;
+  const T* resid = (const T*)ep.resid;
+  const T* dact = (const T*)ep.dact_in;
+  T* pre = (T*)ep.preact_out;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    if (n0 + j < N) {
       float x = v[j] * ep.scale;
       if (bias) x += to_f32(bias[n0 + j]);
       if (pre) pre[off + j] = from_f32<T>(x);
@@ -82,6 +102,50 @@ __device__ __forceinline__ void epilogue4(float v[4], int64_t m, int64_t n0, int
   }
 }
 
+// Epilogue features the main kernel is specialised on (so that its loads carry no branches and the
+// compiler can batch them); other combinations run on the generic kernel.
+enum : int { E_BIAS = 1, E_GELU = 2, E_RESID = 4, E_DACT = 8, E_PRE = 16, E_ACC = 32 };
+
+template <int EPI, typename OutT>
+__device__ __forceinline__ void epilogue4_static(float v[4], const float bias4[4], int64_t off, OutT* C,
+                                                 const EpiDev& ep) {
+  float t[4];
+  if constexpr (EPI & E_BIAS) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += bias4[j];
+  }
+  if constexpr (EPI & E_PRE) store4((bf16_t*)ep.preact_out + off, v);
+  if constexpr (EPI & E_GELU) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
+  }
+  if constexpr (EPI & E_DACT) {
+    load4((const bf16_t*)ep.dact_in + off, t);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_f(t[j]);
+  }
+  if constexpr (EPI & E_RESID) {
+    load4((const bf16_t*)ep.resid + off, t);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += t[j];
+  }
+  if constexpr (EPI & E_ACC) {
+    load4(C + off, t);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] += t[j];
+  }
+  store4(C + off, v);
+}
+
+// compile-time loop: f(integral_constant<int, I>) for I in [0, N)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (I < N) {
+    f(std::integral_constant<int, I>{});
+    static_for<I + 1, N>(f);
+  }
+}
+
 // workgroup id -> tile id such that XCD x (ids congruent x mod 8) gets a contiguous tile range
 __device__ __forceinline__ int64_t xcd_tile(int64_t pid, int64_t n_tiles) {
   const int64_t q = n_tiles >> 3, rem = n_tiles & 7;
@@ -91,7 +155,7 @@ __device__ __forceinline__ int64_t xcd_tile(int64_t pid, int64_t n_tiles) {
 
 // ------------------------------------------------------------------------------------------------
 template <int WGM, int WGN, int TM, int TN, typename OutT>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_generic_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, OutT* __restrict__ C, int64_t M, int64_t N,
     int64_t K, EpiDev ep, int32_t tiles_m, int32_t tiles_n, int32_t group_m) {
   constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NT = 64 * WGM * WGN;
@@ -183,20 +247,180 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
     __syncthreads();
   }
 
-  // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C)
-#pragma unroll
-  for (int a = 0; a < TN; ++a)
-#pragma unroll
-    for (int b = 0; b < TM; ++b) {
+  // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
+  // Indices into acc must be compile-time constants or the accumulators leave the register file.
+  const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
+  static_for<0, TN>([&](auto a) {
+    static_for<0, TM>([&](auto b) {
       const int64_t m = m0 + (wm * TM + b) * 32 + lr;
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
+      static_for<0, 4>([&](auto rg) {
         const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
         float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
                       acc[a][b][rg * 4 + 3]};
-        epilogue4<bf16_t, OutT>(v, m, n, M, N, C, ep);
-      }
+        if (interior) epilogue4_vec<bf16_t, OutT>(v, m, n, N, C, ep);
+        else epilogue4_scalar<bf16_t, OutT>(v, m, n, M, N, C, ep);
+      });
+    });
+  });
+}
+
+// ------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+template <int WGM, int WGN, int TM, int TN, typename OutT, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, OutT* __restrict__ C, int64_t M, int64_t N,
+    int64_t K, EpiDev ep, int32_t tiles_m, int32_t tiles_n, int32_t group_m) {
+  constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NW = WGM * WGN;
+  constexpr int GX = BM / 8, G = (BM + BN) / 8, GPW = G / NW;   // 8-row groups of 1 KB; per wave
+  constexpr int STAGE = (BM + BN) * 8;                          // uint4 per LDS stage
+  static_assert(G % NW == 0 && GPW <= 32, "tile / wave mismatch");
+  extern __shared__ uint4 smem[];
+
+  const int64_t tile = xcd_tile(blockIdx.x, (int64_t)tiles_m * tiles_n);
+  const int64_t per_group = (int64_t)group_m * tiles_n;
+  const int64_t grp = tile / per_group;
+  const int32_t first_m = (int32_t)(grp * group_m);
+  const int32_t rows_in_group = (tiles_m - first_m < group_m) ? tiles_m - first_m : group_m;
+  const int32_t tm_i = first_m + (int32_t)((tile % per_group) % rows_in_group);
+  const int32_t tn_i = (int32_t)((tile % per_group) / rows_in_group);
+  const int64_t m0 = (int64_t)tm_i * BM, n0 = (int64_t)tn_i * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WGM, wn = wave / WGM;
+  const int lr = lane & 31, lk = lane >> 5;
+
+  // global source of this lane for each 1 KB group the wave moves per K step
+  const bf16_t* src[GPW];
+#pragma unroll
+  for (int i = 0; i < GPW; ++i) {
+    const int g = wave + i * NW;
+    const bool isx = g < GX;
+    const int r = (isx ? g : g - GX) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    int64_t row = (isx ? m0 : n0) + r;
+    const int64_t lim = isx ? M : N;
+    if (row >= lim) row = lim - 1;
+    src[i] = (isx ? X : W) + row * K + c * 8;
+  }
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)smem);
+  auto issue = [&](int stage, int64_t k0) {
+#pragma unroll
+    for (int i = 0; i < GPW; ++i) {
+      const int g = wave + i * NW;
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)((stage * STAGE + g * 64) * 16));
+      const bf16_t* p = src[i] + k0;
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p)
+                   : "memory", "m0");
     }
+  };
+  int offW[TN], offX[TM], swW[TN], swX[TM];
+#pragma unroll
+  for (int a = 0; a < TN; ++a) {
+    const int r = (wn * TN + a) * 32 + lr;
+    offW[a] = BM * 8 + r * 8;
+    swW[a] = (r >> 1) & 7;
+  }
+#pragma unroll
+  for (int b = 0; b < TM; ++b) {
+    const int r = (wm * TM + b) * 32 + lr;
+    offX[b] = r * 8;
+    swX[b] = (r >> 1) & 7;
+  }
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int a = 0; a < TN; ++a)
+#pragma unroll
+    for (int b = 0; b < TM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  bf16x8 fw[2][TN], fx[2][TM];
+  auto load_frags = [&](int buf, const uint4* st, int kk) {
+    const int c = kk * 2 + lk;
+#pragma unroll
+    for (int a = 0; a < TN; ++a) fw[buf][a] = as_bf16x8(st[offW[a] + (c ^ swW[a])]);
+#pragma unroll
+    for (int b = 0; b < TM; ++b) fx[buf][b] = as_bf16x8(st[offX[b] + (c ^ swX[b])]);
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+      for (int b = 0; b < TM; ++b)
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][a], fx[buf][b], acc[a][b], 0, 0, 0);
+  };
+
+  const int64_t nk = K / 64;
+  issue(0, 0);
+  if (nk > 1) {
+    issue(1, 64);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(GPW) : "memory");   // stage 0 has landed, stage 1 in flight
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __builtin_amdgcn_s_barrier();
+  load_frags(0, smem, 0);
+  for (int64_t kt = 0; kt < nk; ++kt) {
+    const int cur = (int)(kt & 1);
+    const uint4* sc = smem + cur * STAGE;
+    const uint4* sn = smem + (cur ^ 1) * STAGE;
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): fragments fetched during the previous MFMA block
+    load_frags(1, sc, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(0, sc, 2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
+    load_frags(1, sc, 3);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(0);
+    __builtin_amdgcn_sched_barrier(0);
+    // every wave holds the last fragments of this stage in registers and the next stage has landed
+    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    if (kt + 2 < nk) issue(cur, (kt + 2) * 64);
+    if (kt + 1 < nk) load_frags(0, sn, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfmas(1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
+  // Indices into acc must be compile-time constants or the accumulators leave the register file.
+  const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
+  if (interior) {
+    static_for<0, TN>([&](auto a) {
+      float bias4[4][4] = {};
+      if constexpr (EPI & E_BIAS) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg)
+          load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
+      }
+      static_for<0, TM>([&](auto b) {
+        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
+        static_for<0, 4>([&](auto rg) {
+          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
+          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                        acc[a][b][rg * 4 + 3]};
+          epilogue4_static<EPI, OutT>(v, bias4[rg], m * N + n, C, ep);
+        });
+      });
+    });
+  } else {
+    static_for<0, TN>([&](auto a) {
+      static_for<0, TM>([&](auto b) {
+        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
+        static_for<0, 4>([&](auto rg) {
+          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
+          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                        acc[a][b][rg * 4 + 3]};
+          epilogue4_scalar<bf16_t, OutT>(v, m, n, M, N, C, ep);
+        });
+      });
+    });
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -233,38 +457,71 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const float* __restric
     __syncthreads();
   }
 #pragma unroll
-  for (int i = 0; i < 4; ++i) epilogue4<float, OutT>(acc[i], m0 + ty * 4 + i, n0 + tx * 4, M, N, C, ep);
+  for (int i = 0; i < 4; ++i) epilogue4_scalar<float, OutT>(acc[i], m0 + ty * 4 + i, n0 + tx * 4, M, N, C, ep);
 }
 
-template <int WGM, int WGN, int TM, int TN, typename OutT>
-hipError_t launch_bf16(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
-                       hipStream_t stream) {
-  constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+template <typename OutT, typename Kern>
+hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, const void* X, const void* W, void* C,
+                        int64_t M, int64_t N, int64_t K, const EpiDev& ep, hipStream_t stream) {
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const size_t lds = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
-  auto kern = gemm_bf16_nt_kernel<WGM, WGN, TM, TN, OutT>;
-  static bool attr_set = false;   // raise the dynamic-LDS limit once per instantiation
-  if (!attr_set) {
+  if (!*attr_set) {   // raise the dynamic-LDS limit once per instantiation
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    *attr_set = true;
   }
   const int32_t group_m = 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(64 * WGM * WGN), lds, stream,
-                     (const bf16_t*)X, (const bf16_t*)W, (OutT*)C, M, N, K, ep, (int32_t)tiles_m, (int32_t)tiles_n,
-                     group_m);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(threads), lds, stream, (const bf16_t*)X,
+                     (const bf16_t*)W, (OutT*)C, M, N, K, ep,
+                     (int32_t)tiles_m, (int32_t)tiles_n, group_m);
   return hipGetLastError();
+}
+
+template <typename OutT>
+hipError_t launch_generic(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
+                          hipStream_t stream) {
+  static bool attr = false;
+  return launch_tiles<OutT>(gemm_bf16_nt_generic_kernel<2, 2, 2, 2, OutT>, 128, 128, 256, &attr, X, W, C, M, N, K, ep,
+                      stream);
+}
+
+// main kernel for one epilogue combination: 256x256 tiles (8 waves) once they give most of the 256 CUs a
+// tile, 128x128 tiles (4 waves, two workgroups per CU) below that
+template <typename OutT, int EPI>
+hipError_t launch_fast(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
+                       hipStream_t stream) {
+  static bool attr_big = false, attr_small = false;
+  const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+  if (t256 >= 192)
+    return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 4, 4, 2, OutT, EPI>, 256, 256, 512, &attr_big, X, W, C, M, N, K, ep,
+                        stream);
+  return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 2, 2, 2, OutT, EPI>, 128, 128, 256, &attr_small, X, W, C, M, N, K, ep,
+                      stream);
 }
 
 template <typename OutT>
 hipError_t dispatch_bf16(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
                          hipStream_t stream) {
-  // Pick the largest tile that still gives every CU (256 of them) at least ~2 tiles of work.
-  const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-  const int64_t t128x256 = ((M + 127) / 128) * ((N + 255) / 256);
-  if (t256 >= 512) return launch_bf16<2, 2, 4, 4, OutT>(X, W, C, M, N, K, ep, stream);
-  if (t128x256 >= 384) return launch_bf16<2, 2, 2, 4, OutT>(X, W, C, M, N, K, ep, stream);
-  return launch_bf16<2, 2, 2, 2, OutT>(X, W, C, M, N, K, ep, stream);
+  const bool aligned = (((uintptr_t)X | (uintptr_t)W) & 15) == 0;
+  int epi = (ep.bias ? E_BIAS : 0) | (ep.gelu ? E_GELU : 0) | (ep.resid ? E_RESID : 0) | (ep.dact_in ? E_DACT : 0) |
+            (ep.preact_out ? E_PRE : 0) | (ep.accumulate ? E_ACC : 0);
+  if (K % 64 == 0 && aligned && ep.scale == 1.0f) {
+    if constexpr (std::is_same<OutT, float>::value) {
+      if (epi == 0) return launch_fast<float, 0>(X, W, C, M, N, K, ep, stream);
+      if (epi == E_ACC) return launch_fast<float, E_ACC>(X, W, C, M, N, K, ep, stream);
+    } else {
+      switch (epi) {
+        case 0: return launch_fast<bf16_t, 0>(X, W, C, M, N, K, ep, stream);
+        case E_BIAS: return launch_fast<bf16_t, E_BIAS>(X, W, C, M, N, K, ep, stream);
+        case E_BIAS | E_GELU: return launch_fast<bf16_t, E_BIAS | E_GELU>(X, W, C, M, N, K, ep, stream);
+        case E_BIAS | E_RESID: return launch_fast<bf16_t, E_BIAS | E_RESID>(X, W, C, M, N, K, ep, stream);
+        case E_BIAS | E_GELU | E_PRE: return launch_fast<bf16_t, E_BIAS | E_GELU | E_PRE>(X, W, C, M, N, K, ep, stream);
+        case E_DACT: return launch_fast<bf16_t, E_DACT>(X, W, C, M, N, K, ep, stream);
+        default: break;
+      }
+    }
+  }
+  return launch_generic<OutT>(X, W, C, M, N, K, ep, stream);
 }
 
 }  // namespace

@@ -92,10 +92,24 @@ __device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
   *(uint4*)p = t;
 }
 
-// exact GELU: x * Phi(x), and its derivative Phi(x) + x * phi(x)
-__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute error <= 1.5e-7, far
+// below the fp32 tolerance of the layer): one exp, one reciprocal and five FMAs instead of the
+// library routine, which would otherwise dominate the FFN epilogue.
+__device__ __forceinline__ float erf_fast(float x) {
+  const float ax = fabsf(x);
+  const float t = __frcp_rn(fmaf(0.3275911f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float y = 1.0f - p * t * __expf(-ax * ax);
+  return copysignf(y, x);
+}
+
+// GELU in the erf form, x * Phi(x), and its derivative Phi(x) + x * phi(x)
+__device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erf_fast(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_grad_f(float x) {
-  return 0.5f * (1.0f + erff(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
+  return 0.5f * (1.0f + erf_fast(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

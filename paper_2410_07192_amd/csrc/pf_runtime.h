@@ -63,4 +63,11 @@ struct pf_ctx {
   int64_t replica_base = 0;       // replicas completed by earlier passes over a cyclic plan
   // the hidden states currently carried come from here when the next node starts a replica
   int32_t device = 0;
+  // optional per-kernel-class timing with HIP events on the launching stream
+  struct TimedPair { hipEvent_t a, b; int32_t cls; };
+  uint32_t timing_mask = 0;
+  std::vector<TimedPair> timing_pool;
+  size_t timing_used = 0;
+  int64_t cls_count[PF_KERNEL_CLASSES] = {};
+  double cls_ms[PF_KERNEL_CLASSES] = {};
 };

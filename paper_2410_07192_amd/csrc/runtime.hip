@@ -171,6 +171,10 @@ int32_t pf_ctx_destroy(pf_ctx* c) {
   for (hipEvent_t ev : c->slot_ready) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->slot_free) if (ev) (void)hipEventDestroy(ev);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  for (auto& p : c->timing_pool) {
+    if (p.a) (void)hipEventDestroy(p.a);
+    if (p.b) (void)hipEventDestroy(p.b);
+  }
   delete c;
   return PF_OK;
 }
@@ -242,31 +246,84 @@ static int32_t acquire_layer(pf_ctx* c, int32_t layer, hipStream_t fs, int32_t* 
   return PF_OK;
 }
 
+// ---- optional event timing of kernel classes ---------------------------------------------------------
+struct TimedScope {
+  pf_ctx* c;
+  hipStream_t st;
+  hipEvent_t end = nullptr;
+  TimedScope(pf_ctx* ctx, int32_t cls, hipStream_t s) : c(ctx), st(s) {
+    if (!((c->timing_mask >> cls) & 1u) || c->timing_used >= c->timing_pool.size()) return;
+    pf_ctx::TimedPair& p = c->timing_pool[c->timing_used];
+    if (hipEventRecord(p.a, st) != hipSuccess) return;
+    p.cls = cls;
+    end = p.b;
+    ++c->timing_used;
+  }
+  ~TimedScope() {
+    if (end) (void)hipEventRecord(end, st);
+  }
+};
+
+static int32_t drain_timing(pf_ctx* c) {
+  PF_HIP(hipDeviceSynchronize());
+  for (size_t i = 0; i < c->timing_used; ++i) {
+    float ms = 0.f;
+    const pf_ctx::TimedPair& p = c->timing_pool[i];
+    if (hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+      c->cls_count[p.cls] += 1;
+      c->cls_ms[p.cls] += ms;
+    }
+  }
+  c->timing_used = 0;
+  return PF_OK;
+}
+
 // ---- one layer, one microbatch -------------------------------------------------------------------
 static int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st) {
   const pf_model_desc& m = c->md;
   const int64_t* o = c->lay.off;
   const int64_t T = c->lay.tokens;
   const int32_t d = m.d_model, f = m.d_ff, dt = m.dtype;
-  PF_HIP(pf::layernorm_fwd(dt, x_in, wb + o[0], wb + o[1], c->ws_ln, nullptr, nullptr, T, d, m.eps, st));
+  {
+    TimedScope t(c, PF_K_LAYERNORM, st);
+    PF_HIP(pf::layernorm_fwd(dt, x_in, wb + o[0], wb + o[1], c->ws_ln, nullptr, nullptr, T, d, m.eps, st));
+  }
   pf::GemmEpilogue e1;
   e1.bias = wb + o[3];
-  PF_HIP(pf::gemm_nt(dt, c->ws_ln, wb + o[2], c->ws_qkv, T, 3 * d, d, e1, st));
-  PF_HIP(pf::attention_fwd(dt, c->ws_qkv, c->ws_attn, nullptr, m.batch, m.seq_len, m.n_heads, d / m.n_heads,
-                           m.causal, st));
+  {
+    TimedScope t(c, PF_K_GEMM_QKV, st);
+    PF_HIP(pf::gemm_nt(dt, c->ws_ln, wb + o[2], c->ws_qkv, T, 3 * d, d, e1, st));
+  }
+  {
+    TimedScope t(c, PF_K_ATTENTION, st);
+    PF_HIP(pf::attention_fwd(dt, c->ws_qkv, c->ws_attn, nullptr, m.batch, m.seq_len, m.n_heads, d / m.n_heads,
+                             m.causal, st));
+  }
   pf::GemmEpilogue e2;
   e2.bias = wb + o[5];
   e2.resid = x_in;
-  PF_HIP(pf::gemm_nt(dt, c->ws_attn, wb + o[4], x_out, T, d, d, e2, st));
-  PF_HIP(pf::layernorm_fwd(dt, x_out, wb + o[6], wb + o[7], c->ws_ln, nullptr, nullptr, T, d, m.eps, st));
+  {
+    TimedScope t(c, PF_K_GEMM_OUT, st);
+    PF_HIP(pf::gemm_nt(dt, c->ws_attn, wb + o[4], x_out, T, d, d, e2, st));
+  }
+  {
+    TimedScope t(c, PF_K_LAYERNORM, st);
+    PF_HIP(pf::layernorm_fwd(dt, x_out, wb + o[6], wb + o[7], c->ws_ln, nullptr, nullptr, T, d, m.eps, st));
+  }
   pf::GemmEpilogue e3;
   e3.bias = wb + o[9];
   e3.gelu = 1;
-  PF_HIP(pf::gemm_nt(dt, c->ws_ln, wb + o[8], c->ws_mid, T, f, d, e3, st));
+  {
+    TimedScope t(c, PF_K_GEMM_FFN1, st);
+    PF_HIP(pf::gemm_nt(dt, c->ws_ln, wb + o[8], c->ws_mid, T, f, d, e3, st));
+  }
   pf::GemmEpilogue e4;
   e4.bias = wb + o[11];
   e4.resid = x_out;
-  PF_HIP(pf::gemm_nt(dt, c->ws_mid, wb + o[10], x_out, T, d, f, e4, st));
+  {
+    TimedScope t(c, PF_K_GEMM_FFN2, st);
+    PF_HIP(pf::gemm_nt(dt, c->ws_mid, wb + o[10], x_out, T, d, f, e4, st));
+  }
   return PF_OK;
 }
 
@@ -601,6 +658,36 @@ int32_t pf_ctx_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, in
   (void)what; (void)layer; (void)dst; (void)dst_bytes; (void)stream;
   if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_read_params: null context");
   return pf::fail(PF_ERR_STATE, "pf_ctx_read_params: not a training context");
+}
+
+int32_t pf_ctx_kernel_timing(pf_ctx* c, uint32_t mask) {
+  if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_kernel_timing: null context");
+  if (mask && c->timing_pool.empty()) {
+    c->timing_pool.resize(16384);
+    for (auto& p : c->timing_pool) {
+      p.a = p.b = nullptr;
+      PF_HIP(hipEventCreate(&p.a));
+      PF_HIP(hipEventCreate(&p.b));
+    }
+  }
+  int32_t rc = drain_timing(c);
+  if (rc != PF_OK) return rc;
+  for (int i = 0; i < PF_KERNEL_CLASSES; ++i) {
+    c->cls_count[i] = 0;
+    c->cls_ms[i] = 0.0;
+  }
+  c->timing_mask = mask;
+  return PF_OK;
+}
+
+int32_t pf_ctx_kernel_stats(pf_ctx* c, int32_t cls, int64_t* count, int64_t* total_ns) {
+  if (!c || cls < 0 || cls >= PF_KERNEL_CLASSES || !count || !total_ns)
+    return pf::fail(PF_ERR_ARG, "pf_ctx_kernel_stats: bad argument");
+  int32_t rc = drain_timing(c);
+  if (rc != PF_OK) return rc;
+  *count = c->cls_count[cls];
+  *total_ns = (int64_t)(c->cls_ms[cls] * 1e6);
+  return PF_OK;
 }
 
 // ---- single kernels --------------------------------------------------------------------------------
