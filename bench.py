@@ -27,6 +27,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
 
 
 def gemm_flops(M, N, K):
@@ -108,7 +109,7 @@ def main():
         t_plan += time.perf_counter() - t0
         stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, replicas=k, cursor=C.c_int32(0)))
 
-    timed_mask = (1 << pf.PF_K_GEMM_QKV) | (1 << pf.PF_K_GEMM_FFN1)
+    timed_mask = 0x7f            # every kernel class of a layer visit
 
     def run_step(i):
         st = stages[i % p]
@@ -127,25 +128,48 @@ def main():
         s = run_step(i)
         for k_ in agg:
             agg[k_] += s[k_]
+        model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)      # folds this step's event pairs into the totals
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
     tokens = agg["replicas_done"] * shape.tokens
     value = tokens / (agg["offered_ns"] * 1e-9)
 
-    # dominant kernel: the 256x256-tile bf16 GEMM (fused QKV projection and first FFN matrix)
+    # per-kernel-class rates from the HIP events recorded on the fill stream during the timed steps
     T, d, f = shape.tokens, shape.d_model, shape.d_ff
-    n_q, ns_q = model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_QKV)
-    n_f, ns_f = model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)
-    flops = n_q * gemm_flops(T, 3 * d, d) + n_f * gemm_flops(T, f, d)
-    achieved = flops / max(1, ns_q + ns_f) * 1e-3            # TFLOP/s
-    roofline = {"bound": "mfma", "achieved": achieved, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": achieved / BF16_PEAK_TFLOPS, "traffic": None,
-                "kernel": "gemm_bf16_nt_kernel<2,4,4,2> 256x256 tile (QKV and FFN1 GEMMs)",
-                "launches": n_q + n_f, "avg_us": (ns_q + ns_f) / max(1, n_q + n_f) * 1e-3}
+    att_flops = 4.0 * shape.batch * shape.seq_len ** 2 * d * (0.5 if shape.causal else 1.0)
+    esz = 2
+    classes = [
+        ("gemm_qkv", pf.PF_K_GEMM_QKV, "mfma", gemm_flops(T, 3 * d, d)),
+        ("gemm_out", pf.PF_K_GEMM_OUT, "mfma", gemm_flops(T, d, d)),
+        ("gemm_ffn1", pf.PF_K_GEMM_FFN1, "mfma", gemm_flops(T, f, d)),
+        ("gemm_ffn2", pf.PF_K_GEMM_FFN2, "mfma", gemm_flops(T, d, f)),
+        ("attention", pf.PF_K_ATTENTION, "mfma", att_flops),
+        ("layernorm", pf.PF_K_LAYERNORM, "hbm", 2.0 * T * d * esz),       # read x, write y
+        ("embed", pf.PF_K_EMBED, "hbm", 2.0 * T * d * esz + T * 4),        # gather row, write row, ids
+    ]
+    kernels = {}
+    for name_, cls, bound, work in classes:
+        n_, ns_ = model.ctx.pf_ctx_kernel_stats(cls)
+        if n_ == 0:
+            continue
+        avg_s = ns_ * 1e-9 / n_
+        if bound == "mfma":
+            kernels[name_] = {"bound": "mfma", "achieved": work / avg_s * 1e-12, "peak": BF16_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": work / avg_s * 1e-12 / BF16_PEAK_TFLOPS,
+                              "launches": n_, "avg_us": avg_s * 1e6}
+        else:
+            kernels[name_] = {"bound": "hbm", "achieved": work / avg_s * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": work / avg_s * 1e-9 / HBM_PEAK_GBS, "launches": n_, "avg_us": avg_s * 1e6}
+    # dominant kernel: the first FFN matrix (256x256-tile bf16 MFMA GEMM with the bias+GELU epilogue),
+    # the longest launch of a layer visit; algorithmic work = 2*M*N*K with M=tokens, N=d_ff, K=d_model
+    dom = kernels["gemm_ffn1"]
+    roofline = {"bound": "mfma", "achieved": dom["achieved"], "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": dom["frac"], "traffic": None,
+                "kernel": "gemm_bf16_nt_kernel<2,4,4,2,bf16_t,3> (FFN1: M=%d N=%d K=%d, bias+GELU)" % (T, f, d),
+                "launches": dom["launches"], "avg_us": dom["avg_us"]}
 
-    layer_flops = gemm_flops(T, 3 * d, d) + gemm_flops(T, d, d) + 2 * gemm_flops(T, f, d) + \
-        4.0 * shape.batch * shape.seq_len ** 2 * d * (0.5 if shape.causal else 1.0)
+    layer_flops = gemm_flops(T, 3 * d, d) + gemm_flops(T, d, d) + 2 * gemm_flops(T, f, d) + att_flops
     out = {
         "metric": "fill tokens/s in bubbles", "value": value, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
@@ -162,7 +186,7 @@ def main():
         "fill_tflops_in_bubbles": agg["replicas_done"] * shape.n_layers * layer_flops / (agg["offered_ns"] * 1e-9) * 1e-12,
         "replicas_done": agg["replicas_done"], "chunks_run": agg["chunks_run"],
         "chain_ms": chain_ns * 1e-6, "planner_ms_all_stages": t_plan * 1e3,
-        "roofline": roofline,
+        "roofline": roofline, "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs)

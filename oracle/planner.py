@@ -252,4 +252,34 @@ def chain_nodes(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, 
             nodes.append((OP_LAYER_FWD, l, 0, g, persistent + ws_fwd))
         nodes.append((OP_FINAL_LN, -1, 0, g, persistent))
         return nodes
-    raise NotImplementedError("training chains")
+    # Training: the job copies every parameter into its own memory and keeps, for its whole life,
+    # fp32 master weights, Adam moments and gradient accumulators, working and transposed copies in
+    # the storage type, one checkpoint per layer input and microbatch, and the workspaces of the
+    # recomputing backward; every node therefore reports the same footprint.
+    L = n_layers
+    sizes = (d, d, 3 * d * d, 3 * d, d * d, d, d, d, f * d, f, d * f, d)
+    blob32 = sum(_al256(n * 4) for n in sizes)
+    wt = sum(_al256(n * esize) for n in (3 * d * d, d * d, f * d, d * f))
+    mid = _al256(tokens * f * esize)
+    vp = -(-vocab // 64) * 64
+    total = ws_fwd
+    total += L * (blob + wt + 4 * blob32)
+    emb32 = _al256(vp * d * 4) + _al256(seq * d * 4) + 2 * _al256(d * 4)
+    total += 2 * _al256(vp * d * esize) + _al256(seq * d * esize) + 2 * _al256(d * esize) + 4 * emb32
+    total += g * (L + 1) * act + g * act + g * act                 # checkpoints, running gradient, head input
+    lse = _al256(batch * n_heads * seq * 4)
+    stat = _al256(tokens * 4)
+    total += 2 * act + mid + 2 * lse + 6 * stat                    # recompute outputs and statistics
+    t_a = _al256(max(tokens * f, 3 * tokens * d) * esize)
+    total += mid + 3 * act + 2 * act + t_a + mid                   # backward tensors and the two transposes
+    total += _al256(256 * 4 * 2 * d * 4)                           # LayerNorm-backward partial sums
+    total += 2 * _al256(tokens * vp * esize) + 256                 # logits, their transpose, loss cell
+    nodes.append((OP_EMBED, -1, 0, g, total))
+    for l in range(L):
+        nodes.append((OP_LAYER_FWD, l, 0, g, total))
+    nodes.append((OP_FINAL_LN, -1, 0, g, total))
+    nodes.append((OP_HEAD_LOSS, -1, 0, g, total))
+    for l in reversed(range(L)):
+        nodes.append((OP_LAYER_BWD, l, 0, g, total))
+    nodes.append((OP_OPT, -1, 0, g, total))
+    return nodes

@@ -393,3 +393,38 @@ def pf_op_attention(dtype, qkv, out, B, S, h, dh, causal, lse=None, stream=None)
 
 def pf_op_embed(dtype, ids, tok, pos, x, tokens, S, d, V, stream=None):
     _check(lib.pf_op_embed(dtype, ids, tok, pos, x, tokens, S, d, V, stream))
+
+
+def unpack_layer_blob_f32(md, raw):
+    """fp32 layer blob as returned by pf_ctx_read_params (uint8 or float32 array) -> dict of float32 arrays
+    in the mathematical layout ([in, out] matrices)."""
+    md32 = pf_model_desc.from_buffer_copy(md)
+    md32.dtype = PF_DTYPE_F32
+    size, off = pf_layer_blob_layout(md32)
+    raw = np.ascontiguousarray(raw).view(np.uint8).reshape(-1)
+    d, f = md.d_model, md.d_ff
+    shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (3 * d, d), "b_qkv": (3 * d,), "w_o": (d, d), "b_o": (d,),
+              "ln2_g": (d,), "ln2_b": (d,), "w_1": (f, d), "b_1": (f,), "w_2": (d, f), "b_2": (d,)}
+    out = {}
+    for i, name in enumerate(_BLOB_ORDER):
+        n = int(np.prod(shapes[name]))
+        a = raw[off[i]:off[i] + 4 * n].view(np.float32).reshape(shapes[name])
+        out[name] = a.T.copy() if a.ndim == 2 else a.copy()
+    return out, size
+
+
+def unpack_embedding_f32(md, raw):
+    """fp32 tok | pos | lnf_g | lnf_b block of pf_ctx_read_params(layer=-1) -> dict."""
+    raw = np.ascontiguousarray(raw).view(np.uint8).reshape(-1)
+    al = lambda x: (x + 255) // 256 * 256
+    vp = (md.vocab + 63) // 64 * 64
+    d, S = md.d_model, md.seq_len
+    o1 = al(vp * d * 4)
+    o2 = o1 + al(S * d * 4)
+    o3 = o2 + al(d * 4)
+    total = o3 + al(d * 4)
+    tok = raw[0:vp * d * 4].view(np.float32).reshape(vp, d)
+    return dict(tok_emb=tok[:md.vocab].copy(), tok_pad=tok[md.vocab:].copy(),
+                pos_emb=raw[o1:o1 + S * d * 4].view(np.float32).reshape(S, d).copy(),
+                lnf_g=raw[o2:o2 + d * 4].view(np.float32).copy(),
+                lnf_b=raw[o3:o3 + d * 4].view(np.float32).copy()), total

@@ -41,4 +41,32 @@ hipError_t attention_fwd(int32_t dtype, const void* qkv, void* out, float* lse, 
 hipError_t embed_fwd(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
                      int64_t tokens, int32_t S, int32_t d, int32_t V, hipStream_t stream);
 
+// ---- training-only kernels -----------------------------------------------------------------------------
+// out[c][r] = in[r][c]
+hipError_t transpose2d(int32_t dtype, const void* in, void* out, int64_t R, int64_t C, hipStream_t stream);
+// acc[n] += sum over rows of x[row][n]   (fp32 atomics)
+hipError_t colsum_add(int32_t dtype, const void* x, float* acc, int64_t rows, int64_t N, hipStream_t stream);
+// LayerNorm backward: dx = LN'(dy) (+ resid), dg += sum dy*xhat, db += sum dy.  dx may alias resid or dy.
+// partial: fp32 scratch of LN_BWD_MAX_BLOCKS * 4 * 2 * d elements.
+constexpr int64_t LN_BWD_MAX_BLOCKS = 256;
+hipError_t layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
+                         const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
+                         int64_t rows, int32_t d, hipStream_t stream);
+// Attention backward from the saved log-sum-exp.  dqkv: [B*S][3*d] like qkv; Dsum: fp32 [B][h][S] scratch.
+hipError_t attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* dout, const float* lse,
+                         float* Dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
+                         hipStream_t stream);
+// In place on logits [tokens][pitch]: (softmax - onehot(next token)) * inv_n; loss_sum += -log p[target].
+hipError_t ce_loss_inplace(int32_t dtype, void* logits, const int32_t* ids, float* loss_sum, int64_t tokens,
+                           int64_t pitch, int32_t V, int32_t S, float inv_n, hipStream_t stream);
+hipError_t embed_bwd(int32_t dtype, const void* dx, const int32_t* ids, float* dtok, float* dpos, int64_t tokens,
+                     int32_t S, int32_t d, int32_t V, hipStream_t stream);
+// Adam with bias correction on fp32 arrays; g holds the sum over `accum` microbatches and is cleared.
+hipError_t adam_update(float* theta, float* m, float* v, float* g, int64_t n, float lr, float b1, float b2, float eps,
+                       int64_t step, int32_t accum, hipStream_t stream);
+// fp32 [R][C] -> dst [R][C] in `dtype` and, if dst_t is not null, dst_t [C][R]
+hipError_t cast_from_f32(int32_t dtype, const float* src, void* dst, void* dst_t, int64_t R, int64_t C,
+                         hipStream_t stream);
+hipError_t widen_to_f32(int32_t dtype, const void* src, float* dst, int64_t n, hipStream_t stream);
+
 }  // namespace pf

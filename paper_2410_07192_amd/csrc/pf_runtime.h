@@ -28,6 +28,40 @@ struct Layout {
 
 int32_t make_layout(const pf_model_desc& md, const pf_exec_config& cfg, Layout* out);
 
+// Everything a training context (or the emulated main-job stage) keeps in its arena.
+struct TrainState {
+  int64_t Vp = 0;                       // vocabulary padded to a multiple of 64 (0: no embedding / head)
+  int64_t blob32 = 0, off32[12] = {};   // fp32 layer layout (master weights, Adam moments, gradients)
+  int64_t wt_off[4] = {}, wt_bytes = 0; // transposed w_qkv, w_o, w_1, w_2 inside a layer's transposed block
+  int64_t emb32_off[4] = {}, emb32 = 0; // fp32 tok | pos | lnf_g | lnf_b
+  std::vector<char*> Wk, Wt;            // working weights (model dtype, blob layout) and transposed matrices
+  std::vector<float*> master, m, v, grad;
+  char *E_w = nullptr, *Et = nullptr, *pos_w = nullptr, *lnf_g_w = nullptr, *lnf_b_w = nullptr;
+  float *embM = nullptr, *embm = nullptr, *embv = nullptr, *embg = nullptr;
+  char *ckpt = nullptr, *G = nullptr, *Hf = nullptr;
+  char *ln2 = nullptr, *x1 = nullptr, *u = nullptr, *d_mid = nullptr, *d_qkv = nullptr, *d_attn = nullptr,
+       *d_ln = nullptr, *tA = nullptr, *tB = nullptr, *logits = nullptr, *logitsT = nullptr;
+  float *lse = nullptr, *Dsum = nullptr, *stats = nullptr, *ln_partial = nullptr, *loss = nullptr;
+  int64_t stat_stride = 0;              // floats between the six per-token statistic arrays
+  int64_t mb_accum = 0;                 // microbatches accumulated since the last optimizer step
+  int64_t steps = 0;                    // optimizer steps taken
+  int64_t loss_count = 0;               // HEAD_LOSS evaluations since the loss was last read
+};
+
+int64_t train_arena_bytes(const pf_model_desc& md, const pf_exec_config& cfg, const Layout& lay);
+
+}  // namespace pf
+
+struct pf_ctx;
+namespace pf {
+int32_t train_create(pf_ctx* c, const pf_weights* w, char* base, hipStream_t st);
+void train_destroy(pf_ctx* c);
+int32_t train_fwd_node(pf_ctx* c, const pf_node& n, int64_t replica, hipStream_t st);
+int32_t train_bwd_node(pf_ctx* c, const pf_node& n, int64_t replica, const void* grad_in, hipStream_t st);
+int32_t train_main_step(pf_ctx* c, int32_t instr, int32_t index, const void* io, hipStream_t st);
+int32_t train_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, hipStream_t st);
+// one pre-LN layer forward for one microbatch with the weights at wb (blob layout)
+int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st);
 }  // namespace pf
 
 struct pf_ctx {
@@ -63,6 +97,7 @@ struct pf_ctx {
   int64_t replica_base = 0;       // replicas completed by earlier passes over a cyclic plan
   // the hidden states currently carried come from here when the next node starts a replica
   int32_t device = 0;
+  pf::TrainState* tr = nullptr;   // training contexts only
   // optional per-kernel-class timing with HIP events on the launching stream
   struct TimedPair { hipEvent_t a, b; int32_t cls; };
   uint32_t timing_mask = 0;

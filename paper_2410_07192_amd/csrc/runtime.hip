@@ -35,7 +35,7 @@ static bool bad_model(const pf_model_desc* m) {
 }
 
 static bool bad_cfg(const pf_exec_config* c) {
-  return !c || c->g < 1 || (c->streamed && c->n_slots < 2) || c->n_slots < 0;
+  return !c || c->g < 1 || (c->streamed && c->n_slots < 2) || c->n_slots < 0 || (c->training && c->streamed);
 }
 
 int32_t make_layout(const pf_model_desc& md, const pf_exec_config& cfg, Layout* L) {
@@ -58,6 +58,14 @@ int32_t make_layout(const pf_model_desc& md, const pf_exec_config& cfg, Layout* 
               align_up(L->tokens * f * e, 256) /*FFN mid*/;
   L->total = L->slots + L->carried + L->ws_fwd;
   L->resident = L->emb + (cfg.streamed ? 0 : (int64_t)md.n_layers * L->blob);
+  if (cfg.training) {
+    // a training context copies every parameter into its arena and keeps checkpoints instead of one
+    // carried tensor
+    L->slots = 0;
+    L->carried = 0;
+    L->resident = 0;
+    L->total = L->ws_fwd + train_arena_bytes(md, cfg, *L);
+  }
   return PF_OK;
 }
 
@@ -90,7 +98,8 @@ int32_t pf_build_chain(const pf_model_desc* model, const pf_exec_config* cfg, pf
                        int32_t* n_out) {
   if (pf::bad_model(model) || pf::bad_cfg(cfg) || !n_out || cap < 0 || (cap > 0 && !out))
     return pf::fail(PF_ERR_ARG, "pf_build_chain: bad argument");
-  if (cfg->training) return pf::fail(PF_ERR_STATE, "pf_build_chain: training chains are not available in this build");
+  if (cfg->training && model->vocab == 0)
+    return pf::fail(PF_ERR_ARG, "pf_build_chain: a training fill job needs a vocabulary (embedding and tied head)");
   Layout L;
   pf::make_layout(*model, *cfg, &L);
   const int64_t persistent = L.resident + L.slots + L.carried;
@@ -99,6 +108,19 @@ int32_t pf_build_chain(const pf_model_desc* model, const pf_exec_config* cfg, pf
     if (n < cap) out[n] = pf_node{0, mem, op, layer, 0, cfg->g};
     ++n;
   };
+  if (cfg->training) {
+    // the whole arena (parameters, optimizer state, checkpoints, workspaces) stays allocated for the
+    // life of the job, so every node reports it
+    put(PF_OP_EMBED, -1, L.total);
+    for (int32_t l = 0; l < model->n_layers; ++l) put(PF_OP_LAYER_FWD, l, L.total);
+    put(PF_OP_FINAL_LN, -1, L.total);
+    put(PF_OP_HEAD_LOSS, -1, L.total);
+    for (int32_t l = model->n_layers - 1; l >= 0; --l) put(PF_OP_LAYER_BWD, l, L.total);
+    put(PF_OP_OPT, -1, L.total);
+    *n_out = n;
+    if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_build_chain: %d nodes, capacity %d", n, cap);
+    return PF_OK;
+  }
   if (model->vocab > 0) put(PF_OP_EMBED, -1, persistent);
   for (int32_t l = 0; l < model->n_layers; ++l) put(PF_OP_LAYER_FWD, l, persistent + L.ws_fwd);
   put(PF_OP_FINAL_LN, -1, persistent);
@@ -112,8 +134,10 @@ int32_t pf_ctx_create(const pf_model_desc* model, const pf_exec_config* cfg, con
   if (pf::bad_model(model) || pf::bad_cfg(cfg) || !w || !w->layers || !arena || arena_bytes <= 0 || !out)
     return pf::fail(PF_ERR_ARG, "pf_ctx_create: bad argument");
   if (((uintptr_t)arena & 255) != 0) return pf::fail(PF_ERR_ARG, "pf_ctx_create: arena must be 256-byte aligned");
-  if (cfg->training) return pf::fail(PF_ERR_STATE, "pf_ctx_create: training contexts are not available in this build");
-  if (!w->lnf_g || !w->lnf_b || (model->vocab > 0 && (!w->tok_emb || !w->pos_emb)))
+  if (cfg->training && adam && (adam->accum < 1 || !(adam->lr >= 0.f)))
+    return pf::fail(PF_ERR_ARG, "pf_ctx_create: bad Adam constants");
+  if (((!cfg->training || model->vocab > 0) && (!w->lnf_g || !w->lnf_b)) ||
+      (model->vocab > 0 && (!w->tok_emb || !w->pos_emb)))
     return pf::fail(PF_ERR_ARG, "pf_ctx_create: missing embedding / final LayerNorm pointers");
   for (int32_t l = 0; l < model->n_layers; ++l)
     if (!w->layers[l]) return pf::fail(PF_ERR_ARG, "pf_ctx_create: layer %d pointer is null", l);
@@ -124,7 +148,7 @@ int32_t pf_ctx_create(const pf_model_desc* model, const pf_exec_config* cfg, con
   if (!c) return pf::fail(PF_ERR_NOMEM, "pf_ctx_create: host allocation failed");
   c->md = *model;
   c->cfg = *cfg;
-  if (adam) c->adam = *adam;
+  c->adam = adam ? *adam : pf_adam{1e-4f, 0.9f, 0.999f, 1e-8f, 4};
   pf::make_layout(*model, *cfg, &c->lay);
   if (arena_bytes < c->lay.total) {
     const long long need = (long long)c->lay.total;
@@ -144,8 +168,15 @@ int32_t pf_ctx_create(const pf_model_desc* model, const pf_exec_config* cfg, con
   c->ws_ln = p; p += c->lay.act;
   c->ws_qkv = p; p += 3 * c->lay.act;
   c->ws_attn = p; p += c->lay.act;
-  c->ws_mid = p;
+  c->ws_mid = p; p += c->lay.ws_fwd - 5 * c->lay.act;
   hipError_t e = hipGetDevice(&c->device);
+  if (e == hipSuccess && cfg->training) {
+    int32_t rc = pf::train_create(c, w, p, nullptr);
+    if (rc != PF_OK) {
+      pf_ctx_destroy(c);
+      return rc;
+    }
+  }
   if (e == hipSuccess && cfg->streamed) {
     c->slot_layer.assign(cfg->n_slots, -1);
     c->slot_free_valid.assign(cfg->n_slots, 0);
@@ -171,6 +202,7 @@ int32_t pf_ctx_destroy(pf_ctx* c) {
   for (hipEvent_t ev : c->slot_ready) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->slot_free) if (ev) (void)hipEventDestroy(ev);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  if (c->tr) pf::train_destroy(c);
   for (auto& p : c->timing_pool) {
     if (p.a) (void)hipEventDestroy(p.a);
     if (p.b) (void)hipEventDestroy(p.b);
@@ -279,7 +311,9 @@ static int32_t drain_timing(pf_ctx* c) {
 }
 
 // ---- one layer, one microbatch -------------------------------------------------------------------
-static int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st) {
+}  // extern "C"
+
+int32_t pf::layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st) {
   const pf_model_desc& m = c->md;
   const int64_t* o = c->lay.off;
   const int64_t T = c->lay.tokens;
@@ -327,6 +361,8 @@ static int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* 
   return PF_OK;
 }
 
+extern "C" {
+
 static int32_t check_chunk(const pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, int64_t cap,
                            const char* who) {
   if (!c || !ch || !F || nF <= 0) return pf::fail(PF_ERR_ARG, "%s: null argument", who);
@@ -359,6 +395,15 @@ int32_t pf_fill_chunk_fwd(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32
   const pf_model_desc& m = c->md;
   const int32_t g = c->cfg.g;
   const int64_t act = c->lay.act, T = c->lay.tokens;
+  if (c->tr) {
+    if (act_in || act_out)
+      return pf::fail(PF_ERR_ARG, "pf_fill_chunk_fwd: act_in / act_out are not supported for training contexts");
+    for (int32_t j = ch->node_begin; j < ch->node_end; ++j) {
+      rc = pf::train_fwd_node(c, F[j % nF], c->replica_base + j / nF, st);
+      if (rc != PF_OK) return rc;
+    }
+    return PF_OK;
+  }
   const void* last_out = c->X;
   for (int32_t j = ch->node_begin; j < ch->node_end; ++j) {
     const pf_node& n = F[j % nF];
@@ -392,7 +437,7 @@ int32_t pf_fill_chunk_fwd(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32
           wb = (const char*)c->layers[n.layer];
         }
         for (int32_t mb = 0; mb < g; ++mb) {
-          rc = layer_forward(c, wb, src + mb * act, c->X + mb * act, st);
+          rc = pf::layer_forward(c, wb, src + mb * act, c->X + mb * act, st);
           if (rc != PF_OK) return rc;
         }
         if (slot >= 0) {
@@ -422,10 +467,24 @@ int32_t pf_fill_chunk_fwd(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32
 
 int32_t pf_fill_chunk_bwd(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, const void* grad_io,
                           void* grad_out, int64_t cap_bytes, void* fill_stream) {
-  (void)grad_io; (void)grad_out; (void)fill_stream;
   int32_t rc = check_chunk(c, ch, F, nF, cap_bytes, "pf_fill_chunk_bwd");
   if (rc != PF_OK) return rc;
-  return pf::fail(PF_ERR_STATE, "pf_fill_chunk_bwd: backward nodes are not available in this build");
+  if (!c->tr) return pf::fail(PF_ERR_STATE, "pf_fill_chunk_bwd: not a training context");
+  for (int32_t j = ch->node_begin; j < ch->node_end; ++j)
+    if (F[j % nF].op <= PF_OP_HEAD_LOSS)
+      return pf::fail(PF_ERR_STATE, "pf_fill_chunk_bwd: node %d is a forward-type node", j % nF);
+  hipStream_t st = (hipStream_t)fill_stream;
+  bool saw_layer = false;
+  for (int32_t j = ch->node_begin; j < ch->node_end; ++j) {
+    const pf_node& n = F[j % nF];
+    const void* gin = (j == ch->node_begin && n.op == PF_OP_LAYER_BWD) ? grad_io : nullptr;
+    rc = pf::train_bwd_node(c, n, c->replica_base + j / nF, gin, st);
+    if (rc != PF_OK) return rc;
+    saw_layer = saw_layer || n.op == PF_OP_LAYER_BWD;
+  }
+  if (grad_out && saw_layer)
+    PF_HIP(hipMemcpyAsync(grad_out, c->tr->G, (size_t)((int64_t)c->cfg.g * c->lay.act), hipMemcpyDeviceToDevice, st));
+  return PF_OK;
 }
 
 int32_t pf_fill_chunk(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t nF, int64_t cap_bytes,
@@ -509,11 +568,13 @@ static void wait_until(int64_t deadline) {
 }
 
 int32_t pf_main_stage_step(pf_ctx* c, int32_t instr, int32_t index, const void* io, void* main_stream) {
-  (void)index; (void)io; (void)main_stream;
-  if (!c) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: null context");
+  if (!c || !io || index < 0) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: bad argument");
   if (instr == PF_INSTR_BUBBLE)
     return pf::fail(PF_ERR_ARG, "pf_main_stage_step: the bubble instruction is executed by pf_timeline_run");
-  return pf::fail(PF_ERR_STATE, "pf_main_stage_step: the real main stage is not available in this build");
+  if (instr != PF_INSTR_FWD && instr != PF_INSTR_BWD) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: unknown instruction");
+  if (!c->tr || c->md.vocab != 0)
+    return pf::fail(PF_ERR_STATE, "pf_main_stage_step: needs a training context without vocabulary");
+  return pf::train_main_step(c, instr, index, io, (hipStream_t)main_stream);
 }
 
 int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, int32_t m, int32_t stage,
@@ -649,15 +710,26 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
 }
 
 int32_t pf_ctx_train_state(pf_ctx* c, double* loss, int64_t* steps) {
-  (void)loss; (void)steps;
   if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_train_state: null context");
-  return pf::fail(PF_ERR_STATE, "pf_ctx_train_state: not a training context");
+  if (!c->tr) return pf::fail(PF_ERR_STATE, "pf_ctx_train_state: not a training context");
+  PF_HIP(hipDeviceSynchronize());
+  if (steps) *steps = c->tr->steps;
+  if (loss) {
+    float sum = 0.f;
+    PF_HIP(hipMemcpy(&sum, c->tr->loss, sizeof sum, hipMemcpyDeviceToHost));
+    PF_HIP(hipMemset(c->tr->loss, 0, sizeof sum));
+    const double n = (double)c->tr->loss_count * c->md.batch * (c->md.seq_len - 1);
+    *loss = n > 0 ? sum / n : 0.0;
+    c->tr->loss_count = 0;
+  }
+  return PF_OK;
 }
 
 int32_t pf_ctx_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, void* stream) {
-  (void)what; (void)layer; (void)dst; (void)dst_bytes; (void)stream;
-  if (!c) return pf::fail(PF_ERR_ARG, "pf_ctx_read_params: null context");
-  return pf::fail(PF_ERR_STATE, "pf_ctx_read_params: not a training context");
+  if (!c || !dst || (what != 0 && what != 1) || layer < -1)
+    return pf::fail(PF_ERR_ARG, "pf_ctx_read_params: bad argument");
+  if (!c->tr) return pf::fail(PF_ERR_STATE, "pf_ctx_read_params: not a training context");
+  return pf::train_read_params(c, what, layer, dst, dst_bytes, (hipStream_t)stream);
 }
 
 int32_t pf_ctx_kernel_timing(pf_ctx* c, uint32_t mask) {

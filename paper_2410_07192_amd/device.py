@@ -45,10 +45,10 @@ def empty_storage(shape, md) -> torch.Tensor:
 class DeviceModel:
     """A model's parameters in the library's layout plus an execution context for one configuration."""
 
-    def __init__(self, shape, params, g=1, streamed=False, n_slots=0, batch=None):
+    def __init__(self, shape, params, g=1, streamed=False, n_slots=0, batch=None, training=False, adam=None):
         self.shape = shape
         self.md = pf.model_desc(shape, batch)
-        self.cfg = pf.pf_exec_config(g, int(streamed), n_slots, 0)
+        self.cfg = pf.pf_exec_config(g, int(streamed), n_slots, int(training))
         md = self.md
         size, _ = pf.pf_layer_blob_layout(md)
         self.blobs = []
@@ -61,16 +61,18 @@ class DeviceModel:
             self.blobs.append(t)
         self.tok = storage_tensor(params["tok_emb"], md) if shape.vocab > 0 else None
         self.pos = storage_tensor(params["pos_emb"], md) if shape.vocab > 0 else None
-        self.lnf_g = storage_tensor(params["lnf_g"], md)
-        self.lnf_b = storage_tensor(params["lnf_b"], md)
+        self.lnf_g = storage_tensor(params["lnf_g"], md) if "lnf_g" in params else None
+        self.lnf_b = storage_tensor(params["lnf_b"], md) if "lnf_b" in params else None
         self.arena_bytes = pf.pf_ctx_arena_bytes(md, self.cfg)
         self.arena = torch.empty(self.arena_bytes + 256, dtype=torch.uint8, device="cuda")
         base = (self.arena.data_ptr() + 255) // 256 * 256
         self.ctx = pf.Context(md, self.cfg, [b.data_ptr() for b in self.blobs],
                               self.tok.data_ptr() if self.tok is not None else None,
                               self.pos.data_ptr() if self.pos is not None else None,
-                              self.lnf_g.data_ptr(), self.lnf_b.data_ptr(), base, self.arena_bytes)
-        self.chain = pf.pf_build_chain(md, self.cfg)
+                              self.lnf_g.data_ptr() if self.lnf_g is not None else None,
+                              self.lnf_b.data_ptr() if self.lnf_b is not None else None, base, self.arena_bytes,
+                              adam)
+        self.chain = pf.pf_build_chain(md, self.cfg) if not (training and shape.vocab == 0) else None
         self._io = None
 
     def set_io(self, inputs: torch.Tensor, n_in: int, outputs: torch.Tensor | None, n_out: int):

@@ -1,0 +1,187 @@
+"""GPU parity of the training path (forward, tied-head loss, recomputing backward, gradient
+accumulation, Adam) and of the emulated main-job stage, against the CPU checker.
+
+Gradient tolerance: max |gpu - ref| / max |ref| per gradient tensor, 1e-4 for fp32 storage and 2e-2
+for bf16 storage (the checker gets the bf16-rounded parameters widened to float64)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import transformer as ot          # noqa: E402
+from paper_2410_07192_amd import synth        # noqa: E402
+
+
+def _mods():
+    from paper_2410_07192_amd import binding as pf
+    from paper_2410_07192_amd import device as dev
+    return pf, dev
+
+
+def rel_err(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def read_layer(m, what, layer):
+    pf, dev = _mods()
+    md32 = pf.pf_model_desc.from_buffer_copy(m.md)
+    md32.dtype = pf.PF_DTYPE_F32
+    size, _ = pf.pf_layer_blob_layout(md32)
+    buf = torch.empty(size, dtype=torch.uint8, device="cuda")
+    m.ctx.pf_ctx_read_params(what, layer, buf.data_ptr(), size)
+    m.ctx.pf_ctx_sync()
+    return pf.unpack_layer_blob_f32(m.md, buf.cpu().numpy())[0]
+
+
+def read_emb(m, what):
+    pf, dev = _mods()
+    md = m.md
+    al = lambda x: (x + 255) // 256 * 256
+    vp = (md.vocab + 63) // 64 * 64
+    size = al(vp * md.d_model * 4) + al(md.seq_len * md.d_model * 4) + 2 * al(md.d_model * 4)
+    buf = torch.empty(size, dtype=torch.uint8, device="cuda")
+    m.ctx.pf_ctx_read_params(what, -1, buf.data_ptr(), size)
+    m.ctx.pf_ctx_sync()
+    out, total = pf.unpack_embedding_f32(md, buf.cpu().numpy())
+    assert total == size
+    return out
+
+
+TRAIN_SHAPES = [
+    (synth.ModelShape(2, 64, 4, 128, 24, 2, 50, True, "f32"), 1e-4),      # d_head 16, T = 48
+    (synth.ModelShape(2, 128, 2, 256, 64, 2, 300, True, "bf16"), 2e-2),   # d_head 64, T = 128
+    (synth.ModelShape(1, 256, 2, 512, 96, 2, 130, False, "bf16"), 2e-2),  # d_head 128, encoder, T = 192
+]
+
+
+@pytest.mark.parametrize("shape,tol", TRAIN_SHAPES, ids=lambda x: getattr(x, "dtype", None) and f"{x.dtype}-d{x.d_model}" or "")
+def test_gradients_loss_and_adam(shape, tol):
+    pf, dev = _mods()
+    params = synth.make_model_params(shape, seed=31, std=0.08)
+    P = ot.cast_params(params)
+    adam = pf.pf_adam(1e-3, 0.9, 0.999, 1e-8, 2)
+    m = dev.DeviceModel(shape, params, training=True, adam=adam)
+    try:
+        ids = np.stack([synth.make_token_ids(shape, seed=50 + i)[None] for i in range(2)])   # 2 replicas, g = 1
+        d_in = dev.to_device(ids.astype(np.int32))
+        m.set_io(d_in, 2, None, 0)
+        nF = len(m.chain)
+        assert nF == 2 * shape.n_layers + 4
+        st = torch.cuda.Stream()
+        # replica 0: forward chunk, then the backward cut in two (a bubble boundary in between)
+        cut = shape.n_layers + 3
+        m.ctx.pf_fill_chunk_fwd(m.chunk(0, cut), m.chain, stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        m.ctx.pf_fill_chunk_bwd(m.chunk(cut, cut + 1), m.chain, stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        m.ctx.pf_fill_chunk(m.chunk(cut + 1, nF), m.chain, stream=st.cuda_stream)
+        loss, steps = m.ctx.pf_ctx_train_state()
+        assert steps == 0                                       # accum = 2: no optimizer step yet
+        ref_loss, G = ot.model_loss_and_grads(ids[0, 0], P, shape.n_heads, shape.causal, shape.eps, checkpoint=True)
+        assert abs(loss - ref_loss) < tol * max(1.0, abs(ref_loss))
+        for l in range(shape.n_layers):
+            got = read_layer(m, 0, l)
+            for k, ref in G["layers"][l].items():
+                assert rel_err(got[k], ref) < tol, (l, k)
+        ge = read_emb(m, 0)
+        for k in ("tok_emb", "pos_emb", "lnf_g", "lnf_b"):
+            assert rel_err(ge[k], G[k]) < tol, k
+        assert not ge["tok_pad"].any()                          # padded vocabulary rows get no gradient
+        # replica 1 through pf_fill_chunk in one go: triggers the optimizer step on the mean gradient
+        ch = m.chunk(nF, 2 * nF)
+        m.ctx.pf_fill_chunk(ch, m.chain, stream=st.cuda_stream)
+        loss2, steps = m.ctx.pf_ctx_train_state()
+        assert steps == 1
+        ref_loss2, G2 = ot.model_loss_and_grads(ids[1, 0], P, shape.n_heads, shape.causal, shape.eps)
+        assert abs(loss2 - ref_loss2) < tol * max(1.0, abs(ref_loss2))
+        # Adam on the mean of the two microbatch gradients; compare the UPDATE (theta1 - theta0)
+        for l in range(shape.n_layers):
+            got = read_layer(m, 1, l)
+            for k in G["layers"][l]:
+                gmean = 0.5 * (G["layers"][l][k] + G2["layers"][l][k])
+                th1, _, _ = ot.adam_step(P["layers"][l][k], 0.0, 0.0, gmean, 1, lr=1e-3)
+                upd_ref = th1 - P["layers"][l][k]
+                upd_got = got[k].astype(np.float64) - P["layers"][l][k]
+                # the first Adam step is -lr * g/(|g| + eps): compare where the gradient is not tiny
+                big = np.abs(gmean) > max(1e-3, 5 * tol) * np.abs(gmean).max()
+                assert np.abs(upd_got - upd_ref)[big].max() < 0.05 * 1e-3, (l, k)
+        # gradients were cleared by the step
+        assert not any(np.any(v) for v in read_layer(m, 0, 0).values())
+    finally:
+        m.close()
+
+
+def test_training_chunked_through_timeline():
+    """A training chain planned onto bubbles and run by the Executor loop lowers nothing silently:
+    optimizer steps happen and the loss is finite."""
+    import ctypes as C
+    pf, dev = _mods()
+    shape = synth.ModelShape(2, 128, 2, 256, 64, 4, 300, True, "bf16")
+    params = synth.make_model_params(shape, seed=3, std=0.05)
+    m = dev.DeviceModel(shape, params, training=True, adam=pf.pf_adam(1e-3, 0.9, 0.999, 1e-8, 2))
+    try:
+        ids = np.stack([synth.make_token_ids(shape, seed=70 + i)[None] for i in range(4)])
+        d_in = dev.to_device(ids.astype(np.int32))
+        m.set_io(d_in, 4, None, 0)
+        st, main = torch.cuda.Stream(), torch.cuda.Stream()
+        m.ctx.pf_profile_chain(m.chain, 1, 2, st.cuda_stream)
+        _, steps0 = m.ctx.pf_ctx_train_state()
+        p, mm, stage, tf, tb = 3, 4, 1, 2_000_000, 4_000_000
+        windows = pf.pf_schedule_1f1b(p, mm, stage, tf, tb, 1 << 34, True, 0)
+        plan, n_plan, k = pf.pf_plan_bubbles(windows, m.chain, 800_000, 0, 0, raw=True)
+        cursor = C.c_int32(0)
+        done = 0
+        for _ in range(4):
+            s = pf.pf_timeline_run(m.ctx, None, None, p, mm, stage, tf, tb, windows, plan, n_plan, m.chain, cursor,
+                                   st.cuda_stream, main.cuda_stream)
+            done += s["replicas_done"]
+        loss, steps = m.ctx.pf_ctx_train_state()
+        assert done >= 2 and steps - steps0 >= done // 2 - 1
+        assert np.isfinite(loss) and 0 < loss < 2 * np.log(shape.vocab)
+    finally:
+        m.close()
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", 1e-4), ("bf16", 2e-2)])
+def test_main_stage_forward_backward(dtype, tol):
+    """Emulated main-job stage: forward of two microbatches, then their backwards (1F1B order keeps
+    several microbatches in flight), against the checker's layer forward/backward."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(2, 128, 2, 256, 64, 2, 0, True, dtype)
+    params = synth.make_model_params(shape, seed=41, std=0.08)
+    P = ot.cast_params(params)
+    m = dev.DeviceModel(shape, params, g=2, training=True)
+    try:
+        xs = [synth.make_hidden(shape, seed=60 + i) for i in range(2)]
+        dys = [synth.make_hidden(shape, seed=80 + i) * (1.0 if dtype == "f32" else 1.0) for i in range(2)]
+        dxs = [dev.storage_tensor(x, m.md) for x in xs]
+        ddy = [dev.storage_tensor(x, m.md) for x in dys]
+        st = torch.cuda.Stream()
+        for j in range(2):
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, j, dxs[j].data_ptr(), st.cuda_stream)
+        for j in range(2):
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, j, ddy[j].data_ptr(), st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        Gsum = [None, None]
+        for j in range(2):
+            x = xs[j].astype(np.float64)
+            caches = []
+            for l in range(2):
+                x, c = ot.layer_forward(x, P["layers"][l], shape.n_heads, True, shape.eps, keep=True)
+                caches.append(c)
+            dx = dys[j].astype(np.float64)
+            for l in (1, 0):
+                dx, G = ot.layer_backward(dx, caches[l], P["layers"][l], shape.n_heads)
+                Gsum[l] = G if Gsum[l] is None else {k: Gsum[l][k] + G[k] for k in G}
+        for l in range(2):
+            got = read_layer(m, 0, l)
+            for k, ref in Gsum[l].items():
+                assert rel_err(got[k], ref) < tol, (l, k)
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_BUBBLE, 0, dxs[0].data_ptr(), st.cuda_stream)
+        assert e.value.code == pf.PF_ERR_ARG
+    finally:
+        m.close()

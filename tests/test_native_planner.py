@@ -166,6 +166,17 @@ def test_blob_layout_and_chain_against_checker():
             got = [(n.op, n.layer, n.mb_first, n.mb_count, n.mem_bytes) for n in chain]
             assert got == want
             assert pf.pf_ctx_arena_bytes(md, cfg) > 0
+    s = synth.WORKLOADS["cfg4"]
+    md = pf.model_desc(s)
+    for g in (1, 2):
+        cfg = pf.pf_exec_config(g, 0, 0, 1)
+        chain = pf.pf_build_chain(md, cfg)
+        want = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2, g, False, 0, True)
+        got = [(n.op, n.layer, n.mb_first, n.mb_count, n.mem_bytes) for n in chain]
+        assert got == want and len(got) == 2 * s.n_layers + 4
+        assert [n[1] for n in got if n[0] == op.OP_LAYER_BWD] == list(range(s.n_layers - 1, -1, -1))
+        assert pf.pf_ctx_arena_bytes(md, cfg) == want[0][4]
+        assert want[0][4] < 16 * synth.GIB          # the training fill job fits its 16 GiB bubble memory
 
 
 def test_context_calls_fail_loudly_without_a_device_or_with_bad_arguments():
