@@ -1,16 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the fill-job hot path on one MI355X.
 
-A step is one emulated main-job iteration of one 1F1B stage: the stage's idle windows are derived,
-the fill job's chain is profiled and partitioned onto them (Algorithm 1), and the Executor loop
-runs the planned chunks inside the windows while the main stage is emulated on the timeline.
-Steps rotate over all p stages; the headline value aggregates over them:
+A step is one emulated main-job iteration (for the explicit-bubble workload: one bubble cycle):
+the stage's idle windows are derived, the fill job's chain is profiled on the device and partitioned
+onto the windows (Algorithm 1), and the Executor loop runs the planned chunks inside the windows
+while the main stage is emulated on the timeline.  The headline value is
 
-    fill tokens/s in bubbles = tokens of fill sequences that completed every layer
+    fill tokens/s in bubbles = tokens of fill sequences that completed the whole chain
                                / summed duration of the windows offered
 
-Default workload: the 12-layer bf16 encoder inference fill job (d=768, 12 heads, FFN 3072,
-seq 512, batch 32) in the bubbles of 1F1B p=8, m=16, t_f=15 ms, t_b=30 ms with 24 GiB free.
+Workloads (--workload):
+  cfg2 (default)  12-layer bf16 encoder inference fill job, weights resident, 1F1B p=8 m=16
+                  t_f=15 ms t_b=30 ms, 24 GiB free; steps rotate over the 8 stages.
+  cfg3            24-layer d=2048 causal decoder inference, weights streamed from pinned host memory,
+                  explicit 40 ms bubbles separated by 20 ms, 8 GiB cap; g microbatches per layer
+                  visit chosen by the planner.
+  cfg4            12-layer d=1024 causal decoder TRAINING fill job (fwd + recompute/bwd + Adam,
+                  accumulation across bubbles), 1F1B p=16 m=32, 16 GiB free.
+  cfg5            real main-job stage (3 layers d=8192, fwd+bwd on its own stream) under emulated
+                  1F1B p=16 m=32 with measured t_f/t_b, the cfg3 job filling its bubbles; reports
+                  the main-stage slowdown.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -28,16 +37,22 @@ if ROOT not in sys.path:
 
 BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak
+GIB = 1 << 30
 
 
 def gemm_flops(M, N, K):
     return 2.0 * M * N * K
 
 
+def layer_fwd_flops(shape):
+    T, d, f = shape.tokens, shape.d_model, shape.d_ff
+    att = 4.0 * shape.batch * shape.seq_len ** 2 * d * (0.5 if shape.causal else 1.0)
+    return gemm_flops(T, 3 * d, d) + gemm_flops(T, d, d) + 2 * gemm_flops(T, f, d) + att
+
+
 def cpu_baseline(shape, params, ids, n_seq):
     """The CPU checker as it stands, timed on a bounded sample: n_seq sequences of the workload's
     batch through the whole model (embedding, all layers, final LayerNorm)."""
-    import numpy as np
     from oracle import transformer as ot
     try:
         from threadpoolctl import threadpool_info
@@ -54,62 +69,87 @@ def cpu_baseline(shape, params, ids, n_seq):
                       f"{shape.n_layers} layers in float64, {dt:.1f} s"}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=16)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="cfg2")
-    ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
-    ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
-    ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=4)
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the fill path has no cross-GPU step "
-              "(one independent Executor per device). Use --gpus 1.", file=sys.stderr)
-        sys.exit(2)
+def kernel_rates(ctx, pf, shape):
+    """Per-kernel-class rates from the HIP events the library recorded on the fill stream."""
+    T, d, f = shape.tokens, shape.d_model, shape.d_ff
+    att = 4.0 * shape.batch * shape.seq_len ** 2 * d * (0.5 if shape.causal else 1.0)
+    esz = 2
+    classes = [
+        ("gemm_qkv", pf.PF_K_GEMM_QKV, "mfma", gemm_flops(T, 3 * d, d)),
+        ("gemm_out", pf.PF_K_GEMM_OUT, "mfma", gemm_flops(T, d, d)),
+        ("gemm_ffn1", pf.PF_K_GEMM_FFN1, "mfma", gemm_flops(T, f, d)),
+        ("gemm_ffn2", pf.PF_K_GEMM_FFN2, "mfma", gemm_flops(T, d, f)),
+        ("attention", pf.PF_K_ATTENTION, "mfma", att),
+        ("layernorm", pf.PF_K_LAYERNORM, "hbm", 2.0 * T * d * esz),       # read x, write y
+        ("embed", pf.PF_K_EMBED, "hbm", 2.0 * T * d * esz + T * 4),        # gather row, write row, ids
+    ]
+    out = {}
+    for name, cls, bound, work in classes:
+        n, ns = ctx.pf_ctx_kernel_stats(cls)
+        if n == 0:
+            continue
+        avg_s = ns * 1e-9 / n
+        if bound == "mfma":
+            out[name] = {"bound": "mfma", "achieved": work / avg_s * 1e-12, "peak": BF16_PEAK_TFLOPS,
+                         "unit": "TFLOP/s", "frac": work / avg_s * 1e-12 / BF16_PEAK_TFLOPS, "launches": n,
+                         "avg_us": avg_s * 1e6}
+        else:
+            out[name] = {"bound": "hbm", "achieved": work / avg_s * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": work / avg_s * 1e-9 / HBM_PEAK_GBS, "launches": n, "avg_us": avg_s * 1e6}
+    return out
 
-    import numpy as np
-    import torch
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; there is no CPU fallback for the product path", file=sys.stderr)
-        sys.exit(3)
-    from paper_2410_07192_amd import binding as pf
-    from paper_2410_07192_amd import device as dev
-    from paper_2410_07192_amd import synth
 
-    name = args.workload
+def ffn1_roofline(kernels, shape, tile="2,4,4,2"):
+    dom = kernels["gemm_ffn1"]
+    return {"bound": "mfma", "achieved": dom["achieved"], "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": dom["frac"], "traffic": None,
+            "kernel": "gemm_bf16_nt_kernel<%s,bf16_t,bias+GELU> (FFN1: M=%d N=%d K=%d)" %
+                      (tile, shape.tokens, shape.d_ff, shape.d_model),
+            "launches": dom["launches"], "avg_us": dom["avg_us"]}
+
+
+AGG_KEYS = ("offered_ns", "idle_ns", "fill_busy_ns", "overrun_ns", "replicas_done", "chunks_run", "iter_ns",
+            "main_busy_ns")
+
+
+def base_line(args, metric_value, wall, extra):
+    out = {"metric": "fill tokens/s in bubbles", "value": metric_value, "unit": "tokens/s", "n_gpus": 1,
+           "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / max(1, args.steps) * 1e3,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    out.update(extra)
+    return out
+
+
+def fill_stats(agg):
+    off = max(1, agg["offered_ns"])
+    return {"pct_bubble_filled": 100.0 * agg["fill_busy_ns"] / off,
+            "pct_idle_filled": 100.0 * agg["fill_busy_ns"] / max(1, agg["idle_ns"]),
+            "overrun_pct_of_offered": 100.0 * agg["overrun_ns"] / off,
+            "replicas_done": agg["replicas_done"], "chunks_run": agg["chunks_run"]}
+
+
+# ---------------------------------------------------------------------------------------------- cfg2
+def run_cfg2(args, np, torch, pf, dev, synth):
+    name = "cfg2"
     shape = synth.WORKLOADS[name]
     p, m, tf, tb, free = synth.SCHEDULES[name]
-    cfg_index = int(name[3:]) - 1
-    params = synth.make_model_params(shape, seed=0 + 100 * cfg_index)
+    params = synth.make_model_params(shape, seed=100)
     n_ring = 4
-    ids = np.stack([synth.make_token_ids(shape, seed=1 + 100 * cfg_index + 1000 * i) for i in range(n_ring)])
-
+    ids = np.stack([synth.make_token_ids(shape, seed=101 + 1000 * i) for i in range(n_ring)])
     model = dev.DeviceModel(shape, params)
     d_in = dev.to_device(ids.astype(np.int32))
     d_out = dev.empty_storage((2, 1, shape.batch, shape.seq_len, shape.d_model), model.md)
     model.set_io(d_in, n_ring, d_out, 2)
-    fill = torch.cuda.Stream()
-    main_s = torch.cuda.Stream()
-
-    # per-node profile on this device (the profiles the Executor is handed)
+    fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
     model.ctx.pf_profile_chain(model.chain, 3, 7, fill.cuda_stream)
     chain_ns = sum(n.dur_ns for n in model.chain)
-
-    # windows and plans for every stage
-    stages = []
-    t_plan = 0.0
+    stages, t_plan = [], 0.0
     for s in range(p):
         windows = pf.pf_schedule_1f1b(p, m, s, tf, tb, free, not args.paper_mode, 2 * max(n.dur_ns for n in model.chain))
         t0 = time.perf_counter()
         plan, n_plan, k = pf.pf_plan_bubbles(windows, model.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
         t_plan += time.perf_counter() - t0
-        stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, replicas=k, cursor=C.c_int32(0)))
-
-    timed_mask = 0x7f            # every kernel class of a layer visit
+        stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, cursor=C.c_int32(0)))
 
     def run_step(i):
         st = stages[i % p]
@@ -120,9 +160,9 @@ def main():
         run_step(i)
     for st in stages:
         st["cursor"] = C.c_int32(0)
-    model.ctx.pf_ctx_kernel_timing(timed_mask)
+    model.ctx.pf_ctx_kernel_timing(0x7f)
     torch.cuda.synchronize()
-    agg = dict(offered_ns=0, idle_ns=0, fill_busy_ns=0, overrun_ns=0, replicas_done=0, chunks_run=0, iter_ns=0)
+    agg = dict.fromkeys(AGG_KEYS, 0)
     t0 = time.perf_counter()
     for i in range(args.steps):
         s = run_step(i)
@@ -131,66 +171,281 @@ def main():
         model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)      # folds this step's event pairs into the totals
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-
     tokens = agg["replicas_done"] * shape.tokens
-    value = tokens / (agg["offered_ns"] * 1e-9)
-
-    # per-kernel-class rates from the HIP events recorded on the fill stream during the timed steps
-    T, d, f = shape.tokens, shape.d_model, shape.d_ff
-    att_flops = 4.0 * shape.batch * shape.seq_len ** 2 * d * (0.5 if shape.causal else 1.0)
-    esz = 2
-    classes = [
-        ("gemm_qkv", pf.PF_K_GEMM_QKV, "mfma", gemm_flops(T, 3 * d, d)),
-        ("gemm_out", pf.PF_K_GEMM_OUT, "mfma", gemm_flops(T, d, d)),
-        ("gemm_ffn1", pf.PF_K_GEMM_FFN1, "mfma", gemm_flops(T, f, d)),
-        ("gemm_ffn2", pf.PF_K_GEMM_FFN2, "mfma", gemm_flops(T, d, f)),
-        ("attention", pf.PF_K_ATTENTION, "mfma", att_flops),
-        ("layernorm", pf.PF_K_LAYERNORM, "hbm", 2.0 * T * d * esz),       # read x, write y
-        ("embed", pf.PF_K_EMBED, "hbm", 2.0 * T * d * esz + T * 4),        # gather row, write row, ids
-    ]
-    kernels = {}
-    for name_, cls, bound, work in classes:
-        n_, ns_ = model.ctx.pf_ctx_kernel_stats(cls)
-        if n_ == 0:
-            continue
-        avg_s = ns_ * 1e-9 / n_
-        if bound == "mfma":
-            kernels[name_] = {"bound": "mfma", "achieved": work / avg_s * 1e-12, "peak": BF16_PEAK_TFLOPS,
-                              "unit": "TFLOP/s", "frac": work / avg_s * 1e-12 / BF16_PEAK_TFLOPS,
-                              "launches": n_, "avg_us": avg_s * 1e6}
-        else:
-            kernels[name_] = {"bound": "hbm", "achieved": work / avg_s * 1e-9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                              "frac": work / avg_s * 1e-9 / HBM_PEAK_GBS, "launches": n_, "avg_us": avg_s * 1e6}
-    # dominant kernel: the first FFN matrix (256x256-tile bf16 MFMA GEMM with the bias+GELU epilogue),
-    # the longest launch of a layer visit; algorithmic work = 2*M*N*K with M=tokens, N=d_ff, K=d_model
-    dom = kernels["gemm_ffn1"]
-    roofline = {"bound": "mfma", "achieved": dom["achieved"], "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": dom["frac"], "traffic": None,
-                "kernel": "gemm_bf16_nt_kernel<2,4,4,2,bf16_t,3> (FFN1: M=%d N=%d K=%d, bias+GELU)" % (T, f, d),
-                "launches": dom["launches"], "avg_us": dom["avg_us"]}
-
-    layer_flops = gemm_flops(T, 3 * d, d) + gemm_flops(T, d, d) + 2 * gemm_flops(T, f, d) + att_flops
-    out = {
-        "metric": "fill tokens/s in bubbles", "value": value, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+    kernels = kernel_rates(model.ctx, pf, shape)
+    out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": f"{name}: 12-layer bf16 encoder inference fill job d=768 h=12 ff=3072 seq=512 "
                                f"batch=32, weights resident, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 24 GiB free, "
                                f"all {p} stages in rotation",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
                    "windows": "contiguous only" if args.paper_mode else "all idle windows"},
-        "pct_bubble_filled": 100.0 * agg["fill_busy_ns"] / agg["offered_ns"],
-        "pct_idle_filled": 100.0 * agg["fill_busy_ns"] / agg["idle_ns"],
-        "overrun_pct_of_offered": 100.0 * agg["overrun_ns"] / agg["offered_ns"],
-        "main_slowdown_pct": None,
-        "fill_tflops_in_bubbles": agg["replicas_done"] * shape.n_layers * layer_flops / (agg["offered_ns"] * 1e-9) * 1e-12,
-        "replicas_done": agg["replicas_done"], "chunks_run": agg["chunks_run"],
+        **fill_stats(agg), "main_slowdown_pct": None,
+        "fill_tflops_in_bubbles": agg["replicas_done"] * shape.n_layers * layer_fwd_flops(shape) /
+        (agg["offered_ns"] * 1e-9) * 1e-12,
         "chain_ms": chain_ns * 1e-6, "planner_ms_all_stages": t_plan * 1e3,
-        "roofline": roofline, "kernels": kernels,
-    }
+        "roofline": ffn1_roofline(kernels, shape), "kernels": kernels})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs)
     model.close()
+    return out
+
+
+# ---------------------------------------------------------------------------------------------- cfg3
+def make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4), n_slots=3):
+    shape = synth.WORKLOADS["cfg3"]
+    md = pf.model_desc(shape)
+    blobs = [dev.random_layer_blob(md, 300 + l, pinned=True) for l in range(shape.n_layers)]
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(299)
+    mk = lambda *s: (torch.randn(*s, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+    tok, pos = mk(shape.vocab, shape.d_model), mk(shape.seq_len, shape.d_model)
+    lnf_g, lnf_b = mk(shape.d_model) + 1.0, mk(shape.d_model)
+    models = []
+    for g in gs:
+        mdl = dev.RawModel(shape, blobs, tok, pos, lnf_g, lnf_b, g=g, streamed=True, n_slots=n_slots)
+        n_ring = 2
+        ids = torch.randint(0, shape.vocab, (n_ring, g, shape.batch, shape.seq_len), dtype=torch.int32, device="cuda",
+                            generator=gen)
+        out = dev.empty_storage((1, g, shape.batch, shape.seq_len, shape.d_model), mdl.md)
+        mdl.set_io(ids, n_ring, out, 1)
+        models.append(mdl)
+    return shape, models
+
+
+def run_cfg3(args, np, torch, pf, dev, synth):
+    shape, models = make_cfg3_models(torch, pf, dev, synth)
+    fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
+    windows = [dict(start=20_000_000, dur=40_000_000, free=8 * GIB, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
+    for mdl in models:
+        mdl.ctx.pf_profile_chain(mdl.chain, 1, 3, fill.cuda_stream)
+    cfgs = [dict(F=mdl.chain, samples=mdl.cfg.g * shape.batch) for mdl in models]
+    best, rep, cyc, chk = pf.pf_select_config(windows, cfgs, args.fill_ppm, args.switch_ns, 0)
+    if best < 0:
+        raise RuntimeError("no configuration of the streamed job fits the 40 ms / 8 GiB bubbles")
+    mdl = models[best]
+    plan, n_plan, k = pf.pf_plan_bubbles(windows, mdl.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
+    cursor = C.c_int32(0)
+
+    def run_step():
+        return pf.pf_timeline_run(mdl.ctx, None, None, 0, 0, 0, 0, 0, windows, plan, n_plan, mdl.chain, cursor,
+                                  fill.cuda_stream, main_s.cuda_stream)
+
+    for _ in range(args.warmup):
+        run_step()
+    mdl.ctx.pf_ctx_kernel_timing(0x7f)
+    torch.cuda.synchronize()
+    agg = dict.fromkeys(AGG_KEYS, 0)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        s = run_step()
+        for k_ in agg:
+            agg[k_] += s[k_]
+        mdl.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    g = mdl.cfg.g
+    tokens = agg["replicas_done"] * g * shape.tokens
+    kernels = kernel_rates(mdl.ctx, pf, shape)
+    blob_bytes = pf.pf_layer_blob_layout(mdl.md)[0]
+    layer_visits = sum(1 for n in mdl.chain if n.op == pf.PF_OP_LAYER_FWD) * agg["replicas_done"]
+    out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
+        "config": {"workload": "cfg3: 24-layer bf16 causal decoder inference fill job d=2048 h=16 ff=8192 seq=1024 "
+                               "batch=16, weights streamed per layer from pinned host memory (3 HBM slots), "
+                               "explicit 40 ms bubbles separated by 20 ms, 8 GiB cap",
+                   "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
+                   "microbatches_per_layer_visit": g,
+                   "candidates": {f"g={m_.cfg.g}": {"replicas": rep[i], "cycles": cyc[i],
+                                                     "chain_ms": sum(n.dur_ns for n in m_.chain) * 1e-6}
+                                  for i, m_ in enumerate(models)}},
+        **fill_stats(agg), "main_slowdown_pct": None,
+        "fill_tflops_in_bubbles": agg["replicas_done"] * g * shape.n_layers * layer_fwd_flops(shape) /
+        (agg["offered_ns"] * 1e-9) * 1e-12,
+        "host_to_hbm_gbs_in_bubbles": layer_visits * blob_bytes / (agg["offered_ns"] * 1e-9) * 1e-9,
+        "roofline": ffn1_roofline(kernels, shape), "kernels": kernels})
+    for m_ in models:
+        m_.close()
+    return out
+
+
+# ---------------------------------------------------------------------------------------------- cfg4
+def run_cfg4(args, np, torch, pf, dev, synth):
+    name = "cfg4"
+    shape = synth.WORKLOADS[name]
+    p, m, tf, tb, free = synth.SCHEDULES[name]
+    params = synth.make_model_params(shape, seed=300)
+    adam = pf.pf_adam(1e-4, 0.9, 0.999, 1e-8, 4)
+    model = dev.DeviceModel(shape, params, training=True, adam=adam)
+    n_ring = 4
+    ids = np.stack([synth.make_token_ids(shape, seed=301 + 1000 * i)[None] for i in range(n_ring)])
+    d_in = dev.to_device(ids.astype(np.int32))
+    model.set_io(d_in, n_ring, None, 0)
+    fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
+    model.ctx.pf_profile_chain(model.chain, 1, 3, fill.cuda_stream)
+    model.ctx.pf_ctx_train_state()
+    chain_ns = sum(n.dur_ns for n in model.chain)
+    stages = []
+    for s in range(p):
+        windows = pf.pf_schedule_1f1b(p, m, s, tf, tb, free, True, 2 * max(n.dur_ns for n in model.chain))
+        plan, n_plan, k = pf.pf_plan_bubbles(windows, model.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
+        stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, cursor=C.c_int32(0)))
+
+    def run_step(i):
+        st = stages[i % p]
+        return pf.pf_timeline_run(model.ctx, None, None, p, m, st["stage"], tf, tb, st["windows"], st["plan"],
+                                  st["n_plan"], model.chain, st["cursor"], fill.cuda_stream, main_s.cuda_stream)
+
+    for i in range(args.warmup):
+        run_step(i)
+    _, steps0 = model.ctx.pf_ctx_train_state()
+    torch.cuda.synchronize()
+    agg = dict.fromkeys(AGG_KEYS, 0)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        s = run_step(i)
+        for k_ in agg:
+            agg[k_] += s[k_]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    loss, steps1 = model.ctx.pf_ctx_train_state()
+    tokens = agg["replicas_done"] * shape.tokens
+    # forward + recompute + backward (2x forward) = 4x the layer forward, plus the head's three T x V x d GEMMs
+    step_flops = 4 * shape.n_layers * layer_fwd_flops(shape) + 3 * gemm_flops(shape.tokens, shape.vocab, shape.d_model)
+    L = shape.n_layers
+    out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
+        "config": {"workload": f"{name}: 12-layer bf16 causal decoder TRAINING fill job d=1024 h=16 ff=4096 seq=1024 "
+                               f"microbatch=8, fwd + recompute/bwd + Adam every 4 microbatches, gradients accumulated "
+                               f"across bubbles, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 16 GiB free, stages in rotation",
+                   "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns},
+        **fill_stats(agg), "main_slowdown_pct": None,
+        "fill_tflops_in_bubbles": agg["replicas_done"] * step_flops / (agg["offered_ns"] * 1e-9) * 1e-12,
+        "chain_ms": chain_ns * 1e-6, "optimizer_steps": steps1 - steps0, "mean_loss": loss,
+        "arena_gib": model.arena_bytes / GIB,
+        "node_ms": {"layer_fwd": model.chain[1].dur_ns * 1e-6, "head_loss": model.chain[L + 2].dur_ns * 1e-6,
+                    "layer_bwd": model.chain[L + 3].dur_ns * 1e-6, "opt": model.chain[len(model.chain) - 1].dur_ns * 1e-6},
+        "roofline": None})
+    model.close()
+    return out
+
+
+# ---------------------------------------------------------------------------------------------- cfg5
+def run_cfg5(args, np, torch, pf, dev, synth):
+    shape5 = synth.WORKLOADS["cfg5"]
+    p, m = 16, 32
+    stage = args.stage
+    in_flight = min(p - stage, m)
+    md5 = pf.model_desc(shape5)
+    blobs5 = [dev.random_layer_blob(md5, 500 + l) for l in range(shape5.n_layers)]
+    main = dev.RawModel(shape5, blobs5, None, None, None, None, g=in_flight, training=True)
+    del blobs5
+    main.blobs = []          # the context copied the parameters into its arena
+    torch.cuda.empty_cache()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    x = torch.randn(shape5.batch, shape5.seq_len, shape5.d_model, device="cuda", generator=gen).to(torch.bfloat16)
+    fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    def time_main(reps):
+        tfs, tbs = [], []
+        for r in range(reps):
+            ev[0].record(main_s)
+            main.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, 0, x.data_ptr(), main_s.cuda_stream)
+            ev[1].record(main_s)
+            main.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, 0, x.data_ptr(), main_s.cuda_stream)
+            ev[2].record(main_s)
+            torch.cuda.synchronize()
+            tfs.append(ev[0].elapsed_time(ev[1]))
+            tbs.append(ev[1].elapsed_time(ev[2]))
+        return sorted(tfs)[len(tfs) // 2], sorted(tbs)[len(tbs) // 2]
+
+    time_main(1)
+    tf_ms, tb_ms = time_main(3)
+    tf, tb = int(tf_ms * 1e6), int(tb_ms * 1e6)
+
+    shape3, models = make_cfg3_models(torch, pf, dev, synth, gs=(2,))
+    fm = models[0]
+    fm.ctx.pf_profile_chain(fm.chain, 1, 3, fill.cuda_stream)
+    windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, 8 * GIB, True, 2 * max(n.dur_ns for n in fm.chain))
+    plan, n_plan, k = pf.pf_plan_bubbles(windows, fm.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
+    cursor = C.c_int32(0)
+
+    def run_iter(with_fill):
+        return pf.pf_timeline_run(fm.ctx if with_fill else None, main.ctx, x.data_ptr(), p, m, stage, tf, tb, windows,
+                                  plan, n_plan, fm.chain, cursor, fill.cuda_stream, main_s.cuda_stream)
+
+    for _ in range(args.warmup):
+        run_iter(True)
+    base = [run_iter(False) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    agg = dict.fromkeys(AGG_KEYS, 0)
+    t0 = time.perf_counter()
+    filled = []
+    for _ in range(args.steps):
+        s = run_iter(True)
+        filled.append(s)
+        for k_ in agg:
+            agg[k_] += s[k_]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    t_base = sum(s["iter_ns"] for s in base) / len(base)
+    t_fill = sum(s["iter_ns"] for s in filled) / len(filled)
+    mb_base = sum(s["main_busy_ns"] for s in base) / len(base)
+    mb_fill = sum(s["main_busy_ns"] for s in filled) / len(filled)
+    g = fm.cfg.g
+    tokens = agg["replicas_done"] * g * shape3.tokens
+    out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
+        "config": {"workload": f"cfg5: main-job stage of 3 layers d=8192 h=64 ff=32768 seq=2048 microbatch=1 bf16 fwd+bwd "
+                               f"(recomputing backward) on its own stream, emulated 1F1B p={p} m={m} stage {stage} with "
+                               f"measured t_f={tf_ms:.1f} ms t_b={tb_ms:.1f} ms; fill = cfg3 job (streamed weights, g=2), "
+                               f"8 GiB cap",
+                   "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns},
+        **fill_stats(agg),
+        "main_slowdown_pct": 100.0 * (t_fill - t_base) / t_base,
+        "main_iter_ms_without_fill": t_base * 1e-6, "main_iter_ms_with_fill": t_fill * 1e-6,
+        "main_busy_ms_without_fill": mb_base * 1e-6, "main_busy_ms_with_fill": mb_fill * 1e-6,
+        "main_stage_tflops": (4 * shape5.n_layers * layer_fwd_flops(shape5) * m) / (mb_base * 1e-9) * 1e-12,
+        "fill_tflops_in_bubbles": agg["replicas_done"] * g * shape3.n_layers * layer_fwd_flops(shape3) /
+        (agg["offered_ns"] * 1e-9) * 1e-12,
+        "roofline": None})
+    fm.close()
+    main.close()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
+    ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
+    ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles (cfg2)")
+    ap.add_argument("--stage", type=int, default=7, help="pipeline stage emulated by cfg5")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the fill path has no cross-GPU step "
+              "(one independent Executor per device). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    defaults = {"cfg2": (16, 2), "cfg3": (50, 3), "cfg4": (16, 1), "cfg5": (3, 1)}
+    if args.steps is None:
+        args.steps = defaults[args.workload][0]
+    if args.warmup is None:
+        args.warmup = defaults[args.workload][1]
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; there is no CPU fallback for the product path", file=sys.stderr)
+        sys.exit(3)
+    from paper_2410_07192_amd import binding as pf
+    from paper_2410_07192_amd import device as dev
+    from paper_2410_07192_amd import synth
+
+    run = {"cfg2": run_cfg2, "cfg3": run_cfg3, "cfg4": run_cfg4, "cfg5": run_cfg5}[args.workload]
+    out = run(args, np, torch, pf, dev, synth)
     print(json.dumps(out))
 
 

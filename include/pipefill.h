@@ -268,7 +268,10 @@ typedef struct pf_timeline_stats {
  * fill_stream with the window's free_bytes as cap, and the window is held open on the host for
  * its dur_ns.  fill_ctx may be NULL (no filling: the baseline for slowdown).  *cursor (host,
  * in/out) advances over plan[0..n_plan); when it reaches n_plan it wraps to 0 (the plan is
- * cyclic: the same chunks serve new replicas).  Synchronises the device at the end. */
+ * cyclic: the same chunks serve new replicas).  Synchronises the device at the end.
+ * Explicit cycles: with p == 0 (m, stage, tf_ns, tb_ns ignored, main_ctx must be NULL) the windows are
+ * taken as given: before window k the fill and copy streams stay idle for start_ns[k] minus the end
+ * of window k-1 (start_ns[0] for the first), then the window opens for dur_ns[k]. */
 int32_t pf_timeline_run(pf_ctx* fill_ctx, pf_ctx* main_ctx, const void* main_io,
                         int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int64_t tb_ns,
                         const pf_bubble* windows, int32_t nW,

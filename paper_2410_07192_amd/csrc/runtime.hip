@@ -581,7 +581,15 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
                         int64_t tf_ns, int64_t tb_ns, const pf_bubble* W, int32_t nW, const pf_chunk* plan,
                         int32_t n_plan, const pf_node* F, int32_t nF, int32_t* cursor, void* fill_stream,
                         void* main_stream, pf_timeline_stats* stats) {
-  if (p < 1 || m < 1 || stage < 0 || stage >= p || tf_ns <= 0 || tb_ns <= 0 || nW < 0 || (nW > 0 && !W) || !stats)
+  const bool explicit_cycle = (p == 0);   // windows given with their own start times, main stage is a placeholder
+  if (explicit_cycle) {
+    if (mc || nW <= 0 || !W || !stats) return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad explicit cycle");
+    int64_t t = 0;
+    for (int32_t k = 0; k < nW; ++k) {
+      if (W[k].start_ns < t || W[k].dur_ns <= 0) return pf::fail(PF_ERR_ARG, "pf_timeline_run: windows overlap or are empty");
+      t = W[k].start_ns + W[k].dur_ns;
+    }
+  } else if (p < 1 || m < 1 || stage < 0 || stage >= p || tf_ns <= 0 || tb_ns <= 0 || nW < 0 || (nW > 0 && !W) || !stats)
     return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad schedule argument");
   if (fc && (!plan || n_plan <= 0 || !F || nF <= 0 || !cursor || *cursor < 0 || *cursor >= n_plan))
     return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad plan argument");
@@ -589,15 +597,22 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   if (fc && fs == mstr) return pf::fail(PF_ERR_ARG, "pf_timeline_run: fill and main streams must differ");
   // instruction list of the stage in 1F1B order, bubbles where the schedule has idle windows
   struct Instr { int32_t kind, index; };
+  constexpr int32_t INSTR_WAIT = 100;   // explicit cycle: the closed interval before window `index`
   std::vector<Instr> prog;
-  const int32_t nf0 = std::min(p - stage, m);
+  if (explicit_cycle) {
+    for (int32_t k = 0; k < nW; ++k) {
+      prog.push_back({INSTR_WAIT, k});
+      prog.push_back({PF_INSTR_BUBBLE, k});
+    }
+  }
+  const int32_t nf0 = explicit_cycle ? 0 : std::min(p - stage, m);
   const bool has_fb = (int64_t)p * tf_ns + (int64_t)(p - 1 - stage) * tb_ns > (int64_t)(stage + nf0) * tf_ns;
   int32_t nb = 0;
   for (int32_t j = 0; j < nf0; ++j) prog.push_back({PF_INSTR_FWD, j});
-  if (has_fb) prog.push_back({PF_INSTR_BUBBLE, nb++});
+  if (has_fb && !explicit_cycle) prog.push_back({PF_INSTR_BUBBLE, nb++});
   int32_t fnext = nf0;
   bool fwd_before = true;
-  for (int32_t j = 0; j < m; ++j) {
+  for (int32_t j = 0; j < m && !explicit_cycle; ++j) {
     if (!fwd_before) prog.push_back({PF_INSTR_BUBBLE, nb++});
     prog.push_back({PF_INSTR_BWD, j});
     fwd_before = false;
@@ -606,8 +621,8 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
       fwd_before = true;
     }
   }
-  if (stage > 0) prog.push_back({PF_INSTR_BUBBLE, nb++});
-  if (nb != nW)
+  if (stage > 0 && !explicit_cycle) prog.push_back({PF_INSTR_BUBBLE, nb++});
+  if (!explicit_cycle && nb != nW)
     return pf::fail(PF_ERR_ARG, "pf_timeline_run: the schedule has %d idle windows, %d were passed", nb, nW);
 
   std::memset(stats, 0, sizeof *stats);
@@ -632,6 +647,12 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   int64_t t_sched = t_start;          // scheduled time of the next instruction (placeholder main stage)
   for (size_t pc = 0; pc < prog.size() && rc == PF_OK; ++pc) {
     const Instr in = prog[pc];
+    if (in.kind == INSTR_WAIT) {
+      const int64_t prev_end = in.index ? W[in.index - 1].start_ns + W[in.index - 1].dur_ns : 0;
+      t_sched += W[in.index].start_ns - prev_end;
+      wait_until(t_sched);
+      continue;
+    }
     if (in.kind != PF_INSTR_BUBBLE) {
       if (mc) {
         hipEvent_t a = nullptr, b = nullptr;

@@ -84,3 +84,58 @@ class DeviceModel:
 
     def close(self):
         self.ctx.destroy()
+
+
+def random_layer_blob(md, seed, pinned=False):
+    """A layer blob drawn on the device (N(0, 0.02^2) everywhere, LayerNorm scales 1 + N): for the
+    large benchmark workloads, where drawing and transposing on the host would take minutes.  Same
+    distribution as synth.make_layer_params, different stream of random numbers."""
+    size, off = pf.pf_layer_blob_layout(md)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    if md.dtype == pf.PF_DTYPE_BF16:
+        n = size // 2
+        vals = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+        step = 1 << 26
+        for a in range(0, n, step):
+            b = min(n, a + step)
+            vals[a:b] = (torch.randn(b - a, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+        for i in (0, 6):
+            vals[off[i] // 2: off[i] // 2 + md.d_model] += 1.0
+        raw = vals.view(torch.uint8)
+    else:
+        n = size // 4
+        vals = torch.randn(n, device="cuda", generator=gen) * 0.02
+        for i in (0, 6):
+            vals[off[i] // 4: off[i] // 4 + md.d_model] += 1.0
+        raw = vals.view(torch.uint8)
+    if pinned:
+        host = torch.empty(size, dtype=torch.uint8, pin_memory=True)
+        host.copy_(raw)
+        return host
+    return raw
+
+
+class RawModel:
+    """Like DeviceModel but from ready-made blobs and embedding tensors (device plumbing only)."""
+
+    def __init__(self, shape, blobs, tok, pos, lnf_g, lnf_b, g=1, streamed=False, n_slots=0, training=False, adam=None):
+        self.shape = shape
+        self.md = pf.model_desc(shape)
+        self.cfg = pf.pf_exec_config(g, int(streamed), n_slots, int(training))
+        self.blobs, self.tok, self.pos, self.lnf_g, self.lnf_b = blobs, tok, pos, lnf_g, lnf_b
+        self.arena_bytes = pf.pf_ctx_arena_bytes(self.md, self.cfg)
+        self.arena = torch.empty(self.arena_bytes + 256, dtype=torch.uint8, device="cuda")
+        base = (self.arena.data_ptr() + 255) // 256 * 256
+        ptr = lambda t: t.data_ptr() if t is not None else None
+        self.ctx = pf.Context(self.md, self.cfg, [b.data_ptr() for b in blobs], ptr(tok), ptr(pos), ptr(lnf_g),
+                              ptr(lnf_b), base, self.arena_bytes, adam)
+        self.chain = pf.pf_build_chain(self.md, self.cfg) if not (training and shape.vocab == 0) else None
+
+    def set_io(self, inputs, n_in, outputs, n_out):
+        self._io = (inputs, outputs)
+        self.ctx.pf_ctx_set_io(inputs.data_ptr(), n_in, outputs.data_ptr() if outputs is not None else None, n_out)
+
+    def close(self):
+        self.ctx.destroy()
+        self.arena = None
