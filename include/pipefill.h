@@ -311,6 +311,11 @@ int32_t pf_op_layernorm(int32_t dtype, const void* x, const void* g, const void*
  * column blocks), out: [B*S][h*dh], lse: fp32 [B][h][S] or NULL.  dh in {8,16,32,64,128}. */
 int32_t pf_op_attention(int32_t dtype, const void* qkv, void* out, float* lse, int32_t B, int32_t S,
                         int32_t h, int32_t dh, int32_t causal, void* stream);
+/* Backward of pf_op_attention from the saved lse: dqkv [B*S][3*h*dh] receives dQ | dK | dV.  out / dout:
+ * [B*S][h*dh]; dsum: fp32 scratch [B][h][S]. */
+int32_t pf_op_attention_bwd(int32_t dtype, const void* qkv, const void* out, const void* dout, const float* lse,
+                            float* dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
+                            void* stream);
 /* x[t] = tok[ids[t]] + pos[t mod S]; ids int32 [tokens]; ids outside [0,V) contribute zeros. */
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
                     int64_t tokens, int32_t S, int32_t d, int32_t V, void* stream);

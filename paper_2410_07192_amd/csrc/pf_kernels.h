@@ -56,6 +56,10 @@ hipError_t layernorm_bwd(int32_t dtype, const void* dy, const void* x, const voi
 hipError_t attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* dout, const float* lse,
                          float* Dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
                          hipStream_t stream);
+// bf16, d_head 64 / 128: MFMA version (called by attention_bwd)
+hipError_t attention_bwd_mfma(const void* qkv, const void* o, const void* dout, const float* lse, float* Dsum,
+                              void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
+                              hipStream_t stream);
 // In place on logits [tokens][pitch]: (softmax - onehot(next token)) * inv_n; loss_sum += -log p[target].
 hipError_t ce_loss_inplace(int32_t dtype, void* logits, const int32_t* ids, float* loss_sum, int64_t tokens,
                            int64_t pitch, int32_t V, int32_t S, float inv_n, hipStream_t stream);

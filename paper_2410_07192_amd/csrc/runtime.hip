@@ -819,6 +819,16 @@ int32_t pf_op_attention(int32_t dtype, const void* qkv, void* out, float* lse, i
   return PF_OK;
 }
 
+int32_t pf_op_attention_bwd(int32_t dtype, const void* qkv, const void* out, const void* dout, const float* lse,
+                            float* dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
+                            void* stream) {
+  if (bad_dtype(dtype) || !qkv || !out || !dout || !lse || !dsum || !dqkv || B <= 0 || S <= 0 || h <= 0 || B > 65535 ||
+      h > 65535 || !(dh == 8 || dh == 16 || dh == 32 || dh == 64 || dh == 128))
+    return pf::fail(PF_ERR_ARG, "pf_op_attention_bwd: bad argument");
+  PF_HIP(pf::attention_bwd(dtype, qkv, out, dout, lse, dsum, dqkv, B, S, h, dh, causal, (hipStream_t)stream));
+  return PF_OK;
+}
+
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int64_t tokens,
                     int32_t S, int32_t d, int32_t V, void* stream) {
   if (bad_dtype(dtype) || !ids || !tok || !pos || !x || tokens <= 0 || S <= 0 || d <= 0 || d % 8 != 0 || V <= 0)

@@ -463,6 +463,8 @@ hipError_t attention_bwd(int32_t dtype, const void* qkv, const void* o, const vo
                          float* Dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
                          hipStream_t st) {
   if (B <= 0 || S <= 0 || h <= 0 || B > 65535 || h > 65535) return hipErrorInvalidValue;
+  if (dtype == PF_DTYPE_BF16_ && (dh == 64 || dh == 128))
+    return attention_bwd_mfma(qkv, o, dout, lse, Dsum, dqkv, B, S, h, dh, causal, st);
   if (dtype == PF_DTYPE_BF16_) return launch_attn_bwd<bf16_t>(qkv, o, dout, lse, Dsum, dqkv, B, S, h, dh, causal, st);
   return launch_attn_bwd<float>(qkv, o, dout, lse, Dsum, dqkv, B, S, h, dh, causal, st);
 }

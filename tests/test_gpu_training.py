@@ -185,3 +185,42 @@ def test_main_stage_forward_backward(dtype, tol):
         assert e.value.code == pf.PF_ERR_ARG
     finally:
         m.close()
+
+
+ATT_BWD = [("bf16", 2, 200, 3, 64), ("bf16", 1, 321, 2, 128), ("bf16", 2, 64, 2, 64), ("bf16", 1, 130, 2, 16),
+           ("f32", 2, 100, 2, 32), ("f32", 1, 70, 1, 64)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype,B,S,h,dh", ATT_BWD)
+def test_attention_backward_kernel(dtype, B, S, h, dh, causal):
+    pf, dev = _mods()
+    md = pf.pf_model_desc()
+    md.dtype = pf.PF_DTYPE_BF16 if dtype == "bf16" else pf.PF_DTYPE_F32
+    d = h * dh
+    rng = np.random.default_rng(S * 7 + dh)
+    rnd = lambda *s: (synth.round_to_bf16(rng.standard_normal(s).astype(np.float32)) if dtype == "bf16"
+                      else rng.standard_normal(s).astype(np.float32))
+    qkv, dout = rnd(B, S, 3 * d), rnd(B, S, d)
+    dq_, do_ = dev.storage_tensor(qkv, md), dev.storage_tensor(dout, md)
+    out = dev.empty_storage((B, S, d), md)
+    dqkv = dev.empty_storage((B, S, 3 * d), md)
+    lse = torch.empty((B, h, S), dtype=torch.float32, device="cuda")
+    dsum = torch.empty((B, h, S), dtype=torch.float32, device="cuda")
+    pf.pf_op_attention(md.dtype, dq_.data_ptr(), out.data_ptr(), B, S, h, dh, causal, lse.data_ptr())
+    pf.pf_op_attention_bwd(md.dtype, dq_.data_ptr(), out.data_ptr(), do_.data_ptr(), lse.data_ptr(), dsum.data_ptr(),
+                           dqkv.data_ptr(), B, S, h, dh, causal)
+    torch.cuda.synchronize()
+    q64 = qkv.astype(np.float64)
+    q, k, v = (ot.split_heads(q64[..., i * d:(i + 1) * d], h) for i in range(3))
+    A = ot.attention_probs(q, k, causal)
+    do = ot.split_heads(dout.astype(np.float64), h)
+    dA = do @ v.transpose(0, 1, 3, 2)
+    dv = A.transpose(0, 1, 3, 2) @ do
+    ds = A * (dA - (dA * A).sum(-1, keepdims=True))
+    dq = ds @ k / np.sqrt(dh)
+    dk = ds.transpose(0, 1, 3, 2) @ q / np.sqrt(dh)
+    got = dev.read_storage(dqkv, md)
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    for i, ref in enumerate((dq, dk, dv)):
+        assert rel_err(got[..., i * d:(i + 1) * d], ot.merge_heads(ref)) < tol, "qkv"[i]
