@@ -390,6 +390,68 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
   // Indices into acc must be compile-time constants or the accumulators leave the register file.
   const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
+  // Staged epilogue (bf16 output, no per-element side inputs other than bias / residual): bias and GELU
+  // are applied in registers, the bf16 tile goes through LDS (free after the K loop; 16-byte slots
+  // XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the tile, the residual
+  // being added on the way out from equally coalesced loads.
+  constexpr bool STAGED = std::is_same<OutT, bf16_t>::value && !(EPI & (E_PRE | E_DACT | E_ACC));
+  if constexpr (STAGED) {
+    const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid) & 15) == 0);
+    if (interior && aligned16) {
+      constexpr int SLOTS = BN / 8, NT = 64 * NW, PER = BM * BN / 8 / NT;
+      uint2* st8 = (uint2*)smem;
+      static_for<0, TN>([&](auto a) {
+        float bias4[4][4] = {};
+        if constexpr (EPI & E_BIAS) {
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg)
+            load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
+        }
+        static_for<0, TM>([&](auto b) {
+          const int row = (wm * TM + b) * 32 + lr;
+          static_for<0, 4>([&](auto rg) {
+            float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                          acc[a][b][rg * 4 + 3]};
+            if constexpr (EPI & E_BIAS) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) v[j] += bias4[rg][j];
+            }
+            if constexpr (EPI & E_GELU) {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
+            }
+            uint2 pk;
+            pk.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
+            pk.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+            const int slot = (wn * TN + a) * 4 + rg;
+            st8[row * (SLOTS * 2) + ((slot ^ (row & (SLOTS - 1))) * 2) + lk] = pk;
+          });
+        });
+      });
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_s_barrier();
+#pragma unroll 4
+      for (int i = 0; i < PER; ++i) {
+        const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+        uint4 v = smem[row * SLOTS + (slot ^ (row & (SLOTS - 1)))];
+        const int64_t off = (m0 + row) * N + n0 + slot * 8;
+        if constexpr (EPI & E_RESID) {
+          const uint4 r = *(const uint4*)((const bf16_t*)ep.resid + off);
+          const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, rw[4] = {r.x, r.y, r.z, r.w};
+          uint32_t ow[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float lo = bf16_bits_to_f32(vw[j] & 0xffffu) + bf16_bits_to_f32(rw[j] & 0xffffu);
+            const float hi = bf16_bits_to_f32(vw[j] >> 16) + bf16_bits_to_f32(rw[j] >> 16);
+            ow[j] = f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+          }
+          v = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        }
+        *(uint4*)((bf16_t*)C + off) = v;
+      }
+      return;
+    }
+  }
   if (interior) {
     static_for<0, TN>([&](auto a) {
       float bias4[4][4] = {};
