@@ -29,8 +29,10 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(const bf16_t* __rest
   constexpr int KS = DH / 16;        // MFMA K steps over d_head
   constexpr int DT = DH / 32;        // 32-row tiles of O^T
   constexpr int VP = 68;             // pitch (elements) of a V^T row: 64 keys + 4 pad
+  constexpr int KCH = 64 * CPR / 256;   // K chunks staged per thread
+  constexpr int VUNITS = 16 * CPR;      // (4-key group, chunk) units of the V transpose, one per thread
   __shared__ uint4 sK[64 * CPR];
-  __shared__ uint16_t sVt[DH * VP];
+  __shared__ __align__(16) uint16_t sVt[DH * VP];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
@@ -63,29 +65,59 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(const bf16_t* __rest
     if (need < n_tiles) n_tiles = need;
   }
 
+  // Tile staging goes global -> registers (issued before the previous tile's MFMAs, so the loads
+  // are in flight during them) -> LDS.  K keeps its row-major chunks (swizzled).  V is transposed
+  // on the way: a thread takes one 8-wide d_head chunk of FOUR consecutive keys and writes, for each
+  // of the 8 d_head rows, the 4 keys as one 8-byte piece; 16 lanes with consecutive key groups cover
+  // 128 contiguous bytes of a V^T row, so the LDS writes are free of bank conflicts.
+  const int v_kg = tid & 15, v_c = tid >> 4;
+  uint4 rk[KCH], rv[4];
+  auto load_regs = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      const int q = tid + i * 256, r = q / CPR, c = q % CPR;
+      rk[i] = (k0 + r < S) ? *(const uint4*)(base + (int64_t)(k0 + r) * rs + d + c * 8) : make_uint4(0, 0, 0, 0);
+    }
+    if (tid < VUNITS) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int key = k0 + 4 * v_kg + j;
+        rv[j] = (key < S) ? *(const uint4*)(base + (int64_t)key * rs + 2 * d + v_c * 8) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto write_lds = [&]() {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      const int q = tid + i * 256, r = q / CPR, c = q % CPR;
+      const int sw = (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
+      sK[r * CPR + sw] = rk[i];
+    }
+    if (tid < VUNITS) {
+      const uint32_t w0[4] = {rv[0].x, rv[0].y, rv[0].z, rv[0].w}, w1[4] = {rv[1].x, rv[1].y, rv[1].z, rv[1].w};
+      const uint32_t w2[4] = {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, w3[4] = {rv[3].x, rv[3].y, rv[3].z, rv[3].w};
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        uint2 even, odd;   // d_head rows 2jj and 2jj+1 of the chunk, keys 4kg..4kg+3
+        even.x = (w0[jj] & 0xffffu) | (w1[jj] << 16);
+        even.y = (w2[jj] & 0xffffu) | (w3[jj] << 16);
+        odd.x = (w0[jj] >> 16) | (w1[jj] & 0xffff0000u);
+        odd.y = (w2[jj] >> 16) | (w3[jj] & 0xffff0000u);
+        *(uint2*)(sVt + (v_c * 8 + 2 * jj) * VP + 4 * v_kg) = even;
+        *(uint2*)(sVt + (v_c * 8 + 2 * jj + 1) * VP + 4 * v_kg) = odd;
+      }
+    }
+  };
+
+  load_regs(0);
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int k0 = kt * 64;
     __syncthreads();   // previous tile fully consumed
-    // stage K (row-major, swizzled chunks) and V^T
-#pragma unroll
-    for (int i = 0; i < 64 * CPR / 256; ++i) {
-      const int q = tid + i * 256, r = q / CPR, c = q % CPR;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (k0 + r < S) {
-        const bf16_t* p = base + (int64_t)(k0 + r) * rs + c * 8;
-        kv = *(const uint4*)(p + d);
-        vv = *(const uint4*)(p + 2 * d);
-      }
-      const int sw = (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
-      sK[r * CPR + sw] = kv;
-      const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        sVt[(c * 8 + 2 * j) * VP + r] = (uint16_t)(w[j] & 0xffffu);
-        sVt[(c * 8 + 2 * j + 1) * VP + r] = (uint16_t)(w[j] >> 16);
-      }
-    }
+    write_lds();
     __syncthreads();
+    if (kt + 1 < n_tiles) load_regs(k0 + 64);
+    // a wave whose 32 queries all precede this tile has nothing to add (causal)
+    if (causal && k0 > q_blk + wave * 32 + 31) continue;
 
     // S^T tile: 64 keys x 32 queries per wave
     f32x16 accS[2];
@@ -118,13 +150,13 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(const bf16_t* __rest
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const float m_new = fmaxf(m_run, mx);
     const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = exp2f(m_run - m_use);            // m_run = -inf -> 0
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);            // m_run = -inf -> 0
     float ps = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(accS[ks][r] - m_use);
+        const float p = __builtin_amdgcn_exp2f(accS[ks][r] - m_use);
         accS[ks][r] = p;
         ps += p;
       }

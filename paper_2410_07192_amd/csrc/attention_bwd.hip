@@ -161,7 +161,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_bf16_kernel(const bf16_t* __
         const float Lv[4] = {L4.x, L4.y, L4.z, L4.w}, Dv[4] = {D4.x, D4.y, D4.z, D4.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          float p = exp2f(aS[rg * 4 + j] * scale_log2e - Lv[j]);
+          float p = __builtin_amdgcn_exp2f(aS[rg * 4 + j] * scale_log2e - Lv[j]);
           if (need_mask && key > q0 + qi + j) p = 0.f;
           P[qs][rg * 4 + j] = p;
           dS[qs][rg * 4 + j] = p * (aP[rg * 4 + j] - Dv[j]);
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(const bf16_t* __r
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = exp2f(aS[r] * scale_log2e - Lq);
+        float p = __builtin_amdgcn_exp2f(aS[r] * scale_log2e - Lq);
         if (need_mask) {
           const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
           if (key >= S || (causal && key > q_row)) p = 0.f;
