@@ -1,0 +1,166 @@
+"""GPU parity at the benchmark's full shapes, on sampled outputs the CPU checker can compute one by one
+(attention couples tokens only inside a sequence, so one whole sequence of the batch is checked), in
+the launch configuration bench.py uses; plus the explicit-bubble timeline."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from oracle import planner as op               # noqa: E402
+from oracle import transformer as ot           # noqa: E402
+from paper_2410_07192_amd import synth         # noqa: E402
+
+
+def _mods():
+    from paper_2410_07192_amd import binding as pf
+    from paper_2410_07192_amd import device as dev
+    return pf, dev
+
+
+def rel_err(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def test_cfg2_full_batch_sampled_sequences():
+    """12-layer bf16 encoder at d=768, seq 512, batch 32: the whole chain on the GPU, two sequences of
+    the batch against the checker (end to end through 12 layers, not teacher-forced)."""
+    pf, dev = _mods()
+    shape = synth.WORKLOADS["cfg2"]
+    params = synth.make_model_params(shape, seed=100)
+    ids = synth.make_token_ids(shape, seed=101)
+    m = dev.DeviceModel(shape, params)
+    try:
+        d_in = dev.to_device(ids[None].astype(np.int32))
+        d_out = dev.empty_storage((1, 1, shape.batch, shape.seq_len, shape.d_model), m.md)
+        m.set_io(d_in, 1, d_out, 1)
+        st = torch.cuda.Stream()
+        nF = len(m.chain)
+        for a, b in ((0, 5), (5, 6), (6, nF)):
+            m.ctx.pf_fill_chunk_fwd(m.chunk(a, b), m.chain, stream=st.cuda_stream)
+            m.ctx.pf_ctx_sync()
+        got = dev.read_storage(d_out, m.md)[0, 0]
+        P = ot.cast_params(params)
+        for b in (0, 19):
+            ref = ot.model_forward(ids[b:b + 1], P, shape.n_heads, shape.causal, shape.eps)
+            assert rel_err(got[b], ref[0]) < 2e-2, b
+        assert np.isfinite(got).all()
+    finally:
+        m.close()
+
+
+def test_cfg3_shaped_layer_streamed_teacher_forced():
+    """One layer of the d=2048 / 16-head / FFN-8192 causal decoder at seq 1024 (d_head 128), weights
+    streamed from pinned host memory through 3 slots, g = 2 microbatches per visit."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(2, 2048, 16, 8192, 1024, 2, 0, True, "bf16")
+    params = synth.make_model_params(shape, seed=200)
+    g = 2
+    x = np.stack([synth.make_hidden(shape, seed=210 + i) for i in range(g)])
+    m = dev.DeviceModel(shape, params, g=g, streamed=True, n_slots=3)
+    try:
+        d_in = dev.storage_tensor(x, m.md)
+        d_mid = dev.empty_storage(x.shape, m.md)
+        st = torch.cuda.Stream()
+        m.ctx.pf_fill_chunk_fwd(m.chunk(0, 1), m.chain, act_in=d_in.data_ptr(), act_out=d_mid.data_ptr(),
+                                stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        got = dev.read_storage(d_mid, m.md)
+        P = ot.cast_params(params)["layers"][0]
+        ref = ot.layer_forward(x[1, 1:2].astype(np.float64), P, shape.n_heads, True, shape.eps)
+        assert rel_err(got[1, 1], ref[0]) < 2e-2
+        # second layer from the GPU's own intermediate (teacher-forced), other microbatch
+        d_out = dev.empty_storage(x.shape, m.md)
+        m.ctx.pf_fill_chunk_fwd(m.chunk(1, 2), m.chain, act_in=d_mid.data_ptr(), act_out=d_out.data_ptr(),
+                                stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        P1 = ot.cast_params(params)["layers"][1]
+        ref1 = ot.layer_forward(got[0, 0:1].astype(np.float64), P1, shape.n_heads, True, shape.eps)
+        assert rel_err(dev.read_storage(d_out, m.md)[0, 0], ref1[0]) < 2e-2
+    finally:
+        m.close()
+
+
+@pytest.mark.parametrize("M,N,K", [(2048, 8192, 8192), (2048, 4096, 32768), (8192, 50304, 1024)])
+def test_large_gemm_sampled_rows(M, N, K):
+    """GEMM shapes of the d=8192 main stage and of the tied head: sampled output rows against float64."""
+    pf, dev = _mods()
+    md = pf.pf_model_desc()
+    md.dtype = pf.PF_DTYPE_BF16
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(M + N + K)
+    X = torch.randn(M, K, device="cuda", generator=gen).to(torch.bfloat16)
+    W = (torch.randn(N, K, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
+    b = torch.randn(N, device="cuda", generator=gen).to(torch.bfloat16)
+    Cm = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+    pf.pf_op_gemm(pf.PF_DTYPE_BF16, X.data_ptr(), W.data_ptr(), Cm.data_ptr(), M, N, K, bias=b.data_ptr())
+    torch.cuda.synchronize()
+    rows = [0, 1, M // 2 + 3, M - 1]
+    Xh = X[rows].float().cpu().numpy().astype(np.float64)
+    Wh = W.float().cpu().numpy().astype(np.float64)
+    ref = Xh @ Wh.T + b.float().cpu().numpy().astype(np.float64)
+    got = Cm[rows].float().cpu().numpy()
+    assert rel_err(got, ref) < 1e-2
+
+
+def test_explicit_bubble_cycle_timeline():
+    """Explicit windows (p = 0): chunks run only inside the given windows, plans are cyclic, results of
+    completed replicas match the checker, and the configuration choice agrees with the checker."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(6, 128, 2, 256, 128, 2, 300, True, "bf16")
+    params = synth.make_model_params(shape, seed=12)
+    n_rep = 3
+    models, cfgs = [], []
+    ids_all = {}
+    st, main = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        for g in (1, 2):
+            m = dev.DeviceModel(shape, params, g=g, streamed=True, n_slots=2)
+            ids = np.stack([np.stack([synth.make_token_ids(shape, seed=500 + 10 * r + j) for j in range(g)])
+                            for r in range(n_rep)])
+            d_in = dev.to_device(ids.astype(np.int32))
+            d_out = dev.empty_storage((n_rep, g, shape.batch, shape.seq_len, shape.d_model), m.md)
+            m.set_io(d_in, n_rep, d_out, n_rep)
+            m.ctx.pf_profile_chain(m.chain, 1, 3, st.cuda_stream)
+            models.append((m, d_in, d_out))
+            ids_all[g] = ids
+            cfgs.append(dict(F=m.chain, samples=g * shape.batch))
+        chain_ns = sum(n.dur_ns for n in models[0][0].chain)
+        windows = [dict(start=300_000, dur=max(2 * chain_ns // 3, 400_000), free=1 << 30, kind=3, fillable=1),
+                   dict(start=300_000 + 2 * chain_ns, dur=max(chain_ns // 2, 400_000), free=1 << 30, kind=3, fillable=1)]
+        windows[1]["start"] = windows[0]["start"] + windows[0]["dur"] + 200_000
+        best, rep, cyc, chk = pf.pf_select_config(windows, cfgs, 900_000, 0, 0)
+        want_best, plans = op.choose_configuration(
+            windows, [dict(F=[(n.dur_ns, n.mem_bytes) for n in c["F"]], samples=c["samples"]) for c in cfgs], 900_000, 0, 0)
+        assert best == want_best and best >= 0
+        m, d_in, d_out = models[best]
+        g = m.cfg.g
+        plan, n_plan, k = pf.pf_plan_bubbles(windows, m.chain, 900_000, 0, 0, raw=True)
+        cursor = C.c_int32(0)
+        done = 0
+        for _ in range(8):
+            s = pf.pf_timeline_run(m.ctx, None, None, 0, 0, 0, 0, 0, windows, plan, n_plan, m.chain, cursor,
+                                   st.cuda_stream, main.cuda_stream)
+            assert s["offered_ns"] == windows[0]["dur"] + windows[1]["dur"]
+            assert s["iter_ns"] >= windows[1]["start"] + windows[1]["dur"]
+            done += s["replicas_done"]
+            if done >= 2:
+                break
+        assert done >= 1
+        got = dev.read_storage(d_out, m.md)
+        for r in range(min(done, n_rep)):
+            for j in range(g):
+                ref = ot.model_forward(ids_all[g][r, j], ot.cast_params(params), shape.n_heads, True, shape.eps)
+                assert rel_err(got[r, j], ref) < 2e-2, (r, j)
+        with pytest.raises(pf.PipeFillError) as e:
+            bad = [dict(start=0, dur=10, free=1, kind=3, fillable=1), dict(start=5, dur=10, free=1, kind=3, fillable=1)]
+            pf.pf_timeline_run(m.ctx, None, None, 0, 0, 0, 0, 0, bad, plan, n_plan, m.chain, C.c_int32(0),
+                               st.cuda_stream, main.cuda_stream)
+        assert e.value.code == pf.PF_ERR_ARG
+    finally:
+        for m, _, _ in models:
+            m.close()
