@@ -11,7 +11,7 @@ while the main stage is emulated on the timeline.  The headline value is
 
 Workloads (--workload):
   cfg2 (default)  12-layer bf16 encoder inference fill job, weights resident, 1F1B p=8 m=16
-                  t_f=15 ms t_b=30 ms, 24 GiB free; steps rotate over the 8 stages.
+                  t_f=15 ms t_b=30 ms, 24 GiB free; the steps are shared evenly by the 8 stages.
   cfg3            24-layer d=2048 causal decoder inference, weights streamed from pinned host memory,
                   explicit 40 ms bubbles separated by 20 ms, 8 GiB cap; g microbatches per layer
                   visit chosen by the planner.
@@ -69,6 +69,30 @@ def cpu_baseline(shape, params, ids, n_seq):
                       f"{shape.n_layers} layers in float64, {dt:.1f} s"}
 
 
+def stage_stepper(pf, model, stages, args, p, m, tf, tb, fill, main_s):
+    """Step i of K runs one iteration of stage (i * p) // K (i % p when K < p): each of the p stages
+    gets K / p consecutive iterations, like p Executors that each sit on one device.  A stage starts
+    with a new fill job planned from its first bubble; when a job completes inside the stage's
+    iterations the library plans the next one from the following bubble."""
+    state = {"stage": -1, "cursor": C.c_int32(0)}
+
+    def reset():
+        state["stage"] = -1
+
+    def run(i):
+        s = (i * p) // args.steps if args.steps >= p else i % p
+        st = stages[s]
+        if s != state["stage"]:
+            state["stage"] = s
+            state["cursor"] = C.c_int32(0)
+            model.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
+        return pf.pf_timeline_run(model.ctx, None, None, p, m, st["stage"], tf, tb, st["windows"], st["plan"],
+                                  st["n_plan"], model.chain, state["cursor"], fill.cuda_stream, main_s.cuda_stream)
+
+    run.reset = reset
+    return run
+
+
 def kernel_rates(ctx, pf, shape):
     """Per-kernel-class rates from the HIP events the library recorded on the fill stream."""
     T, d, f = shape.tokens, shape.d_model, shape.d_ff
@@ -99,10 +123,17 @@ def kernel_rates(ctx, pf, shape):
     return out
 
 
-def ffn1_roofline(kernels, shape, tile="2,4,4,2"):
+# HBM-side traffic of one FFN1 launch of the default workload (M=16384, N=3072, K=768), from two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a plain
+# 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0): 108.6 MiB fetched + 96.0 MiB written.  Algorithmic:
+# 28.5 MiB read (X, W, bias) + 96 MiB written.  A profiler run is needed to refresh it.
+FFN1_CFG2_TRAFFIC_BYTES = int((108.6 + 96.0) * (1 << 20))
+
+
+def ffn1_roofline(kernels, shape, tile="2,4,4,2", traffic=None):
     dom = kernels["gemm_ffn1"]
     return {"bound": "mfma", "achieved": dom["achieved"], "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": dom["frac"], "traffic": None,
+            "frac": dom["frac"], "traffic": traffic,
             "kernel": "gemm_bf16_nt_kernel<%s,bf16_t,bias+GELU> (FFN1: M=%d N=%d K=%d)" %
                       (tile, shape.tokens, shape.d_ff, shape.d_model),
             "launches": dom["launches"], "avg_us": dom["avg_us"]}
@@ -151,16 +182,14 @@ def run_cfg2(args, np, torch, pf, dev, synth):
         t_plan += time.perf_counter() - t0
         stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, cursor=C.c_int32(0)))
 
-    def run_step(i):
-        st = stages[i % p]
-        return pf.pf_timeline_run(model.ctx, None, None, p, m, st["stage"], tf, tb, st["windows"], st["plan"],
-                                  st["n_plan"], model.chain, st["cursor"], fill.cuda_stream, main_s.cuda_stream)
+    run_step = stage_stepper(pf, model, stages, args, p, m, tf, tb, fill, main_s)
 
     for i in range(args.warmup):
-        run_step(i)
-    for st in stages:
-        st["cursor"] = C.c_int32(0)
-    model.ctx.pf_ctx_kernel_timing(0x7f)
+        run_step(0)
+    run_step.reset()
+    # only the roofline kernel is bracketed by events during the timed steps (every pair costs a few
+    # microseconds on the fill stream); the other classes are measured in two extra steps afterwards
+    model.ctx.pf_ctx_kernel_timing(1 << pf.PF_K_GEMM_FFN1)
     torch.cuda.synchronize()
     agg = dict.fromkeys(AGG_KEYS, 0)
     t0 = time.perf_counter()
@@ -172,18 +201,25 @@ def run_cfg2(args, np, torch, pf, dev, synth):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     tokens = agg["replicas_done"] * shape.tokens
+    dominant = kernel_rates(model.ctx, pf, shape)
+    model.ctx.pf_ctx_kernel_timing(0x7f)
+    run_step.reset()
+    for i in range(2):
+        run_step(0)
+        model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)
     kernels = kernel_rates(model.ctx, pf, shape)
+    kernels["gemm_ffn1"] = dominant["gemm_ffn1"]
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": f"{name}: 12-layer bf16 encoder inference fill job d=768 h=12 ff=3072 seq=512 "
                                f"batch=32, weights resident, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 24 GiB free, "
-                               f"all {p} stages in rotation",
+                               f"all {p} stages, {max(1, args.steps // p)} consecutive iteration(s) each",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
                    "windows": "contiguous only" if args.paper_mode else "all idle windows"},
         **fill_stats(agg), "main_slowdown_pct": None,
         "fill_tflops_in_bubbles": agg["replicas_done"] * shape.n_layers * layer_fwd_flops(shape) /
         (agg["offered_ns"] * 1e-9) * 1e-12,
         "chain_ms": chain_ns * 1e-6, "planner_ms_all_stages": t_plan * 1e3,
-        "roofline": ffn1_roofline(kernels, shape), "kernels": kernels})
+        "roofline": ffn1_roofline(kernels, shape, traffic=FFN1_CFG2_TRAFFIC_BYTES), "kernels": kernels})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs)
     model.close()
@@ -225,6 +261,7 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     mdl = models[best]
     plan, n_plan, k = pf.pf_plan_bubbles(windows, mdl.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
     cursor = C.c_int32(0)
+    mdl.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
 
     def run_step():
         return pf.pf_timeline_run(mdl.ctx, None, None, 0, 0, 0, 0, 0, windows, plan, n_plan, mdl.chain, cursor,
@@ -232,7 +269,7 @@ def run_cfg3(args, np, torch, pf, dev, synth):
 
     for _ in range(args.warmup):
         run_step()
-    mdl.ctx.pf_ctx_kernel_timing(0x7f)
+    mdl.ctx.pf_ctx_kernel_timing(1 << pf.PF_K_GEMM_FFN1)
     torch.cuda.synchronize()
     agg = dict.fromkeys(AGG_KEYS, 0)
     t0 = time.perf_counter()
@@ -245,7 +282,13 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     wall = time.perf_counter() - t0
     g = mdl.cfg.g
     tokens = agg["replicas_done"] * g * shape.tokens
+    dominant = kernel_rates(mdl.ctx, pf, shape)
+    mdl.ctx.pf_ctx_kernel_timing(0x7f)
+    for _ in range(4):
+        run_step()
+        mdl.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)
     kernels = kernel_rates(mdl.ctx, pf, shape)
+    kernels["gemm_ffn1"] = dominant["gemm_ffn1"]
     blob_bytes = pf.pf_layer_blob_layout(mdl.md)[0]
     layer_visits = sum(1 for n in mdl.chain if n.op == pf.PF_OP_LAYER_FWD) * agg["replicas_done"]
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
@@ -289,13 +332,11 @@ def run_cfg4(args, np, torch, pf, dev, synth):
         plan, n_plan, k = pf.pf_plan_bubbles(windows, model.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
         stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, cursor=C.c_int32(0)))
 
-    def run_step(i):
-        st = stages[i % p]
-        return pf.pf_timeline_run(model.ctx, None, None, p, m, st["stage"], tf, tb, st["windows"], st["plan"],
-                                  st["n_plan"], model.chain, st["cursor"], fill.cuda_stream, main_s.cuda_stream)
+    run_step = stage_stepper(pf, model, stages, args, p, m, tf, tb, fill, main_s)
 
     for i in range(args.warmup):
-        run_step(i)
+        run_step(0)
+    run_step.reset()
     _, steps0 = model.ctx.pf_ctx_train_state()
     torch.cuda.synchronize()
     agg = dict.fromkeys(AGG_KEYS, 0)
@@ -314,7 +355,7 @@ def run_cfg4(args, np, torch, pf, dev, synth):
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": f"{name}: 12-layer bf16 causal decoder TRAINING fill job d=1024 h=16 ff=4096 seq=1024 "
                                f"microbatch=8, fwd + recompute/bwd + Adam every 4 microbatches, gradients accumulated "
-                               f"across bubbles, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 16 GiB free, stages in rotation",
+                               f"across bubbles, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 16 GiB free, all {p} stages, {max(1, args.steps // p)} consecutive iteration(s) each",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns},
         **fill_stats(agg), "main_slowdown_pct": None,
         "fill_tflops_in_bubbles": agg["replicas_done"] * step_flops / (agg["offered_ns"] * 1e-9) * 1e-12,
@@ -368,6 +409,7 @@ def run_cfg5(args, np, torch, pf, dev, synth):
     windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, 8 * GIB, True, 2 * max(n.dur_ns for n in fm.chain))
     plan, n_plan, k = pf.pf_plan_bubbles(windows, fm.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
     cursor = C.c_int32(0)
+    fm.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
 
     def run_iter(with_fill):
         return pf.pf_timeline_run(fm.ctx if with_fill else None, main.ctx, x.data_ptr(), p, m, stage, tf, tb, windows,
@@ -424,6 +466,9 @@ def main():
     ap.add_argument("--stage", type=int, default=7, help="pipeline stage emulated by cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=4)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device-to-device copy 10 times (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the fill path has no cross-GPU step "
@@ -444,6 +489,15 @@ def main():
     from paper_2410_07192_amd import device as dev
     from paper_2410_07192_amd import synth
 
+    if args.copy_calibration:
+        n = 256 << 20
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}))
+        return
     run = {"cfg2": run_cfg2, "cfg3": run_cfg3, "cfg4": run_cfg4, "cfg5": run_cfg5}[args.workload]
     out = run(args, np, torch, pf, dev, synth)
     print(json.dumps(out))

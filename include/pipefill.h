@@ -259,6 +259,17 @@ typedef struct pf_timeline_stats {
   int32_t replicas_done;    /* replicas of the chain completed in this iteration                 */
 } pf_timeline_stats;
 
+/* What the Executor does when a plan completes (all its replicas ran) in the middle of a bubble
+ * cycle.  enable == 0 (the default): the same plan is reused and the remaining windows of the
+ * cycle stay empty until its first bubble comes round again.  enable != 0: the completed fill
+ * job is followed at once by the next one (Sec. 4.3: the Executor asks for the next job when
+ * one completes): the chain is partitioned again by Algorithm 1 with fill_ppm / switch_ns,
+ * starting at the fillable window after the one that took the last chunk; the new plan is kept
+ * inside the context and replaces the caller's plan in later pf_timeline_run calls on it.  Every
+ * call of this function drops a plan kept earlier (call it when the windows or the chain
+ * change).  PF_ERR_ARG on a bad fraction or switch time. */
+int32_t pf_ctx_set_replan(pf_ctx* ctx, int32_t enable, int64_t fill_ppm, int64_t switch_ns);
+
 /* One iteration of an emulated 1F1B stage with the Executor's bubble loop inside it
  * (Sec. 4.2 signalling, Sec. 4.3 "Bubble synchronization and memory capping").
  * windows/nW: the stage's idle windows in time order (from pf_schedule_1f1b).  The stage's busy
@@ -267,8 +278,9 @@ typedef struct pf_timeline_stats {
  * next planned chunk plan[*cursor] whose bubble index equals the window is launched on
  * fill_stream with the window's free_bytes as cap, and the window is held open on the host for
  * its dur_ns.  fill_ctx may be NULL (no filling: the baseline for slowdown).  *cursor (host,
- * in/out) advances over plan[0..n_plan); when it reaches n_plan it wraps to 0 (the plan is
- * cyclic: the same chunks serve new replicas).  Synchronises the device at the end.
+ * in/out) advances over plan[0..n_plan); when it reaches n_plan it wraps to 0 and the next
+ * plan pass serves new replicas (same plan, or a new one: pf_ctx_set_replan; *cursor then
+ * indexes the plan kept in the context).  Synchronises the device at the end.
  * Explicit cycles: with p == 0 (m, stage, tf_ns, tb_ns ignored, main_ctx must be NULL) the windows are
  * taken as given: before window k the fill and copy streams stay idle for start_ns[k] minus the end
  * of window k-1 (start_ns[0] for the first), then the window opens for dur_ns[k]. */

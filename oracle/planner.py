@@ -272,7 +272,7 @@ def chain_nodes(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, 
     total += 2 * act + mid + 2 * lse + 6 * stat                    # recompute outputs and statistics
     t_a = _al256(max(tokens * f, 3 * tokens * d) * esize)
     total += mid + 3 * act + 2 * act + t_a + mid                   # backward tensors and the two transposes
-    total += _al256(256 * 4 * 2 * d * 4)                           # LayerNorm-backward partial sums
+    total += _al256(128 * 4 * 2 * d * 4)                           # LayerNorm-backward partial sums
     total += 2 * _al256(tokens * vp * esize) + 256                 # logits, their transpose, loss cell
     nodes.append((OP_EMBED, -1, 0, g, total))
     for l in range(L):

@@ -48,7 +48,7 @@ hipError_t transpose2d(int32_t dtype, const void* in, void* out, int64_t R, int6
 hipError_t colsum_add(int32_t dtype, const void* x, float* acc, int64_t rows, int64_t N, hipStream_t stream);
 // LayerNorm backward: dx = LN'(dy) (+ resid), dg += sum dy*xhat, db += sum dy.  dx may alias resid or dy.
 // partial: fp32 scratch of LN_BWD_MAX_BLOCKS * 4 * 2 * d elements.
-constexpr int64_t LN_BWD_MAX_BLOCKS = 256;
+constexpr int64_t LN_BWD_MAX_BLOCKS = 128;
 hipError_t layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
                          const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
                          int64_t rows, int32_t d, hipStream_t stream);

@@ -95,6 +95,9 @@ struct pf_ctx {
   void* out = nullptr;
   int32_t n_out = 0;
   int64_t replica_base = 0;       // replicas completed by earlier passes over a cyclic plan
+  bool replan = false;            // partition again, from the next bubble, when a plan completes
+  int64_t replan_ppm = 1000000, replan_switch_ns = 0;
+  std::vector<pf_chunk> active_plan;   // plan made by the last such re-partitioning (empty: caller's plan)
   // the hidden states currently carried come from here when the next node starts a replica
   int32_t device = 0;
   pf::TrainState* tr = nullptr;   // training contexts only

@@ -591,6 +591,10 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
     }
   } else if (p < 1 || m < 1 || stage < 0 || stage >= p || tf_ns <= 0 || tb_ns <= 0 || nW < 0 || (nW > 0 && !W) || !stats)
     return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad schedule argument");
+  if (fc && fc->replan && !fc->active_plan.empty()) {   // the plan of the fill job now running
+    plan = fc->active_plan.data();
+    n_plan = (int32_t)fc->active_plan.size();
+  }
   if (fc && (!plan || n_plan <= 0 || !F || nF <= 0 || !cursor || *cursor < 0 || *cursor >= n_plan))
     return pf::fail(PF_ERR_ARG, "pf_timeline_run: bad plan argument");
   hipStream_t fs = (hipStream_t)fill_stream, mstr = (hipStream_t)main_stream;
@@ -692,6 +696,32 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
       if (++*cursor == n_plan) {
         *cursor = 0;
         fc->replica_base += plan[n_plan - 1].node_end / nF;
+        if (fc->replan && rc == PF_OK) {
+          // the job is complete: partition the next one from the fillable window after this one
+          int32_t ord = 0, n_fill = 0;
+          for (int32_t k = 0; k < nW; ++k) {
+            if (!W[k].fillable) continue;
+            if (k <= in.index) ++ord;
+            ++n_fill;
+          }
+          const int32_t first = ord % n_fill;
+          int32_t n_new = 0;
+          std::vector<pf_chunk> next;
+          int32_t prc = pf_plan_bubbles(W, nW, F, nF, fc->replan_ppm, fc->replan_switch_ns, first, nullptr, 0,
+                                        &n_new, nullptr);
+          if (prc == PF_ERR_CAPACITY || prc == PF_OK) {
+            next.resize((size_t)n_new);
+            prc = pf_plan_bubbles(W, nW, F, nF, fc->replan_ppm, fc->replan_switch_ns, first, next.data(), n_new,
+                                  &n_new, nullptr);
+          }
+          if (prc != PF_OK || n_new <= 0) {
+            rc = prc != PF_OK ? prc : pf::fail(PF_ERR_STATE, "pf_timeline_run: empty plan");
+          } else {
+            fc->active_plan.swap(next);
+            plan = fc->active_plan.data();
+            n_plan = n_new;
+          }
+        }
       }
     }
     wait_until(deadline);
@@ -728,6 +758,16 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   (void)mb0; (void)mb1;
   if (tstream) (void)hipStreamDestroy(tstream);
   return rc;
+}
+
+int32_t pf_ctx_set_replan(pf_ctx* c, int32_t enable, int64_t fill_ppm, int64_t switch_ns) {
+  if (!c || fill_ppm < 0 || fill_ppm > 1000000 || switch_ns < 0)
+    return pf::fail(PF_ERR_ARG, "pf_ctx_set_replan: bad argument");
+  c->replan = enable != 0;
+  c->replan_ppm = fill_ppm;
+  c->replan_switch_ns = switch_ns;
+  c->active_plan.clear();
+  return PF_OK;
 }
 
 int32_t pf_ctx_train_state(pf_ctx* c, double* loss, int64_t* steps) {

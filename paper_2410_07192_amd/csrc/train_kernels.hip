@@ -117,15 +117,25 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict_
   }
 }
 
-// dst[c] += sum over rows of partial[row][c]  (partial is [n_rows][width])
-__global__ __launch_bounds__(256) void reduce_rows_add_kernel(const float* __restrict__ partial, float* __restrict__ dg,
-                                                              float* __restrict__ db, int32_t n_rows, int32_t d) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= 2 * d) return;
+// dg[c] / db[c] += sum over rows of partial[row][c]  (partial is [n_rows][2*d]).  64 columns per
+// workgroup, 16 row lanes per column, fixed summation order (deterministic).
+__global__ __launch_bounds__(1024) void reduce_rows_add_kernel(const float* __restrict__ partial, float* __restrict__ dg,
+                                                               float* __restrict__ db, int32_t n_rows, int32_t d) {
+  __shared__ float red[16][64];
+  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cx;
   float s = 0.f;
-  for (int r = 0; r < n_rows; ++r) s += partial[(int64_t)r * 2 * d + c];
-  if (c < d) dg[c] += s;
-  else db[c - d] += s;
+  if (c < 2 * d)
+    for (int r = ry; r < n_rows; r += 16) s += partial[(int64_t)r * 2 * d + c];
+  red[ry][cx] = s;
+  __syncthreads();
+  if (ry == 0 && c < 2 * d) {
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t += red[k][cx];
+    if (c < d) dg[c] += t;
+    else db[c - d] += t;
+  }
 }
 
 // ---- attention backward, one thread per row ----------------------------------------------------------
@@ -420,7 +430,7 @@ static hipError_t launch_ln_bwd(const void* dy, const void* x, const void* g, co
   else if (iters <= 16) PF_LNB(16);
   else return hipErrorInvalidValue;
 #undef PF_LNB
-  hipLaunchKernelGGL(reduce_rows_add_kernel, dim3((unsigned)((2 * d + 255) / 256)), dim3(256), 0, st, partial, dg, db,
+  hipLaunchKernelGGL(reduce_rows_add_kernel, dim3((unsigned)((2 * d + 63) / 64)), dim3(1024), 0, st, partial, dg, db,
                      (int32_t)(blocks * 4), d);
   return hipGetLastError();
 }

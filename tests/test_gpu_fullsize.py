@@ -164,3 +164,85 @@ def test_explicit_bubble_cycle_timeline():
     finally:
         for m, _, _ in models:
             m.close()
+
+
+def _simulate_jobs(windows, F, ppm, sw, iters):
+    """Chunks and completed replicas per iteration when every completed fill job is followed by a new one
+    partitioned (by the checker) from the next fillable window."""
+    fill_idx = [i for i, w in enumerate(windows) if w["fillable"]]
+    chunks, _ = op.partition_fill_job(windows, F, ppm, 0, sw)
+    cur, out = 0, []
+    for _ in range(iters):
+        c = r = 0
+        for wi, w in enumerate(windows):
+            if not w["fillable"] or chunks[cur]["bubble"] != wi:
+                continue
+            ch = chunks[cur]
+            if ch["node_end"] > ch["node_begin"]:
+                c += 1
+                r += sum(1 for j in range(ch["node_begin"], ch["node_end"]) if j % len(F) == len(F) - 1)
+            cur += 1
+            if cur == len(chunks):
+                chunks, _ = op.partition_fill_job(windows, F, ppm, (fill_idx.index(wi) + 1) % len(fill_idx), sw)
+                cur = 0
+        out.append((c, r))
+    return out
+
+
+def test_next_job_is_planned_from_the_following_bubble():
+    """A plan that ends in the middle of a cycle: with re-planning on, the next job starts in the very next
+    fillable window (chunk and replica counts per iteration equal the checker's simulation, and the
+    outputs stay right); with it off, the rest of the cycle stays empty."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(3, 128, 2, 256, 64, 2, 300, False, "bf16")
+    params = synth.make_model_params(shape, seed=31)
+    n_ring = 3
+    ids = np.stack([synth.make_token_ids(shape, seed=900 + r)[None] for r in range(n_ring)])
+    st, main = torch.cuda.Stream(), torch.cuda.Stream()
+    m = dev.DeviceModel(shape, params)
+    try:
+        d_in = dev.to_device(ids.astype(np.int32))
+        d_out = dev.empty_storage((n_ring, 1, shape.batch, shape.seq_len, shape.d_model), m.md)
+        m.set_io(d_in, n_ring, d_out, n_ring)
+        for n in m.chain:                      # planning durations set by hand (well above the real ones)
+            n.dur_ns = 400_000
+        nF = len(m.chain)                      # embed, 3 layers, final LN: 5 nodes, 2 ms a replica
+        gap = 100_000
+        durs, fillable = [1_700_000, 700_000, 1_300_000, 1_900_000], [1, 1, 0, 1]
+        windows, t = [], gap
+        for d, f in zip(durs, fillable):
+            windows.append(dict(start=t, dur=d, free=1 << 30, kind=3, fillable=f))
+            t += d + gap
+        F = [(n.dur_ns, n.mem_bytes) for n in m.chain]
+        iters = 6
+        want = _simulate_jobs(windows, F, 1_000_000, 0, iters)
+        assert len({c for c, _ in want}) > 1 or want[0][0] == 3   # the simulation really changes phase
+        plan, n_plan, k = pf.pf_plan_bubbles(windows, m.chain, 1_000_000, 0, 0, raw=True)
+        assert n_plan % 3 != 0                 # the plan ends inside a cycle
+        m.ctx.pf_ctx_set_replan(True, 1_000_000, 0)
+        cursor = C.c_int32(0)
+        got = []
+        for _ in range(iters):
+            s = pf.pf_timeline_run(m.ctx, None, None, 0, 0, 0, 0, 0, windows, plan, n_plan, m.chain, cursor,
+                                   st.cuda_stream, main.cuda_stream)
+            assert s["overrun_ns"] == 0
+            got.append((s["chunks_run"], s["replicas_done"]))
+        assert got == want
+        assert sum(r for _, r in got) >= n_ring
+        out = dev.read_storage(d_out, m.md)
+        for r in range(n_ring):
+            ref = ot.model_forward(ids[r, 0], ot.cast_params(params), shape.n_heads, False, shape.eps)
+            assert rel_err(out[r, 0], ref) < 2e-2, r
+        # without re-planning the plan restarts only at its first bubble
+        m.ctx.pf_ctx_set_replan(False)
+        cursor = C.c_int32(0)
+        chunks_off = 0
+        for _ in range(iters):
+            s = pf.pf_timeline_run(m.ctx, None, None, 0, 0, 0, 0, 0, windows, plan, n_plan, m.chain, cursor,
+                                   st.cuda_stream, main.cuda_stream)
+            chunks_off += s["chunks_run"]
+        assert chunks_off < sum(c for c, _ in want)
+        with pytest.raises(pf.PipeFillError):
+            m.ctx.pf_ctx_set_replan(True, 2_000_000, 0)
+    finally:
+        m.close()
