@@ -58,7 +58,7 @@ __device__ __forceinline__ void epilogue4_vec(float v[4], int64_t m, int64_t n0,
   if (pre) store4(pre + off, v);
   if (ep.gelu) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
+    for (int j = 0; j < 4; ++j) v[j] = gelu_as<T>(v[j]);
   }
   if (dact) {
     load4(dact + off, t);
@@ -93,7 +93,7 @@ __device__ __forceinline__ void epilogue4_scalar(float v[4], int64_t m, int64_t 
       float x = v[j] * ep.scale;
       if (bias) x += to_f32(bias[n0 + j]);
       if (pre) pre[off + j] = from_f32<T>(x);
-      if (ep.gelu) x = gelu_f(x);
+      if (ep.gelu) x = gelu_as<T>(x);
       if (dact) x *= gelu_grad_f(to_f32(dact[off + j]));
       if (resid) x += to_f32(resid[off + j]);
       if (ep.accumulate) x += to_f32(C[off + j]);
@@ -117,7 +117,7 @@ __device__ __forceinline__ void epilogue4_static(float v[4], const float bias4[4
   if constexpr (EPI & E_PRE) store4((bf16_t*)ep.preact_out + off, v);
   if constexpr (EPI & E_GELU) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
+    for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
   }
   if constexpr (EPI & E_DACT) {
     load4((const bf16_t*)ep.dact_in + off, t);
@@ -304,15 +304,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
     src[i] = (isx ? X : W) + row * K + c * 8;
   }
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)smem);
-  auto issue = [&](int stage, int64_t k0) {
-#pragma unroll
-    for (int i = 0; i < GPW; ++i) {
-      const int g = wave + i * NW;
-      const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)((stage * STAGE + g * 64) * 16));
-      const bf16_t* p = src[i] + k0;
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p)
-                   : "memory", "m0");
-    }
+  // one 1 KB group of the stage at k0 straight into LDS stage `stage` (M0 carries the LDS address)
+  auto issue1 = [&](auto ic, int stage, int64_t k0) {
+    constexpr int i = decltype(ic)::value;
+    const int g = wave + i * NW;
+    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)((stage * STAGE + g * 64) * 16));
+    const bf16_t* p = src[i] + k0;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p)
+                 : "memory", "m0");
   };
   int offW[TN], offX[TM], swW[TN], swX[TM];
 #pragma unroll
@@ -342,48 +341,62 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
 #pragma unroll
     for (int b = 0; b < TM; ++b) fx[buf][b] = as_bf16x8(st[offX[b] + (c ^ swX[b])]);
   };
-  auto mfmas = [&](int buf) {
-#pragma unroll
-    for (int a = 0; a < TN; ++a)
-#pragma unroll
-      for (int b = 0; b < TM; ++b)
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][a], fx[buf][b], acc[a][b], 0, 0, 0);
+  // A burst of loads right after the barrier blocks every wave at the texture-address unit (1 KB per
+  // instruction at 64 B/clk) while the MFMA pipe drains; instead one load is issued before every EVERY-th
+  // MFMA of the block after the barrier (index 0) and of the first SPREAD-1 blocks of the next iteration.
+  constexpr int MF = TM * TN, SPREAD = 3, EVERY = SPREAD * MF / GPW;
+  static_assert(EVERY >= 1 && EVERY * GPW <= SPREAD * MF, "load slots");
+  auto mfma_block = [&](auto blkc, auto bufc, bool do_load, int stage, int64_t k0) {
+    constexpr int blk = decltype(blkc)::value, buf = decltype(bufc)::value;
+    static_for<0, MF>([&](auto mi) {
+      constexpr int g = blk * MF + mi;
+      if constexpr (blk < SPREAD && g % EVERY == 0 && g / EVERY < GPW) {
+        if (do_load) issue1(std::integral_constant<int, g / EVERY>{}, stage, k0);
+      }
+      constexpr int a = mi / TM, b = mi % TM;
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][a], fx[buf][b], acc[a][b], 0, 0, 0);
+    });
   };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
 
   const int64_t nk = K / 64;
-  issue(0, 0);
-  if (nk > 1) {
-    issue(1, 64);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(GPW) : "memory");   // stage 0 has landed, stage 1 in flight
-  } else {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  }
+  // prologue: stage 0 completely; of stage 1 the share the block after a barrier issues
+  static_for<0, GPW>([&](auto i) { issue1(i, 0, 0); });
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
+  if (nk > 1) {
+    static_for<0, MF>([&](auto mi) {
+      if constexpr (mi % EVERY == 0 && mi / EVERY < GPW) issue1(std::integral_constant<int, mi / EVERY>{}, 1, 64);
+    });
+  }
   load_frags(0, smem, 0);
   for (int64_t kt = 0; kt < nk; ++kt) {
     const int cur = (int)(kt & 1);
     const uint4* sc = smem + cur * STAGE;
     const uint4* sn = smem + (cur ^ 1) * STAGE;
+    const bool more1 = kt + 1 < nk, more2 = kt + 2 < nk;
     __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): fragments fetched during the previous MFMA block
     load_frags(1, sc, 1);
     __builtin_amdgcn_sched_barrier(0);
-    mfmas(0);
+    mfma_block(I1{}, I0{}, more1, cur ^ 1, (kt + 1) * 64);
     __builtin_amdgcn_sched_barrier(0);
     load_frags(0, sc, 2);
     __builtin_amdgcn_sched_barrier(0);
-    mfmas(1);
+    mfma_block(I2{}, I1{}, more1, cur ^ 1, (kt + 1) * 64);
     __builtin_amdgcn_sched_barrier(0);
     load_frags(1, sc, 3);
     __builtin_amdgcn_sched_barrier(0);
-    mfmas(0);
+    mfma_block(I3{}, I0{}, more1, cur ^ 1, (kt + 1) * 64);
     __builtin_amdgcn_sched_barrier(0);
     // every wave holds the last fragments of this stage in registers and the next stage has landed
     __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
-    if (kt + 2 < nk) issue(cur, (kt + 2) * 64);
-    if (kt + 1 < nk) load_frags(0, sn, 0);
+    if (more1) load_frags(0, sn, 0);
     __builtin_amdgcn_sched_barrier(0);
-    mfmas(1);
+    mfma_block(I0{}, I1{}, more2, cur, (kt + 2) * 64);   // stage `cur` is free: start refilling it
     __builtin_amdgcn_sched_barrier(0);
   }
 
@@ -418,11 +431,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
             }
             if constexpr (EPI & E_GELU) {
 #pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] = gelu_f(v[j]);
+              for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
             }
             uint2 pk;
-            pk.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-            pk.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+            pk.x = pack_bf16x2(v[0], v[1]);
+            pk.y = pack_bf16x2(v[2], v[3]);
             const int slot = (wn * TN + a) * 4 + rg;
             st8[row * (SLOTS * 2) + ((slot ^ (row & (SLOTS - 1))) * 2) + lk] = pk;
           });
@@ -443,7 +456,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
           for (int j = 0; j < 4; ++j) {
             const float lo = bf16_bits_to_f32(vw[j] & 0xffffu) + bf16_bits_to_f32(rw[j] & 0xffffu);
             const float hi = bf16_bits_to_f32(vw[j] >> 16) + bf16_bits_to_f32(rw[j] >> 16);
-            ow[j] = f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+            ow[j] = pack_bf16x2(lo, hi);
           }
           v = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }

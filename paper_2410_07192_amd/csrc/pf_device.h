@@ -29,6 +29,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return u >> 16;
 }
 
+// two floats to packed bf16 (lo in bits 0..15) with the hardware conversion: round to nearest even
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_bits_to_f32(v.bits); }
 
@@ -60,8 +68,8 @@ __device__ __forceinline__ void store4(float* p, const float v[4]) {
 }
 __device__ __forceinline__ void store4(bf16_t* p, const float v[4]) {
   uint2 t;
-  t.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-  t.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
+  t.x = pack_bf16x2(v[0], v[1]);
+  t.y = pack_bf16x2(v[2], v[3]);
   *(uint2*)p = t;
 }
 
@@ -85,10 +93,10 @@ __device__ __forceinline__ void store8(float* p, const float v[8]) {
 }
 __device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
   uint4 t;
-  t.x = f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16);
-  t.y = f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16);
-  t.z = f32_to_bf16_bits(v[4]) | (f32_to_bf16_bits(v[5]) << 16);
-  t.w = f32_to_bf16_bits(v[6]) | (f32_to_bf16_bits(v[7]) << 16);
+  t.x = pack_bf16x2(v[0], v[1]);
+  t.y = pack_bf16x2(v[2], v[3]);
+  t.z = pack_bf16x2(v[4], v[5]);
+  t.w = pack_bf16x2(v[6], v[7]);
   *(uint4*)p = t;
 }
 
@@ -108,6 +116,24 @@ __device__ __forceinline__ float erf_fast(float x) {
 
 // GELU in the erf form, x * Phi(x), and its derivative Phi(x) + x * phi(x)
 __device__ __forceinline__ float gelu_f(float x) { return 0.5f * x * (1.0f + erf_fast(x * 0.70710678118654752f)); }
+// x * sigmoid(x * (c1 + c3 x^2 + c5 x^4)): minimax fit of the erf form over [-8, 8], absolute error of
+// the product <= 2.6e-5 (a hundredth of a bf16 ulp at 1), used where the result is rounded to bf16
+// anyway.  One exp2 and one reciprocal; the coefficients carry the factor -log2(e).  x^2 is clamped so the
+// polynomial stays positive: beyond |x| = 7 the sigmoid is saturated in fp32 either way.
+__device__ __forceinline__ float gelu_bf16_f(float x) {
+  const float x2 = fminf(x * x, 49.0f);
+  float p = fmaf(1.01426451e-03f, x2, -1.06775722e-01f);   // -log2e * (c5 x2 + c3)
+  p = fmaf(p, x2, -2.30112133e+00f);                        // -log2e * c1
+  const float e = __builtin_amdgcn_exp2f(x * p);
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+template <typename T>
+__device__ __forceinline__ float gelu_as(float x);   // GELU for results stored as T
+template <>
+__device__ __forceinline__ float gelu_as<float>(float x) { return gelu_f(x); }
+template <>
+__device__ __forceinline__ float gelu_as<bf16_t>(float x) { return gelu_bf16_f(x); }
+
 __device__ __forceinline__ float gelu_grad_f(float x) {
   return 0.5f * (1.0f + erf_fast(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
 }
