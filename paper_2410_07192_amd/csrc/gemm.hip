@@ -20,138 +20,25 @@
 // bf16 generic path (any K multiple of 8): register-staged LDS tiles, same MFMA layout.
 // fp32 path (small parity workload only): plain LDS-tiled FMA kernel with the same epilogue.
 #include "pf_kernels.h"
-#include "pf_device.h"
-
-#include <type_traits>
+#include "gemm_tile.h"
 
 namespace pf {
+namespace gemm {
+
+extern template hipError_t launch_fast<bf16_t, 0>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<bf16_t, E_BIAS>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<bf16_t, E_BIAS | E_GELU>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<bf16_t, E_BIAS | E_RESID>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<bf16_t, E_BIAS | E_GELU | E_PRE>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<bf16_t, E_DACT>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<float, 0>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+extern template hipError_t launch_fast<float, E_ACC>(const void*, const void*, void*, int64_t, int64_t, int64_t, const EpiDev&, hipStream_t);
+
+}  // namespace gemm
+
 namespace {
 
-struct EpiDev {
-  const void* bias;
-  const void* resid;
-  const void* dact_in;
-  void* preact_out;
-  int32_t gelu, accumulate;
-  float scale;
-};
-
-// Epilogue for 4 consecutive columns n0..n0+3 of row m.  T = storage type of bias / resid / aux,
-// OutT = type of C.  The vector form needs n0+3 < N and N % 4 == 0; the scalar form checks every
-// element.
-template <typename T, typename OutT>
-__device__ __forceinline__ void epilogue4_vec(float v[4], int64_t m, int64_t n0, int64_t N, OutT* C,
-                                              const EpiDev& ep) {
-  const int64_t off = m * N + n0;
-  const T* bias = (const T*)ep.bias;
-  const T* resid = (const T*)ep.resid;
-  const T* dact = (const T*)ep.dact_in;
-  T* pre = (T*)ep.preact_out;
-  float t[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) v[j] *= ep.scale;
-  if (bias) {
-    load4(bias + n0, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += t[j];
-  }
-  if (pre) store4(pre + off, v);
-  if (ep.gelu) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = gelu_as<T>(v[j]);
-  }
-  if (dact) {
-    load4(dact + off, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_f(t[j]);
-  }
-  if (resid) {
-    load4(resid + off, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += t[j];
-  }
-  if (ep.accumulate) {
-    load4(C + off, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += t[j];
-  }
-  store4(C + off, v);
-}
-
-template <typename T, typename OutT>
-__device__ __forceinline__ void epilogue4_scalar(float v[4], int64_t m, int64_t n0, int64_t M, int64_t N, OutT* C,
-                                                 const EpiDev& ep) {
-  if (m >= M) return;
-  const int64_t off = m * N + n0;
-  const T* bias = (const T*)ep.bias;
-  const T* resid = (const T*)ep.resid;
-  const T* dact = (const T*)ep.dact_in;
-  T* pre = (T*)ep.preact_out;
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    if (n0 + j < N) {
-      float x = v[j] * ep.scale;
-      if (bias) x += to_f32(bias[n0 + j]);
-      if (pre) pre[off + j] = from_f32<T>(x);
-      if (ep.gelu) x = gelu_as<T>(x);
-      if (dact) x *= gelu_grad_f(to_f32(dact[off + j]));
-      if (resid) x += to_f32(resid[off + j]);
-      if (ep.accumulate) x += to_f32(C[off + j]);
-      C[off + j] = from_f32<OutT>(x);
-    }
-  }
-}
-
-// Epilogue features the main kernel is specialised on (so that its loads carry no branches and the
-// compiler can batch them); other combinations run on the generic kernel.
-enum : int { E_BIAS = 1, E_GELU = 2, E_RESID = 4, E_DACT = 8, E_PRE = 16, E_ACC = 32 };
-
-template <int EPI, typename OutT>
-__device__ __forceinline__ void epilogue4_static(float v[4], const float bias4[4], int64_t off, OutT* C,
-                                                 const EpiDev& ep) {
-  float t[4];
-  if constexpr (EPI & E_BIAS) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += bias4[j];
-  }
-  if constexpr (EPI & E_PRE) store4((bf16_t*)ep.preact_out + off, v);
-  if constexpr (EPI & E_GELU) {
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
-  }
-  if constexpr (EPI & E_DACT) {
-    load4((const bf16_t*)ep.dact_in + off, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] *= gelu_grad_f(t[j]);
-  }
-  if constexpr (EPI & E_RESID) {
-    load4((const bf16_t*)ep.resid + off, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += t[j];
-  }
-  if constexpr (EPI & E_ACC) {
-    load4(C + off, t);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) v[j] += t[j];
-  }
-  store4(C + off, v);
-}
-
-// compile-time loop: f(integral_constant<int, I>) for I in [0, N)
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f) {
-  if constexpr (I < N) {
-    f(std::integral_constant<int, I>{});
-    static_for<I + 1, N>(f);
-  }
-}
-
-// workgroup id -> tile id such that XCD x (ids congruent x mod 8) gets a contiguous tile range
-__device__ __forceinline__ int64_t xcd_tile(int64_t pid, int64_t n_tiles) {
-  const int64_t q = n_tiles >> 3, rem = n_tiles & 7;
-  const int64_t x = pid & 7, local = pid >> 3;
-  return x * q + (x < rem ? x : rem) + local;
-}
+using namespace gemm;
 
 // ------------------------------------------------------------------------------------------------
 template <int WGM, int WGN, int TM, int TN, typename OutT>
@@ -265,240 +152,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_generic_kernel(
 }
 
 // ------------------------------------------------------------------------------------------------
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
-template <int WGM, int WGN, int TM, int TN, typename OutT, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
-    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, OutT* __restrict__ C, int64_t M, int64_t N,
-    int64_t K, EpiDev ep, int32_t tiles_m, int32_t tiles_n, int32_t group_m) {
-  constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NW = WGM * WGN;
-  constexpr int GX = BM / 8, G = (BM + BN) / 8, GPW = G / NW;   // 8-row groups of 1 KB; per wave
-  constexpr int STAGE = (BM + BN) * 8;                          // uint4 per LDS stage
-  static_assert(G % NW == 0 && GPW <= 32, "tile / wave mismatch");
-  extern __shared__ uint4 smem[];
-
-  const int64_t tile = xcd_tile(blockIdx.x, (int64_t)tiles_m * tiles_n);
-  const int64_t per_group = (int64_t)group_m * tiles_n;
-  const int64_t grp = tile / per_group;
-  const int32_t first_m = (int32_t)(grp * group_m);
-  const int32_t rows_in_group = (tiles_m - first_m < group_m) ? tiles_m - first_m : group_m;
-  const int32_t tm_i = first_m + (int32_t)((tile % per_group) % rows_in_group);
-  const int32_t tn_i = (int32_t)((tile % per_group) / rows_in_group);
-  const int64_t m0 = (int64_t)tm_i * BM, n0 = (int64_t)tn_i * BN;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave % WGM, wn = wave / WGM;
-  const int lr = lane & 31, lk = lane >> 5;
-
-  // global source of this lane for each 1 KB group the wave moves per K step
-  const bf16_t* src[GPW];
-#pragma unroll
-  for (int i = 0; i < GPW; ++i) {
-    const int g = wave + i * NW;
-    const bool isx = g < GX;
-    const int r = (isx ? g : g - GX) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ ((r >> 1) & 7);
-    int64_t row = (isx ? m0 : n0) + r;
-    const int64_t lim = isx ? M : N;
-    if (row >= lim) row = lim - 1;
-    src[i] = (isx ? X : W) + row * K + c * 8;
-  }
-  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_ptr_t)smem);
-  // one 1 KB group of the stage at k0 straight into LDS stage `stage` (M0 carries the LDS address)
-  auto issue1 = [&](auto ic, int stage, int64_t k0) {
-    constexpr int i = decltype(ic)::value;
-    const int g = wave + i * NW;
-    const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)((stage * STAGE + g * 64) * 16));
-    const bf16_t* p = src[i] + k0;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p)
-                 : "memory", "m0");
-  };
-  int offW[TN], offX[TM], swW[TN], swX[TM];
-#pragma unroll
-  for (int a = 0; a < TN; ++a) {
-    const int r = (wn * TN + a) * 32 + lr;
-    offW[a] = BM * 8 + r * 8;
-    swW[a] = (r >> 1) & 7;
-  }
-#pragma unroll
-  for (int b = 0; b < TM; ++b) {
-    const int r = (wm * TM + b) * 32 + lr;
-    offX[b] = r * 8;
-    swX[b] = (r >> 1) & 7;
-  }
-  f32x16 acc[TN][TM];
-#pragma unroll
-  for (int a = 0; a < TN; ++a)
-#pragma unroll
-    for (int b = 0; b < TM; ++b)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
-  bf16x8 fw[2][TN], fx[2][TM];
-  auto load_frags = [&](int buf, const uint4* st, int kk) {
-    const int c = kk * 2 + lk;
-#pragma unroll
-    for (int a = 0; a < TN; ++a) fw[buf][a] = as_bf16x8(st[offW[a] + (c ^ swW[a])]);
-#pragma unroll
-    for (int b = 0; b < TM; ++b) fx[buf][b] = as_bf16x8(st[offX[b] + (c ^ swX[b])]);
-  };
-  // A burst of loads right after the barrier blocks every wave at the texture-address unit (1 KB per
-  // instruction at 64 B/clk) while the MFMA pipe drains; instead one load is issued before every EVERY-th
-  // MFMA of the block after the barrier (index 0) and of the first SPREAD-1 blocks of the next iteration.
-  constexpr int MF = TM * TN, SPREAD = 3, EVERY = SPREAD * MF / GPW;
-  static_assert(EVERY >= 1 && EVERY * GPW <= SPREAD * MF, "load slots");
-  auto mfma_block = [&](auto blkc, auto bufc, bool do_load, int stage, int64_t k0) {
-    constexpr int blk = decltype(blkc)::value, buf = decltype(bufc)::value;
-    static_for<0, MF>([&](auto mi) {
-      constexpr int g = blk * MF + mi;
-      if constexpr (blk < SPREAD && g % EVERY == 0 && g / EVERY < GPW) {
-        if (do_load) issue1(std::integral_constant<int, g / EVERY>{}, stage, k0);
-      }
-      constexpr int a = mi / TM, b = mi % TM;
-      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][a], fx[buf][b], acc[a][b], 0, 0, 0);
-    });
-  };
-  using I0 = std::integral_constant<int, 0>;
-  using I1 = std::integral_constant<int, 1>;
-  using I2 = std::integral_constant<int, 2>;
-  using I3 = std::integral_constant<int, 3>;
-
-  const int64_t nk = K / 64;
-  // prologue: stage 0 completely; of stage 1 the share the block after a barrier issues
-  static_for<0, GPW>([&](auto i) { issue1(i, 0, 0); });
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  if (nk > 1) {
-    static_for<0, MF>([&](auto mi) {
-      if constexpr (mi % EVERY == 0 && mi / EVERY < GPW) issue1(std::integral_constant<int, mi / EVERY>{}, 1, 64);
-    });
-  }
-  load_frags(0, smem, 0);
-  for (int64_t kt = 0; kt < nk; ++kt) {
-    const int cur = (int)(kt & 1);
-    const uint4* sc = smem + cur * STAGE;
-    const uint4* sn = smem + (cur ^ 1) * STAGE;
-    const bool more1 = kt + 1 < nk, more2 = kt + 2 < nk;
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): fragments fetched during the previous MFMA block
-    load_frags(1, sc, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_block(I1{}, I0{}, more1, cur ^ 1, (kt + 1) * 64);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(0, sc, 2);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_block(I2{}, I1{}, more1, cur ^ 1, (kt + 1) * 64);
-    __builtin_amdgcn_sched_barrier(0);
-    load_frags(1, sc, 3);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_block(I3{}, I0{}, more1, cur ^ 1, (kt + 1) * 64);
-    __builtin_amdgcn_sched_barrier(0);
-    // every wave holds the last fragments of this stage in registers and the next stage has landed
-    __builtin_amdgcn_s_waitcnt(0x0070);   // vmcnt(0) lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    if (more1) load_frags(0, sn, 0);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_block(I0{}, I1{}, more2, cur, (kt + 2) * 64);   // stage `cur` is free: start refilling it
-    __builtin_amdgcn_sched_barrier(0);
-  }
-
-  // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
-  // Indices into acc must be compile-time constants or the accumulators leave the register file.
-  const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
-  // Staged epilogue (bf16 output, no per-element side inputs other than bias / residual): bias and GELU
-  // are applied in registers, the bf16 tile goes through LDS (free after the K loop; 16-byte slots
-  // XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the tile, the residual
-  // being added on the way out from equally coalesced loads.
-  constexpr bool STAGED = std::is_same<OutT, bf16_t>::value && !(EPI & (E_PRE | E_DACT | E_ACC));
-  if constexpr (STAGED) {
-    const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid) & 15) == 0);
-    if (interior && aligned16) {
-      constexpr int SLOTS = BN / 8, NT = 64 * NW, PER = BM * BN / 8 / NT;
-      uint2* st8 = (uint2*)smem;
-      static_for<0, TN>([&](auto a) {
-        float bias4[4][4] = {};
-        if constexpr (EPI & E_BIAS) {
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg)
-            load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
-        }
-        static_for<0, TM>([&](auto b) {
-          const int row = (wm * TM + b) * 32 + lr;
-          static_for<0, 4>([&](auto rg) {
-            float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                          acc[a][b][rg * 4 + 3]};
-            if constexpr (EPI & E_BIAS) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] += bias4[rg][j];
-            }
-            if constexpr (EPI & E_GELU) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
-            }
-            uint2 pk;
-            pk.x = pack_bf16x2(v[0], v[1]);
-            pk.y = pack_bf16x2(v[2], v[3]);
-            const int slot = (wn * TN + a) * 4 + rg;
-            st8[row * (SLOTS * 2) + ((slot ^ (row & (SLOTS - 1))) * 2) + lk] = pk;
-          });
-        });
-      });
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_s_barrier();
-#pragma unroll 4
-      for (int i = 0; i < PER; ++i) {
-        const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-        uint4 v = smem[row * SLOTS + (slot ^ (row & (SLOTS - 1)))];
-        const int64_t off = (m0 + row) * N + n0 + slot * 8;
-        if constexpr (EPI & E_RESID) {
-          const uint4 r = *(const uint4*)((const bf16_t*)ep.resid + off);
-          const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, rw[4] = {r.x, r.y, r.z, r.w};
-          uint32_t ow[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float lo = bf16_bits_to_f32(vw[j] & 0xffffu) + bf16_bits_to_f32(rw[j] & 0xffffu);
-            const float hi = bf16_bits_to_f32(vw[j] >> 16) + bf16_bits_to_f32(rw[j] >> 16);
-            ow[j] = pack_bf16x2(lo, hi);
-          }
-          v = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-        }
-        *(uint4*)((bf16_t*)C + off) = v;
-      }
-      return;
-    }
-  }
-  if (interior) {
-    static_for<0, TN>([&](auto a) {
-      float bias4[4][4] = {};
-      if constexpr (EPI & E_BIAS) {
-#pragma unroll
-        for (int rg = 0; rg < 4; ++rg)
-          load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
-      }
-      static_for<0, TM>([&](auto b) {
-        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
-        static_for<0, 4>([&](auto rg) {
-          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
-          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                        acc[a][b][rg * 4 + 3]};
-          epilogue4_static<EPI, OutT>(v, bias4[rg], m * N + n, C, ep);
-        });
-      });
-    });
-  } else {
-    static_for<0, TN>([&](auto a) {
-      static_for<0, TM>([&](auto b) {
-        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
-        static_for<0, 4>([&](auto rg) {
-          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
-          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                        acc[a][b][rg * 4 + 3]};
-          epilogue4_scalar<bf16_t, OutT>(v, m, n, M, N, C, ep);
-        });
-      });
-    });
-  }
-}
-
-// ------------------------------------------------------------------------------------------------
 // fp32: 64x64 tile, K step 16, 256 threads, 4x4 outputs per thread.
 template <typename OutT>
 __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const float* __restrict__ X, const float* __restrict__ W,
@@ -535,42 +188,11 @@ __global__ __launch_bounds__(256) void gemm_f32_nt_kernel(const float* __restric
   for (int i = 0; i < 4; ++i) epilogue4_scalar<float, OutT>(acc[i], m0 + ty * 4 + i, n0 + tx * 4, M, N, C, ep);
 }
 
-template <typename OutT, typename Kern>
-hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, const void* X, const void* W, void* C,
-                        int64_t M, int64_t N, int64_t K, const EpiDev& ep, hipStream_t stream) {
-  const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  const size_t lds = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
-  if (!*attr_set) {   // raise the dynamic-LDS limit once per instantiation
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    *attr_set = true;
-  }
-  const int32_t group_m = 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(threads), lds, stream, (const bf16_t*)X,
-                     (const bf16_t*)W, (OutT*)C, M, N, K, ep,
-                     (int32_t)tiles_m, (int32_t)tiles_n, group_m);
-  return hipGetLastError();
-}
-
 template <typename OutT>
 hipError_t launch_generic(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
                           hipStream_t stream) {
   static bool attr = false;
   return launch_tiles<OutT>(gemm_bf16_nt_generic_kernel<2, 2, 2, 2, OutT>, 128, 128, 256, &attr, X, W, C, M, N, K, ep,
-                      stream);
-}
-
-// main kernel for one epilogue combination: 256x256 tiles (8 waves) once they give most of the 256 CUs a
-// tile, 128x128 tiles (4 waves, two workgroups per CU) below that
-template <typename OutT, int EPI>
-hipError_t launch_fast(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
-                       hipStream_t stream) {
-  static bool attr_big = false, attr_small = false;
-  const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
-  if (t256 >= 192)
-    return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 4, 4, 2, OutT, EPI>, 256, 256, 512, &attr_big, X, W, C, M, N, K, ep,
-                        stream);
-  return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 2, 2, 2, OutT, EPI>, 128, 128, 256, &attr_small, X, W, C, M, N, K, ep,
                       stream);
 }
 
