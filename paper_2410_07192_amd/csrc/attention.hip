@@ -22,9 +22,10 @@ constexpr float LN2 = 0.6931471805599453f;
 
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                             float* __restrict__ lse, int32_t S, int32_t h,
-                                                            int32_t causal, float scale_log2e) {
+                                                            int32_t causal, float scale_log2e, int32_t nq,
+                                                            int32_t n_wg) {
   constexpr int CPR = DH / 8;        // 16-byte chunks per K row
   constexpr int KS = DH / 16;        // MFMA K steps over d_head
   constexpr int DT = DH / 32;        // 32-row tiles of O^T
@@ -36,8 +37,12 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(const bf16_t* __rest
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int b = blockIdx.z, hd = blockIdx.y;
-  const int q_blk = blockIdx.x * 128;
+  // Workgroup ids are dealt round-robin to the 8 XCDs; remapped so that each XCD gets a contiguous range of
+  // (batch, head, query block) units, the query blocks of one head run on one XCD and its L2 serves their
+  // repeated reads of that head's K and V.
+  const int unit = (int)xcd_contiguous(blockIdx.x, n_wg);
+  const int b = unit / (nq * h), hd = (unit / nq) % h;
+  const int q_blk = (unit % nq) * 128;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;                       // row stride of qkv
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
@@ -286,14 +291,16 @@ hipError_t attention_fwd(int32_t dtype, const void* qkv, void* out, float* lse, 
                          int32_t dh, int32_t causal, hipStream_t stream) {
   if (B <= 0 || S <= 0 || h <= 0 || B > 65535 || h > 65535) return hipErrorInvalidValue;
   if (dtype == PF_DTYPE_BF16_ && (dh == 64 || dh == 128)) {
-    const dim3 grid((unsigned)((S + 127) / 128), (unsigned)h, (unsigned)B), block(256);
+    const int64_t nq = (S + 127) / 128, n_wg = nq * h * B;
+    if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)n_wg), block(256);
     const float sl = LOG2E / sqrtf((float)dh);
     if (dh == 64)
       hipLaunchKernelGGL(attn_fwd_bf16_kernel<64>, grid, block, 0, stream, (const bf16_t*)qkv, (bf16_t*)out, lse, S,
-                         h, causal, sl);
+                         h, causal, sl, (int32_t)nq, (int32_t)n_wg);
     else
       hipLaunchKernelGGL(attn_fwd_bf16_kernel<128>, grid, block, 0, stream, (const bf16_t*)qkv, (bf16_t*)out, lse, S,
-                         h, causal, sl);
+                         h, causal, sl, (int32_t)nq, (int32_t)n_wg);
     return hipGetLastError();
   }
   if (dtype == PF_DTYPE_BF16_) return launch_generic<bf16_t>(qkv, out, lse, B, S, h, dh, causal, stream);

@@ -80,12 +80,12 @@ __device__ __forceinline__ bf16x8 read_t_frag(const uint16_t* rowp) {
 
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_bf16_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kernel(const bf16_t* __restrict__ qkv,
                                                                 const bf16_t* __restrict__ dout,
                                                                 const float* __restrict__ lse,
                                                                 const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv,
                                                                 int32_t S, int32_t h, int32_t causal, float scale_log2e,
-                                                                float scale) {
+                                                                float scale, int32_t nblk, int32_t n_wg) {
   constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32, TP = 68;
   // dynamic LDS (68 KB for d_head 128): Q | dO tiles, their transposes, lse and D of the tile
   extern __shared__ uint4 dyn_smem[];
@@ -98,8 +98,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_bf16_kernel(const bf16_t* __
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int b = blockIdx.z, hd = blockIdx.y;
-  const int k_blk = blockIdx.x * 128;
+  // the key blocks of one (batch, head) run on one XCD: they all re-read that head's Q and dO
+  const int unit = (int)xcd_contiguous(blockIdx.x, n_wg);
+  const int b = unit / (nblk * h), hd = (unit / nblk) % h;
+  const int k_blk = (unit % nblk) * 128;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
@@ -203,12 +205,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_bf16_kernel(const bf16_t* __
 
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv,
                                                                const bf16_t* __restrict__ dout,
                                                                const float* __restrict__ lse,
                                                                const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv,
                                                                int32_t S, int32_t h, int32_t causal, float scale_log2e,
-                                                               float scale) {
+                                                               float scale, int32_t nblk, int32_t n_wg) {
   constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32, TP = 68;
   __shared__ uint4 sK[64 * CPR];
   __shared__ uint4 sV[64 * CPR];
@@ -216,8 +218,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_bf16_kernel(const bf16_t* __r
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  const int b = blockIdx.z, hd = blockIdx.y;
-  const int q_blk = blockIdx.x * 128;
+  // the query blocks of one (batch, head) run on one XCD: they all re-read that head's K and V
+  const int unit = (int)xcd_contiguous(blockIdx.x, n_wg);
+  const int b = unit / (nblk * h), hd = (unit / nblk) % h;
+  const int q_blk = (unit % nblk) * 128;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
@@ -312,7 +316,9 @@ hipError_t launch(const void* qkv, const void* o, const void* dout, const float*
   const int64_t n = (int64_t)B * S * h;
   hipLaunchKernelGGL(attn_bwd_prep_kernel<DH>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, (const bf16_t*)o,
                      (const bf16_t*)dout, Dsum, B, S, h);
-  const dim3 grid((unsigned)((S + 127) / 128), (unsigned)h, (unsigned)B), block(256);
+  const int64_t nblk = (S + 127) / 128, n_wg = nblk * h * B;
+  if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)n_wg), block(256);
   constexpr size_t lds = 2 * 64 * (DH / 8) * 16 + 2 * DH * 68 * 2 + 2 * 64 * 4;
   static bool attr_set = false;
   if (!attr_set) {
@@ -322,9 +328,9 @@ hipError_t launch(const void* qkv, const void* o, const void* dout, const float*
     attr_set = true;
   }
   hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<DH>, grid, block, lds, st, (const bf16_t*)qkv, (const bf16_t*)dout, lse,
-                     Dsum, (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale);
+                     Dsum, (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale, (int32_t)nblk, (int32_t)n_wg);
   hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<DH>, grid, block, 0, st, (const bf16_t*)qkv, (const bf16_t*)dout, lse, Dsum,
-                     (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale);
+                     (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale, (int32_t)nblk, (int32_t)n_wg);
   return hipGetLastError();
 }
 

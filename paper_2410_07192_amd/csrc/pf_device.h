@@ -138,6 +138,14 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   return 0.5f * (1.0f + erf_fast(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
 }
 
+// Workgroup ids are dealt round-robin to the 8 XCDs (id % 8).  Returns the work unit of workgroup `pid` such
+// that each XCD owns a contiguous range of the n units (its L2 then sees neighbouring units).
+__device__ __forceinline__ int64_t xcd_contiguous(int64_t pid, int64_t n) {
+  const int64_t q = n >> 3, rem = n & 7;
+  const int64_t x = pid & 7, local = pid >> 3;
+  return x * q + (x < rem ? x : rem) + local;
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
