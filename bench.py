@@ -197,6 +197,8 @@ def run_cfg2(args, np, torch, pf, dev, synth):
         s = run_step(i)
         for k_ in agg:
             agg[k_] += s[k_]
+        if args.verbose:
+            print(f"step {i}: " + " ".join(f"{k_}={s[k_]}" for k_ in AGG_KEYS), file=sys.stderr)
         model.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)      # folds this step's event pairs into the totals
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -466,6 +468,7 @@ def main():
     ap.add_argument("--stage", type=int, default=7, help="pipeline stage emulated by cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=4)
+    ap.add_argument("--verbose", action="store_true", help="per-step statistics on stderr (cfg2)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device-to-device copy 10 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")

@@ -158,6 +158,18 @@ int32_t pf_plan_bubbles(const pf_bubble* B, int32_t nB, const pf_node* F, int32_
                         int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
                         pf_chunk* out, int32_t cap, int32_t* n_out, int32_t* replicas);
 
+/* Algorithm 1 for a job that arrives when its first bubble is partly gone (Sec. 4.3: the Executor
+ * takes the next job as soon as one completes, which is in the middle of a bubble): exactly
+ * pf_plan_bubbles, except that the FIRST visit of bubble `first_bubble` has the duration
+ * first_dur_ns (what is left of it; the fill fraction and the switch time apply to it as to any
+ * bubble) instead of its dur_ns.  Later visits of that bubble, and the replication count, use
+ * dur_ns.  first_dur_ns < 0: no such shortening (identical to pf_plan_bubbles).  A first chunk
+ * that takes no node is an ordinary empty chunk. */
+int32_t pf_plan_bubbles_from(const pf_bubble* bubbles, int32_t n_bubbles, const pf_node* F, int32_t nF,
+                             int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
+                             int64_t first_dur_ns, pf_chunk* out, int32_t cap, int32_t* n_out,
+                             int32_t* replicas);
+
 /* Configuration choice (Sec. 4.1/4.3: the plan that maximises throughput).  chains[c] (host) has
  * n_nodes[c] nodes and processes samples[c] samples per replica.  Every configuration is
  * planned as above; the winner maximises samples*replicas / ceil(chunks / fillable bubbles),
@@ -264,7 +276,9 @@ typedef struct pf_timeline_stats {
  * cycle stay empty until its first bubble comes round again.  enable != 0: the completed fill
  * job is followed at once by the next one (Sec. 4.3: the Executor asks for the next job when
  * one completes): the chain is partitioned again by Algorithm 1 with fill_ppm / switch_ns,
- * starting at the fillable window after the one that took the last chunk; the new plan is kept
+ * starting in the window that took the last chunk (pf_plan_bubbles_from with first_dur_ns =
+ * the window's duration less ceil(planned duration of the chunks already launched in it * 1e6 /
+ * fill_ppm), so the new job is charged its own switch time there); the new plan is kept
  * inside the context and replaces the caller's plan in later pf_timeline_run calls on it.  Every
  * call of this function drops a plan kept earlier (call it when the windows or the chain
  * change).  PF_ERR_ARG on a bad fraction or switch time. */

@@ -116,8 +116,13 @@ def effective_durations(bubbles, fill_ppm=1_000_000, switch_ns=0):
     return eff
 
 
-def partition_fill_job(bubbles, F, fill_ppm=1_000_000, first_bubble=0, switch_ns=0):
+def partition_fill_job(bubbles, F, fill_ppm=1_000_000, first_bubble=0, switch_ns=0, first_dur=None):
     """Algorithm 1: partition a fill job onto the bubble cycle.
+
+    first_dur (Sec. 4.3, a job that is handed over when the previous one completes, i.e. in
+    the middle of a bubble): the first visit of the first bubble only lasts first_dur; the
+    fill fraction and the switch time apply to it like to any bubble.  Later visits and the
+    replication count use the bubble's own duration.
 
     bubbles: list of dicts with dur, free, fillable.   F: list of (dur, mem).
     Returns (chunks, replicas) where each chunk is a dict
@@ -151,7 +156,10 @@ def partition_fill_job(bubbles, F, fill_ppm=1_000_000, first_bubble=0, switch_ns
         begin = pos
         dur = 0
         mem = 0
-        while pos < len(Fp) and dur + Fp[pos][0] < B[i] and Fp[pos][1] <= M[i]:
+        limit = B[i]
+        if first_dur is not None and not chunks:
+            limit = max(first_dur * fill_ppm // 1_000_000 - switch_ns, 0)
+        while pos < len(Fp) and dur + Fp[pos][0] < limit and Fp[pos][1] <= M[i]:
             dur += Fp[pos][0]
             mem = max(mem, Fp[pos][1])
             pos += 1

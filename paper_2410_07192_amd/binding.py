@@ -21,7 +21,7 @@ PF_DTYPE_F32, PF_DTYPE_BF16 = 0, 1
 PF_INSTR_FWD, PF_INSTR_BWD, PF_INSTR_BUBBLE = 0, 1, 2
 
 EXPORTS = [
-    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles",
+    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from",
     "pf_select_config", "pf_build_chain", "pf_layer_blob_layout", "pf_ctx_arena_bytes", "pf_ctx_create",
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
@@ -95,6 +95,8 @@ def _load():
     lib.pf_schedule_1f1b.argtypes = [I32, I32, I32, I64, I64, I64, I32, I64, P(pf_bubble), I32, P(I32)]
     lib.pf_schedule_gpipe.argtypes = [I32, I32, I32, I64, I64, I64, P(pf_bubble), I32, P(I32)]
     lib.pf_plan_bubbles.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, P(pf_chunk), I32, P(I32), P(I32)]
+    lib.pf_plan_bubbles_from.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, I64, P(pf_chunk), I32, P(I32),
+                                         P(I32)]
     lib.pf_select_config.argtypes = [P(pf_bubble), I32, P(P(pf_node)), P(I32), P(I64), I32, I64, I64, I32,
                                      P(I32), P(I32), P(I32), P(I32)]
     lib.pf_build_chain.argtypes = [P(pf_model_desc), P(pf_exec_config), P(pf_node), I32, P(I32)]
@@ -175,24 +177,30 @@ def pf_schedule_gpipe(p, m, stage, tf_ns, tb_ns, free_bytes, cap=2):
     return [_bubble_dict(out[i]) for i in range(n.value)]
 
 
-def pf_plan_bubbles(bubbles, F, fill_ppm=1_000_000, switch_ns=0, first_bubble=0, cap=None, raw=False):
-    """Returns (chunks, replicas); chunks as dicts, or as the ctypes array and count when raw."""
+def pf_plan_bubbles(bubbles, F, fill_ppm=1_000_000, switch_ns=0, first_bubble=0, cap=None, raw=False,
+                    first_dur_ns=-1):
+    """Returns (chunks, replicas); chunks as dicts, or as the ctypes array and count when raw.
+    first_dur_ns >= 0 plans through pf_plan_bubbles_from (first visit of the first bubble shortened)."""
     B = bubbles_to_c(bubbles)
     Fc = nodes_to_c(F)
     nF = len(F)
     n = C.c_int32(0)
     k = C.c_int32(0)
     if cap is None:
-        rc = lib.pf_plan_bubbles(B, len(bubbles), Fc, nF, fill_ppm, switch_ns, first_bubble, None, 0,
-                                 C.byref(n), C.byref(k))
+        rc = lib.pf_plan_bubbles_from(B, len(bubbles), Fc, nF, fill_ppm, switch_ns, first_bubble, first_dur_ns,
+                                      None, 0, C.byref(n), C.byref(k))
         if rc not in (PF_OK, PF_ERR_CAPACITY):
             e = PipeFillError(rc, lib.pf_last_error().decode())
             e.node = n.value
             raise e
         cap = n.value
     out = (pf_chunk * max(1, cap))()
-    rc = lib.pf_plan_bubbles(B, len(bubbles), Fc, nF, fill_ppm, switch_ns, first_bubble, out, cap,
-                             C.byref(n), C.byref(k))
+    if first_dur_ns < 0:
+        rc = lib.pf_plan_bubbles(B, len(bubbles), Fc, nF, fill_ppm, switch_ns, first_bubble, out, cap,
+                                 C.byref(n), C.byref(k))
+    else:
+        rc = lib.pf_plan_bubbles_from(B, len(bubbles), Fc, nF, fill_ppm, switch_ns, first_bubble, first_dur_ns,
+                                      out, cap, C.byref(n), C.byref(k))
     if rc != PF_OK:
         e = PipeFillError(rc, lib.pf_last_error().decode())
         e.node = n.value

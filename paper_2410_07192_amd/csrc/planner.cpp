@@ -24,8 +24,9 @@ struct PlanResult {
 
 // Algorithm 1 (Sec. 4.3).  The replicated chain is never materialised: node j of it is
 // F[j % nF].  Chunks beyond `cap` are counted but not stored.
+// first_dur >= 0: the job arrives when the first bubble is partly gone; that visit (only) has this duration.
 PlanResult plan_impl(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t nF, int64_t ppm,
-                     int64_t sw, int32_t first, pf_chunk* out, int64_t cap) {
+                     int64_t sw, int32_t first, pf_chunk* out, int64_t cap, int64_t first_dur = -1) {
   PlanResult r;
   std::vector<int32_t> idx;
   std::vector<int64_t> dur, mem;
@@ -60,9 +61,10 @@ PlanResult plan_impl(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t n
   while (pos < n_nodes) {
     const int64_t begin = pos;
     int64_t cd = 0, cm = 0;
+    const int64_t limit = (r.n_chunks == 0 && first_dur >= 0) ? usable_ns(first_dur, ppm, sw) : dur[b];
     while (pos < n_nodes) {
       const pf_node& nd = F[pos % nF];
-      if (!(cd + nd.dur_ns < dur[b] && nd.mem_bytes <= mem[b])) break;
+      if (!(cd + nd.dur_ns < limit && nd.mem_bytes <= mem[b])) break;
       cd += nd.dur_ns;
       if (nd.mem_bytes > cm) cm = nd.mem_bytes;
       ++pos;
@@ -172,10 +174,16 @@ int32_t pf_schedule_gpipe(int32_t p, int32_t m, int32_t s, int64_t tf, int64_t t
 int32_t pf_plan_bubbles(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t nF, int64_t fill_ppm,
                         int64_t switch_ns, int32_t first_bubble, pf_chunk* out, int32_t cap,
                         int32_t* n_out, int32_t* replicas) {
+  return pf_plan_bubbles_from(B, nB, F, nF, fill_ppm, switch_ns, first_bubble, -1, out, cap, n_out, replicas);
+}
+
+int32_t pf_plan_bubbles_from(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t nF, int64_t fill_ppm,
+                             int64_t switch_ns, int32_t first_bubble, int64_t first_dur_ns, pf_chunk* out,
+                             int32_t cap, int32_t* n_out, int32_t* replicas) {
   if (bad_bubbles(B, nB) || bad_nodes(F, nF) || fill_ppm < 0 || fill_ppm > 1000000 || switch_ns < 0 ||
       cap < 0 || !n_out || (cap > 0 && !out))
     return pf::fail(PF_ERR_ARG, "pf_plan_bubbles: bad argument");
-  PlanResult r = plan_impl(B, nB, F, nF, fill_ppm, switch_ns, first_bubble, out, cap);
+  PlanResult r = plan_impl(B, nB, F, nF, fill_ppm, switch_ns, first_bubble, out, cap, first_dur_ns);
   if (replicas) *replicas = r.replicas;
   if (r.rc == PF_ERR_ARG) return pf::fail(PF_ERR_ARG, "pf_plan_bubbles: no fillable bubble, first_bubble out of range, or plan too large");
   if (r.rc == PF_ERR_INFEASIBLE) {

@@ -682,45 +682,51 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
     stats->idle_ns += w.dur_ns;
     if (w.fillable) stats->offered_ns += w.dur_ns;
     if (rc == PF_OK && fc && w.fillable && plan[*cursor].bubble == in.index) {
-      const pf_chunk& ch = plan[*cursor];
-      if (ch.node_end > ch.node_begin) {
-        Rec& r = recs[in.index];
-        hipck(hipEventRecord(r.fs0, fs), "record");
-        if (rc == PF_OK) rc = pf_fill_chunk(fc, &ch, F, nF, w.free_bytes, fill_stream);
-        if (rc == PF_OK) hipck(hipEventRecord(r.fs1, fs), "record");
-        r.used = (rc == PF_OK);
-        stats->chunks_run += 1;
-        for (int32_t j = ch.node_begin; j < ch.node_end; ++j)
-          if (j % nF == nF - 1) stats->replicas_done += 1;
-      }
-      if (++*cursor == n_plan) {
+      int64_t planned_ns = 0;   // planned duration of the chunks already launched in this window
+      for (bool again = true; again && rc == PF_OK;) {
+        again = false;
+        const pf_chunk ch = plan[*cursor];
+        if (ch.node_end > ch.node_begin) {
+          Rec& r = recs[in.index];
+          if (!r.used) hipck(hipEventRecord(r.fs0, fs), "record");
+          if (rc == PF_OK) rc = pf_fill_chunk(fc, &ch, F, nF, w.free_bytes, fill_stream);
+          if (rc == PF_OK) hipck(hipEventRecord(r.fs1, fs), "record");
+          r.used = r.used || (rc == PF_OK);
+          stats->chunks_run += 1;
+          for (int32_t j = ch.node_begin; j < ch.node_end; ++j)
+            if (j % nF == nF - 1) stats->replicas_done += 1;
+        }
+        planned_ns += ch.dur_ns;
+        if (++*cursor < n_plan) break;
         *cursor = 0;
         fc->replica_base += plan[n_plan - 1].node_end / nF;
-        if (fc->replan && rc == PF_OK) {
-          // the job is complete: partition the next one from the fillable window after this one
-          int32_t ord = 0, n_fill = 0;
-          for (int32_t k = 0; k < nW; ++k) {
-            if (!W[k].fillable) continue;
-            if (k <= in.index) ++ord;
-            ++n_fill;
-          }
-          const int32_t first = ord % n_fill;
-          int32_t n_new = 0;
-          std::vector<pf_chunk> next;
-          int32_t prc = pf_plan_bubbles(W, nW, F, nF, fc->replan_ppm, fc->replan_switch_ns, first, nullptr, 0,
-                                        &n_new, nullptr);
-          if (prc == PF_ERR_CAPACITY || prc == PF_OK) {
-            next.resize((size_t)n_new);
-            prc = pf_plan_bubbles(W, nW, F, nF, fc->replan_ppm, fc->replan_switch_ns, first, next.data(), n_new,
-                                  &n_new, nullptr);
-          }
-          if (prc != PF_OK || n_new <= 0) {
-            rc = prc != PF_OK ? prc : pf::fail(PF_ERR_STATE, "pf_timeline_run: empty plan");
-          } else {
-            fc->active_plan.swap(next);
-            plan = fc->active_plan.data();
-            n_plan = n_new;
-          }
+        if (!fc->replan || rc != PF_OK) break;
+        // The job is complete.  The next one starts in what is left of this window: its duration less the
+        // share already planned (which charges the new job its own switch time).
+        int32_t ord = 0;
+        for (int32_t k = 0; k <= in.index; ++k) ord += W[k].fillable ? 1 : 0;
+        int64_t left = 0;
+        if (fc->replan_ppm > 0) {
+          const __int128 spent = ((__int128)planned_ns * 1000000 + fc->replan_ppm - 1) / fc->replan_ppm;
+          left = spent < w.dur_ns ? w.dur_ns - (int64_t)spent : 0;
+        }
+        std::vector<pf_chunk> next;
+        int32_t n_new = 0;
+        int32_t prc = pf_plan_bubbles_from(W, nW, F, nF, fc->replan_ppm, fc->replan_switch_ns, ord - 1, left, nullptr, 0,
+                                           &n_new, nullptr);
+        if (prc == PF_ERR_CAPACITY || prc == PF_OK) {
+          next.resize((size_t)n_new);
+          prc = pf_plan_bubbles_from(W, nW, F, nF, fc->replan_ppm, fc->replan_switch_ns, ord - 1, left, next.data(),
+                                     n_new, &n_new, nullptr);
+        }
+        if (prc == PF_OK && n_new <= 0) prc = pf::fail(PF_ERR_STATE, "pf_timeline_run: empty plan");
+        if (prc != PF_OK) {
+          rc = prc;
+        } else {
+          fc->active_plan.swap(next);
+          plan = fc->active_plan.data();
+          n_plan = n_new;
+          again = true;   // its first chunk belongs to this window
         }
       }
     }

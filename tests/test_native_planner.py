@@ -88,6 +88,37 @@ def test_plan_bit_exact_on_random_instances():
     assert n_ok > 200 and n_inf > 20
 
 
+def test_plan_with_a_shortened_first_bubble_bit_exact():
+    rng = np.random.default_rng(77)
+    n_ok = n_short = 0
+    for trial in range(400):
+        bubbles, F = _random_cycle(rng, trial)
+        fill_idx = [i for i, b in enumerate(bubbles) if b["fillable"]]
+        ppm = int(rng.choice([1_000_000, 900_000, 500_001]))
+        sw = int(rng.choice([0, 3, 50]))
+        first = int(rng.integers(0, len(fill_idx)))
+        full = bubbles[fill_idx[first]]["dur"]
+        left = int(rng.integers(0, full + 1))
+        try:
+            want, k = op.partition_fill_job(bubbles, F, ppm, first, sw, first_dur=left)
+        except op.Infeasible as e:
+            with pytest.raises(pf.PipeFillError) as g:
+                pf.pf_plan_bubbles(bubbles, F, ppm, sw, first, first_dur_ns=left)
+            assert g.value.code == pf.PF_ERR_INFEASIBLE and g.value.node == e.node
+            continue
+        got, gk = pf.pf_plan_bubbles(bubbles, F, ppm, sw, first, first_dur_ns=left)
+        assert gk == k and got == want
+        n_ok += 1
+        base, _ = op.partition_fill_job(bubbles, F, ppm, first, sw)
+        n_short += got != base
+    assert n_ok > 150 and n_short > 50
+    # the whole bubble left = the ordinary plan
+    bubbles = [dict(dur=100, free=9), dict(dur=60, free=9)]
+    F = [(7, 1), (9, 2), (5, 1)]
+    assert pf.pf_plan_bubbles(bubbles, F, first_dur_ns=100) == pf.pf_plan_bubbles(bubbles, F)
+    assert pf.pf_plan_bubbles(bubbles, F, first_dur_ns=40) != pf.pf_plan_bubbles(bubbles, F)
+
+
 def test_plan_on_the_benchmark_schedule():
     # cfg2-shaped instance with synthetic node times: all 8 stages
     p, m, tf, tb, free = synth.SCHEDULES["cfg2"]

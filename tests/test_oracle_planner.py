@@ -293,3 +293,49 @@ def test_chain_nodes_shape():
                            g=1, streamed=False, n_slots=0, training=False)
     assert len(nodes) == 14 and [n[0] for n in nodes] == [0] + [1] * 12 + [2]
     assert op.layer_param_count(768, 3072) == 7087872       # one BERT-base-shaped layer
+
+
+def test_job_arriving_in_the_middle_of_a_bubble():
+    """Sec. 4.3 (the next job is taken when one completes): the first visit of the first bubble is shorter,
+    everything else is Algorithm 1.  Hand example: bubbles 10 and 6, chain of four nodes of 2."""
+    B = [dict(dur=10, free=9, fillable=1), dict(dur=6, free=9, fillable=1)]
+    F = [(2, 1)] * 4
+    # ordinary plan: 16 of bubble time -> 1 copy (8 + 8 !< 16); 10 takes 4 nodes (2,4,6,8 < 10)
+    chunks, k = op.partition_fill_job(B, F)
+    assert k == 1 and [(c["bubble"], c["node_begin"], c["node_end"]) for c in chunks] == [(0, 0, 4)]
+    # 5 left of the first bubble: 2 nodes (2, 4 < 5), then 2 in the second (2, 4 < 6)
+    chunks, k = op.partition_fill_job(B, F, first_dur=5)
+    assert k == 1 and [(c["bubble"], c["cycle"], c["node_begin"], c["node_end"]) for c in chunks] == [(0, 0, 0, 2), (1, 0, 2, 4)]
+    # nothing left: an empty first chunk, the job starts in the next bubble
+    chunks, k = op.partition_fill_job(B, F, first_dur=0)
+    assert [(c["bubble"], c["node_begin"], c["node_end"]) for c in chunks] == [(0, 0, 0), (1, 0, 2), (0, 2, 4)]
+    assert chunks[2]["cycle"] == 1                      # the second visit of bubble 0 has its full length
+    # the fill fraction and the switch time apply to the shortened visit too: floor(5 * 0.9) - 1 = 3 -> one node
+    chunks, _ = op.partition_fill_job(B, F, 900_000, 0, 1, first_dur=5)
+    assert (chunks[0]["node_begin"], chunks[0]["node_end"]) == (0, 1)
+    # invariants on random instances: every node placed once and in order, chunk 0 within the shortened limit,
+    # all others within their bubble; with the whole bubble left the plan is the ordinary one
+    rng = np.random.default_rng(5)
+    checked = 0
+    for _ in range(200):
+        n = int(rng.integers(1, 5))
+        B = [dict(dur=int(rng.integers(20, 200)), free=10, fillable=1) for _ in range(n)]
+        F = [(int(rng.integers(1, 15)), int(rng.integers(1, 10))) for _ in range(int(rng.integers(1, 6)))]
+        first = int(rng.integers(0, n))
+        left = int(rng.integers(0, B[first]["dur"] + 1))
+        try:
+            chunks, k = op.partition_fill_job(B, F, 1_000_000, first, 0, first_dur=left)
+        except op.Infeasible:
+            continue
+        checked += 1
+        assert chunks[0]["bubble"] == first and (chunks[0]["dur"] < left or chunks[0]["node_end"] == chunks[0]["node_begin"])
+        pos = 0
+        for i, c in enumerate(chunks):
+            assert c["node_begin"] == pos and c["bubble"] == (first + i) % n and c["cycle"] == (first + i) // n
+            assert c["dur"] == sum(F[j % len(F)][0] for j in range(c["node_begin"], c["node_end"]))
+            if i:
+                assert c["dur"] < B[c["bubble"]]["dur"] or c["node_end"] == c["node_begin"]
+            pos = c["node_end"]
+        assert pos == k * len(F)
+        assert op.partition_fill_job(B, F, 1_000_000, first, 0, first_dur=B[first]["dur"]) == op.partition_fill_job(B, F, 1_000_000, first, 0)
+    assert checked > 100
