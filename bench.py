@@ -253,13 +253,14 @@ def make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4), n_slots=3):
 def run_cfg3(args, np, torch, pf, dev, synth):
     shape, models = make_cfg3_models(torch, pf, dev, synth)
     fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
-    windows = [dict(start=20_000_000, dur=40_000_000, free=8 * GIB, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
+    bubble_ns, cap = int(args.bubble_ms * 1e6), int(args.cap_gib * GIB)
+    windows = [dict(start=bubble_ns // 2, dur=bubble_ns, free=cap, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
     for mdl in models:
         mdl.ctx.pf_profile_chain(mdl.chain, 1, 3, fill.cuda_stream)
     cfgs = [dict(F=mdl.chain, samples=mdl.cfg.g * shape.batch) for mdl in models]
     best, rep, cyc, chk = pf.pf_select_config(windows, cfgs, args.fill_ppm, args.switch_ns, 0)
     if best < 0:
-        raise RuntimeError("no configuration of the streamed job fits the 40 ms / 8 GiB bubbles")
+        raise RuntimeError(f"no configuration of the streamed job fits the {args.bubble_ms} ms / {args.cap_gib} GiB bubbles")
     mdl = models[best]
     plan, n_plan, k = pf.pf_plan_bubbles(windows, mdl.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
     cursor = C.c_int32(0)
@@ -296,7 +297,8 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": "cfg3: 24-layer bf16 causal decoder inference fill job d=2048 h=16 ff=8192 seq=1024 "
                                "batch=16, weights streamed per layer from pinned host memory (3 HBM slots), "
-                               "explicit 40 ms bubbles separated by 20 ms, 8 GiB cap",
+                               f"explicit {args.bubble_ms:g} ms bubbles separated by {args.bubble_ms / 2:g} ms, "
+                               f"{args.cap_gib:g} GiB cap",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
                    "microbatches_per_layer_visit": g,
                    "candidates": {f"g={m_.cfg.g}": {"replicas": rep[i], "cycles": cyc[i],
@@ -469,6 +471,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=4)
     ap.add_argument("--verbose", action="store_true", help="per-step statistics on stderr (cfg2)")
+    ap.add_argument("--bubble-ms", type=float, default=40.0, help="cfg3: duration of the explicit bubbles")
+    ap.add_argument("--cap-gib", type=float, default=8.0, help="cfg3: free memory inside the bubbles")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device-to-device copy 10 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")

@@ -1,0 +1,54 @@
+"""One-GPU sweeps over the Executor's knobs, the analogues of the paper's sensitivity studies: main-job
+slowdown and fill throughput against the fraction of each bubble the Executor tries to fill (Sec. 6.1,
+Fig. 5), fill throughput against the bubble size and against the free memory (Sec. 6.4, Fig. 10).
+
+    python -m paper_2410_07192_amd.sweeps [--which fill,bubble,memory] > sweeps.jsonl
+
+Every point is one run of bench.py (a child process, so each point starts from a fresh context); one JSON
+object per point on stdout: the sweep's name, the knob's value and the fields of bench.py's line that the
+study plots."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+KEEP = ("value", "unit", "pct_bubble_filled", "overrun_pct_of_offered", "main_slowdown_pct", "fill_tflops_in_bubbles",
+        "replicas_done", "chunks_run")
+
+
+def run_point(name, knob, value, extra):
+    cmd = [sys.executable, os.path.join(ROOT, "bench.py"), "--no-cpu-baseline", *extra]
+    out = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    rec = {"sweep": name, knob: value}
+    if out.returncode != 0:
+        rec["error"] = out.stderr.strip().splitlines()[-1] if out.stderr.strip() else f"exit {out.returncode}"
+    else:
+        line = json.loads(out.stdout.strip().splitlines()[-1])
+        rec.update({k: line.get(k) for k in KEEP})
+        rec["microbatches_per_layer_visit"] = line.get("config", {}).get("microbatches_per_layer_visit")
+    print(json.dumps(rec), flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--which", default="fill,bubble,memory")
+    args = ap.parse_args()
+    which = set(args.which.split(","))
+    if "fill" in which:      # real main-stage kernels (cfg5) with the streamed fill job inside its bubbles
+        for ppm in (300_000, 500_000, 680_000, 800_000, 900_000, 980_000):
+            run_point("fill_fraction", "fill_ppm", ppm, ["--workload", "cfg5", "--fill-ppm", str(ppm), "--steps", "2",
+                                                          "--warmup", "1"])
+    if "bubble" in which:    # streamed fill job (cfg3) in explicit bubbles of growing size
+        for ms in (5, 10, 20, 40, 80, 160):
+            run_point("bubble_size", "bubble_ms", ms, ["--workload", "cfg3", "--bubble-ms", str(ms), "--steps", "20"])
+    if "memory" in which:    # the same job with less and less free memory
+        for gib in (1, 2, 3, 4, 6, 8):
+            run_point("free_memory", "cap_gib", gib, ["--workload", "cfg3", "--cap-gib", str(gib), "--steps", "20"])
+
+
+if __name__ == "__main__":
+    main()
