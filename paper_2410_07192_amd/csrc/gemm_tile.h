@@ -293,6 +293,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
         else return (slot + row) % SLOTS;
       };
       uint2* st8 = (uint2*)smem;
+      // the residual tile is requested first, in the layout of the final stores, so that it arrives while the
+      // accumulators go through bias / GELU / LDS
+      constexpr int EARLY = PER < 8 ? PER : 8;   // more would not fit beside the accumulators
+      uint4 rres[(EPI & E_RESID) ? PER : 1];
+      if constexpr (EPI & E_RESID) {
+#pragma unroll
+        for (int i = 0; i < EARLY; ++i) {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
+        }
+      }
       static_for<0, TN>([&](auto a) {
         float bias4[4][4] = {};
         if constexpr (EPI & E_BIAS) {
@@ -321,15 +332,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
           });
         });
       });
+      if constexpr (EPI & E_RESID) {   // the accumulators are dead now: the rest of the residual tile
+#pragma unroll
+        for (int i = EARLY; i < PER; ++i) {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
+        }
+      }
       __builtin_amdgcn_s_waitcnt(0xc07f);
       __builtin_amdgcn_s_barrier();
-#pragma unroll 4
+#pragma unroll
       for (int i = 0; i < PER; ++i) {
         const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
         uint4 v = smem[row * SLOTS + swz(slot, row)];
         const int64_t off = (m0 + row) * N + n0 + slot * 8;
         if constexpr (EPI & E_RESID) {
-          const uint4 r = *(const uint4*)((const bf16_t*)ep.resid + off);
+          const uint4 r = rres[i];
           const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, rw[4] = {r.x, r.y, r.z, r.w};
           uint32_t ow[4];
 #pragma unroll
