@@ -291,3 +291,109 @@ def chain_nodes(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, 
         nodes.append((OP_LAYER_BWD, l, 0, g, total))
     nodes.append((OP_OPT, -1, 0, g, total))
     return nodes
+
+
+# ---------------------------------------------------------------------------------------------
+# Bubble characterisation by the doubling probe (Sec. 4.2)
+# ---------------------------------------------------------------------------------------------
+def stage_program_1f1b(p, m, s):
+    """Instruction list of stage s for one iteration, 1F1B order: ("F", j), ("B", j) and
+    ("BUBBLE", k) where the stage idles in the steady state (k numbers the idle windows of
+    windows_1f1b in time order; the fill-drain bubble, if any, is the last entry)."""
+    prog = []
+    nf0 = min(p - s, m)
+    for j in range(nf0):
+        prog.append(("F", j))
+    k = 0
+    # the fwd-bwd window exists when the first gradient arrives after the last warm-up forward ends
+    if p - s - 1 > 0:
+        prog.append(("BUBBLE", k))
+        k += 1
+    fnext = nf0
+    fwd_before = True
+    for j in range(m):
+        if not fwd_before:
+            prog.append(("BUBBLE", k))
+            k += 1
+        prog.append(("B", j))
+        fwd_before = False
+        if fnext < m:
+            prog.append(("F", fnext))
+            fnext += 1
+            fwd_before = True
+    if s > 0:
+        prog.append(("BUBBLE", k))
+        k += 1
+    return prog
+
+
+def pipeline_period_with_waits(p, m, tf, tb, s, waits, iterations=4):
+    """Steady-state iteration period of a p-stage 1F1B pipeline in which stage s, at its
+    bubble instruction k, does not proceed before waits[k] has passed since its previous
+    instruction ended (Sec. 4.2: "wait a certain amount of time before proceeding to
+    execute the next instruction").  Plain dependency simulation: forward j of stage q needs
+    forward j of stage q-1, backward j of stage q needs backward j of stage q+1, each stage
+    runs its instructions in order, iterations follow each other without a gap.  Returns the
+    time between the ends of the last two simulated iterations."""
+    progs = [stage_program_1f1b(p, m, q) for q in range(p)]
+    done_f = {}
+    done_b = {}
+    pc = [0] * p
+    it = [0] * p
+    free_at = [0] * p          # when the stage finished its previous instruction
+    not_before = [0] * p       # earliest start imposed by a wait
+    end_of_iter = [0] * iterations
+    remaining = p * iterations
+    while remaining:
+        progressed = False
+        for q in range(p):
+            while it[q] < iterations:
+                kind, idx = progs[q][pc[q]]
+                if kind == "BUBBLE":
+                    if q == s:
+                        not_before[q] = free_at[q] + waits[idx]
+                else:
+                    if kind == "F":
+                        dep = done_f.get((q - 1, idx, it[q])) if q > 0 else 0
+                    else:
+                        dep = done_b.get((q + 1, idx, it[q])) if q < p - 1 else 0
+                    if dep is None:
+                        break
+                    start = max(free_at[q], not_before[q], dep)
+                    end = start + (tf if kind == "F" else tb)
+                    (done_f if kind == "F" else done_b)[(q, idx, it[q])] = end
+                    free_at[q] = end
+                    end_of_iter[it[q]] = max(end_of_iter[it[q]], end)
+                progressed = True
+                pc[q] += 1
+                if pc[q] == len(progs[q]):
+                    pc[q] = 0
+                    it[q] += 1
+                    remaining -= 1
+        assert progressed, "dependency deadlock"
+    return end_of_iter[-1] - end_of_iter[-2]
+
+
+def probe_bubble_durations(p, m, s, tf, tb, first_wait, tol_ppm=0):
+    """The doubling probe of Sec. 4.2.  The bubble instructions of stage s are characterised
+    one after the other, in program order, the waits already found staying in place: wait
+    first_wait at the instruction; while the iteration period stays within tol_ppm of the
+    undisturbed one, double the wait; the estimate is the last wait that left the period
+    unaffected (0 if even first_wait slowed the pipeline).  A wait may exceed the idle window
+    it sits in when later windows of the stage absorb the delay (the pipeline only slows once
+    the slack is used up); holding the earlier estimates makes the set jointly harmless.
+    Returns one estimate per idle window of windows_1f1b(p, m, s, ...), in the same order."""
+    n = sum(1 for ins in stage_program_1f1b(p, m, s) if ins[0] == "BUBBLE")
+    base = pipeline_period_with_waits(p, m, tf, tb, s, [0] * n)
+    limit = base + base * tol_ppm // 1_000_000
+    waits = [0] * n
+    for k in range(n):
+        w = first_wait
+        while True:
+            trial = list(waits)
+            trial[k] = w
+            if pipeline_period_with_waits(p, m, tf, tb, s, trial) > limit:
+                break
+            waits[k] = w
+            w *= 2
+    return waits

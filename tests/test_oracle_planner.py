@@ -339,3 +339,45 @@ def test_job_arriving_in_the_middle_of_a_bubble():
         assert pos == k * len(F)
         assert op.partition_fill_job(B, F, 1_000_000, first, 0, first_dur=B[first]["dur"]) == op.partition_fill_job(B, F, 1_000_000, first, 0)
     assert checked > 100
+
+
+def test_doubling_probe_of_bubble_durations():
+    """Sec. 4.2 bubble characterisation.  Pins: the undisturbed simulated period is the closed-form iteration
+    time and the stage program has one bubble instruction per idle window; waits equal to the true windows
+    leave the period alone and one unit more at the last window slows it by exactly that unit; the probed
+    waits are jointly harmless, sum to at most the stage's idle time, and none can be doubled; the last stage
+    (one fill-drain bubble, nothing behind it to absorb a delay) gets the largest first_wait * 2^i <= duration."""
+    checked = 0
+    for p, m, (tf, tb) in itertools.product(range(1, 7), range(1, 8), ((2, 4), (15, 30), (7, 5))):
+        T = op.iteration_time(p, m, tf, tb)
+        for s in range(p):
+            W = op.windows_1f1b(p, m, s, tf, tb, 0)
+            n = sum(1 for ins in op.stage_program_1f1b(p, m, s) if ins[0] == "BUBBLE")
+            assert n == len(W)
+            assert op.pipeline_period_with_waits(p, m, tf, tb, s, [0] * n) == T
+            true = [w["dur"] for w in W]
+            assert op.pipeline_period_with_waits(p, m, tf, tb, s, true) == T
+            if n:
+                more = list(true)
+                more[-1] += 3
+                assert op.pipeline_period_with_waits(p, m, tf, tb, s, more) == T + 3
+            est = op.probe_bubble_durations(p, m, s, tf, tb, 1)
+            assert len(est) == n and sum(est) <= (p - 1) * (tf + tb)
+            assert op.pipeline_period_with_waits(p, m, tf, tb, s, est) == T
+            for k in range(n):
+                t = list(est)
+                t[k] = max(1, 2 * est[k])
+                assert op.pipeline_period_with_waits(p, m, tf, tb, s, t) > T
+            if s == p - 1 and p > 1:
+                assert est[-1] <= true[-1] < 2 * est[-1]
+            checked += 1
+    assert checked > 400
+    # hand example: p=2, m=2, t_f=15, t_b=30, stage 0: windows 30 (fwd-bwd) and 15 (gap).  A wait of 32 before the
+    # first backward is absorbed by the gap behind it (the second backward cannot start before 105 anyway), 64 is
+    # not; the gap then has 13 left: 8 fits, 16 does not.
+    assert [w["dur"] for w in op.windows_1f1b(2, 2, 0, 15, 30, 0)] == [30, 15]
+    assert op.probe_bubble_durations(2, 2, 0, 15, 30, 1) == [32, 8]
+    assert op.probe_bubble_durations(2, 2, 0, 15, 30, 10) == [40, 0]      # 40 uses 10 of the gap: 10 no longer fits 5
+    assert op.probe_bubble_durations(2, 2, 1, 15, 30, 1) == [32]          # fill-drain of 45: 32 <= 45 < 64
+    # a tolerance lets the probe accept waits that slow the pipeline by less than it
+    assert op.probe_bubble_durations(2, 2, 1, 15, 30, 1, tol_ppm=200_000) == [64]   # 135 * 1.2 = 162 >= 135 + 19
