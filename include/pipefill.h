@@ -158,6 +158,23 @@ int32_t pf_plan_bubbles(const pf_bubble* B, int32_t nB, const pf_node* F, int32_
                         int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
                         pf_chunk* out, int32_t cap, int32_t* n_out, int32_t* replicas);
 
+/* Bubble characterisation by the doubling probe (Sec. 4.2, "Bubble characterization"): how long
+ * can stage `stage` of a p-stage, m-microbatch 1F1B pipeline (forward tf_ns, backward tb_ns per
+ * microbatch and stage, no communication time) hold back at each of its bubble instructions before
+ * the main job slows down.  The pipeline is simulated from its dependencies (forward j of a stage
+ * needs forward j of the stage before, backward j the backward j of the stage after, a stage runs
+ * its instructions in order).  The bubble instructions are taken one after the other in program
+ * order, the waits already found staying in place: the wait starts at first_wait_ns and doubles
+ * while the steady-state iteration period stays <= the undisturbed period * (1 + tol_ppm / 1e6);
+ * the estimate is the last wait that passed (0 if first_wait_ns already slows the pipeline).  An
+ * estimate can exceed the idle window it belongs to when a later window of the stage absorbs the
+ * delay; the estimates together never slow the pipeline and sum to at most the stage's idle time.
+ * est_ns (host, out): one value per idle window, same order and count as pf_schedule_1f1b.
+ * PF_ERR_CAPACITY (count in *n_out) if cap is too small; PF_ERR_ARG on non-positive times. */
+int32_t pf_probe_bubbles(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int64_t tb_ns,
+                         int64_t first_wait_ns, int64_t tol_ppm, int64_t* est_ns, int32_t cap,
+                         int32_t* n_out);
+
 /* Algorithm 1 for a job that arrives when its first bubble is partly gone (Sec. 4.3: the Executor
  * takes the next job as soon as one completes, which is in the middle of a bubble): exactly
  * pf_plan_bubbles, except that the FIRST visit of bubble `first_bubble` has the duration

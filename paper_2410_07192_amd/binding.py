@@ -21,7 +21,7 @@ PF_DTYPE_F32, PF_DTYPE_BF16 = 0, 1
 PF_INSTR_FWD, PF_INSTR_BWD, PF_INSTR_BUBBLE = 0, 1, 2
 
 EXPORTS = [
-    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from",
+    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from", "pf_probe_bubbles",
     "pf_select_config", "pf_build_chain", "pf_layer_blob_layout", "pf_ctx_arena_bytes", "pf_ctx_create",
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
@@ -95,6 +95,7 @@ def _load():
     lib.pf_schedule_1f1b.argtypes = [I32, I32, I32, I64, I64, I64, I32, I64, P(pf_bubble), I32, P(I32)]
     lib.pf_schedule_gpipe.argtypes = [I32, I32, I32, I64, I64, I64, P(pf_bubble), I32, P(I32)]
     lib.pf_plan_bubbles.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, P(pf_chunk), I32, P(I32), P(I32)]
+    lib.pf_probe_bubbles.argtypes = [I32, I32, I32, I64, I64, I64, I64, P(I64), I32, P(I32)]
     lib.pf_plan_bubbles_from.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, I64, P(pf_chunk), I32, P(I32),
                                          P(I32)]
     lib.pf_select_config.argtypes = [P(pf_bubble), I32, P(P(pf_node)), P(I32), P(I64), I32, I64, I64, I32,
@@ -175,6 +176,17 @@ def pf_schedule_gpipe(p, m, stage, tf_ns, tb_ns, free_bytes, cap=2):
     n = C.c_int32(0)
     _check(lib.pf_schedule_gpipe(p, m, stage, tf_ns, tb_ns, free_bytes, out, cap, C.byref(n)))
     return [_bubble_dict(out[i]) for i in range(n.value)]
+
+
+def pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm=0):
+    """Estimated harmless wait per idle window of the stage (doubling probe)."""
+    n = C.c_int32(0)
+    rc = lib.pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm, None, 0, C.byref(n))
+    if rc not in (PF_OK, PF_ERR_CAPACITY):
+        raise PipeFillError(rc, lib.pf_last_error().decode())
+    out = (C.c_int64 * max(1, n.value))()
+    _check(lib.pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm, out, n.value, C.byref(n)))
+    return [int(out[i]) for i in range(n.value)]
 
 
 def pf_plan_bubbles(bubbles, F, fill_ppm=1_000_000, switch_ns=0, first_bubble=0, cap=None, raw=False,

@@ -3,6 +3,7 @@
 // ppm, 128-bit cross products), so results are reproducible bit for bit.
 #include "pf_internal.h"
 
+#include <algorithm>
 #include <vector>
 
 namespace {
@@ -93,6 +94,71 @@ PlanResult plan_impl(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t n
     ++slot;
   }
   return r;
+}
+
+// ---- bubble characterisation (Sec. 4.2) --------------------------------------------------------------
+// One iteration of a stage in 1F1B order.  op: 0 forward, 1 backward, 2 bubble; idx: microbatch or window.
+struct StageOp { int32_t op, idx; };
+
+std::vector<StageOp> stage_ops(int32_t p, int32_t m, int32_t s) {
+  std::vector<StageOp> v;
+  const int32_t warm = std::min(p - s, m);
+  for (int32_t j = 0; j < warm; ++j) v.push_back({0, j});
+  int32_t k = 0;
+  if (p - s - 1 > 0) v.push_back({2, k++});
+  int32_t next_f = warm;
+  bool after_fwd = true;
+  for (int32_t j = 0; j < m; ++j) {
+    if (!after_fwd) v.push_back({2, k++});
+    v.push_back({1, j});
+    after_fwd = false;
+    if (next_f < m) {
+      v.push_back({0, next_f++});
+      after_fwd = true;
+    }
+  }
+  if (s > 0) v.push_back({2, k++});
+  return v;
+}
+
+// Steady-state period of the pipeline when stage s holds back, at its bubble k, for waits[k] after its
+// previous instruction.  Finish times live in flat arrays [iteration][stage][microbatch]; stages are swept
+// round-robin, each running as far as its dependencies allow (the schedule is a DAG, so every sweep advances).
+int64_t period_with_waits(int32_t p, int32_t m, int64_t tf, int64_t tb, int32_t s, const std::vector<int64_t>& waits,
+                          const std::vector<std::vector<StageOp>>& ops) {
+  constexpr int32_t ITER = 4;
+  const size_t per_it = (size_t)p * m;
+  std::vector<int64_t> fin_f(ITER * per_it, -1), fin_b(ITER * per_it, -1);
+  std::vector<int32_t> pc(p, 0), it(p, 0);
+  std::vector<int64_t> free_at(p, 0), hold(p, 0);
+  int64_t end_it[ITER] = {0, 0, 0, 0};
+  int32_t live = p;
+  while (live > 0) {
+    for (int32_t q = 0; q < p; ++q) {
+      while (it[q] < ITER) {
+        const StageOp o = ops[q][pc[q]];
+        if (o.op == 2) {
+          if (q == s) hold[q] = free_at[q] + waits[o.idx];
+        } else {
+          const size_t at = (size_t)it[q] * per_it + (size_t)q * m + o.idx;
+          int64_t dep = 0;
+          if (o.op == 0 && q > 0) dep = fin_f[at - m];
+          if (o.op == 1 && q < p - 1) dep = fin_b[at + m];
+          if (dep < 0) break;   // producer not simulated yet
+          const int64_t start = std::max(std::max(free_at[q], hold[q]), dep);
+          const int64_t end = start + (o.op == 0 ? tf : tb);
+          (o.op == 0 ? fin_f : fin_b)[at] = end;
+          free_at[q] = end;
+          if (end > end_it[it[q]]) end_it[it[q]] = end;
+        }
+        if (++pc[q] == (int32_t)ops[q].size()) {
+          pc[q] = 0;
+          if (++it[q] == ITER) --live;
+        }
+      }
+    }
+  }
+  return end_it[ITER - 1] - end_it[ITER - 2];
 }
 
 bool bad_bubbles(const pf_bubble* B, int32_t nB) {
@@ -195,6 +261,38 @@ int32_t pf_plan_bubbles_from(const pf_bubble* B, int32_t nB, const pf_node* F, i
   *n_out = (int32_t)r.n_chunks;
   if (r.n_chunks > cap)
     return pf::fail(PF_ERR_CAPACITY, "pf_plan_bubbles: %lld chunks, capacity %d", (long long)r.n_chunks, cap);
+  return PF_OK;
+}
+
+int32_t pf_probe_bubbles(int32_t p, int32_t m, int32_t s, int64_t tf, int64_t tb, int64_t first_wait,
+                         int64_t tol_ppm, int64_t* est, int32_t cap, int32_t* n_out) {
+  if (p < 1 || m < 1 || s < 0 || s >= p || tf <= 0 || tb <= 0 || first_wait < 1 || tol_ppm < 0 || cap < 0 || !n_out ||
+      (cap > 0 && !est) || (int64_t)p * m > (int64_t)1 << 22)
+    return pf::fail(PF_ERR_ARG, "pf_probe_bubbles: bad argument");
+  std::vector<std::vector<StageOp>> ops;
+  for (int32_t q = 0; q < p; ++q) ops.push_back(stage_ops(p, m, q));
+  int32_t n = 0;
+  for (const StageOp& o : ops[s]) n += (o.op == 2);
+  *n_out = n;
+  if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_probe_bubbles: %d windows, capacity %d", n, cap);
+  std::vector<int64_t> waits(n, 0);
+  const int64_t base = period_with_waits(p, m, tf, tb, s, waits, ops);
+  const int64_t limit = base + (int64_t)((__int128)base * tol_ppm / 1000000);
+  // the pipeline slows down at the latest once one wait exceeds a whole iteration plus the tolerance
+  for (int32_t k = 0; k < n; ++k) {
+    int64_t w = first_wait;
+    for (;;) {
+      const int64_t keep = waits[k];
+      waits[k] = w;
+      const bool slowed = period_with_waits(p, m, tf, tb, s, waits, ops) > limit;
+      if (slowed || w > ((int64_t)1 << 60)) {
+        waits[k] = keep;
+        break;
+      }
+      w *= 2;
+    }
+  }
+  for (int32_t k = 0; k < n; ++k) est[k] = waits[k];
   return PF_OK;
 }
 

@@ -1,5 +1,6 @@
 """Native planner (C ABI) against the CPU checker, bit for bit; host-only error paths; exports."""
 import ctypes as C
+import itertools
 import os
 import re
 
@@ -222,3 +223,30 @@ def test_context_calls_fail_loudly_without_a_device_or_with_bad_arguments():
     assert pf.lib.pf_ctx_arena_bytes(C.byref(bad), C.byref(cfg)) == pf.PF_ERR_ARG
     assert pf.lib.pf_ctx_sync(None) == pf.PF_ERR_ARG
     assert pf.lib.pf_fill_chunk_fwd(None, None, None, 0, None, None, 0, None) == pf.PF_ERR_ARG
+
+
+def test_probe_bubbles_bit_exact_and_errors():
+    n = 0
+    for p, m, (tf, tb), first, tol in itertools.product((1, 2, 3, 5, 8), (1, 2, 4, 7, 16), ((2, 4), (15_000_000, 30_000_000), (7, 5)),
+                                                        (1, 3, 1000), (0, 50_000)):
+        for s in sorted({0, p // 2, p - 1}):
+            want = op.probe_bubble_durations(p, m, s, tf, tb, first, tol)
+            assert pf.pf_probe_bubbles(p, m, s, tf, tb, first, tol) == want, (p, m, s, tf, tb, first, tol)
+            n += 1
+    assert n > 500
+    # cfg2's schedule, 1 us first wait: every estimate within a factor two below what the window (plus slack) allows
+    p, m, tf, tb, _ = synth.SCHEDULES["cfg2"]
+    for s in range(p):
+        est = pf.pf_probe_bubbles(p, m, s, tf, tb, 1000)
+        true = [w["dur"] for w in op.windows_1f1b(p, m, s, tf, tb, 0)]
+        assert len(est) == len(true) and sum(est) <= sum(true)
+        assert est[-1] <= true[-1] < 2 * est[-1] or s < p - 1
+    for bad in (dict(p=0), dict(m=0), dict(stage=4), dict(tf_ns=0), dict(tb_ns=-1), dict(first_wait_ns=0), dict(tol_ppm=-1)):
+        kw = dict(p=4, m=8, stage=1, tf_ns=10, tb_ns=20, first_wait_ns=1, tol_ppm=0)
+        kw.update(bad)
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_probe_bubbles(**kw)
+        assert e.value.code == pf.PF_ERR_ARG
+    nn = C.c_int32(0)
+    buf = (C.c_int64 * 1)()
+    assert pf.lib.pf_probe_bubbles(4, 8, 0, 10, 20, 1, 0, buf, 1, C.byref(nn)) == pf.PF_ERR_CAPACITY and nn.value == 4
