@@ -75,6 +75,38 @@ def test_gemm_plain_and_epilogues(dtype, M, N, K):
     assert rel_err(acc.cpu().numpy(), 2 * ref0) < 1e-4
 
 
+# Shapes that make the tile chooser take the 256x192 and the 256x256 tile with ragged last tiles along M and N
+# (8292 = 32 * 256 + 100), with N a multiple of 8 (16-byte row-contiguous stores) and not (8- and 2-byte stores).
+@pytest.mark.parametrize("M,N,K", [(8292, 2368, 128), (8292, 3112, 128), (8292, 2370, 64), (4196, 6150, 64)])
+def test_gemm_large_tiles_with_ragged_edges(M, N, K):
+    pf, dev = _mods()
+    md = _md("bf16")
+    rng = np.random.default_rng(M + N + K)
+    X, W = _rand(rng, (M, K), "bf16"), _rand(rng, (N, K), "bf16", 0.05)
+    bias, R = _rand(rng, (N,), "bf16"), _rand(rng, (M, N), "bf16")
+    dX, dW, dB, dR = (dev.storage_tensor(a, md) for a in (X, W, bias, R))
+    ref0 = X.astype(np.float64) @ W.astype(np.float64).T
+    out = dev.empty_storage((M, N), md)
+    guard = dev.empty_storage((M + 1, N), md)          # one extra row behind C: must stay untouched
+    guard.zero_()
+    pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), guard.data_ptr(), M, N, K, bias=dB.data_ptr())
+    torch.cuda.synchronize()
+    g = dev.read_storage(guard, md)
+    assert rel_err(g[:M], ref0 + bias) < TOL["bf16"] / 2 and not g[M].any()
+    pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), out.data_ptr(), M, N, K, bias=dB.data_ptr(), gelu=1)
+    torch.cuda.synchronize()
+    assert rel_err(dev.read_storage(out, md), ot.gelu(ref0 + bias)) < TOL["bf16"] / 2
+    pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), out.data_ptr(), M, N, K, bias=dB.data_ptr(),
+                  resid=dR.data_ptr())
+    torch.cuda.synchronize()
+    assert rel_err(dev.read_storage(out, md), ref0 + bias + R) < TOL["bf16"] / 2
+    acc = torch.zeros((M, N), dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), acc.data_ptr(), M, N, K, out_f32=1, accumulate=1)
+    torch.cuda.synchronize()
+    assert rel_err(acc.cpu().numpy(), 2 * ref0) < 1e-4
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("rows,d", [(5, 8), (1000, 768), (37, 2048), (9, 8192), (130, 1000)])
 def test_layernorm(dtype, rows, d):
