@@ -42,7 +42,46 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, fl
   const int64_t r1 = (r0 + rows_per_block < rows) ? r0 + rows_per_block : rows;
   float s = 0.f;
   for (int64_t r = r0; r < r1; ++r) s += to_f32(x[r * N + n]);
-  atomicAdd(acc + n, s);
+  unsafeAtomicAdd(acc + n, s);
+}
+
+// bf16, N a multiple of 8, 16-byte aligned rows: a block covers 1024 columns (128 threads x 8) with two row
+// lanes, 16-byte loads, four rows in flight per thread; the two lanes meet in LDS before the atomics.
+__global__ __launch_bounds__(256) void colsum_bf16_vec_kernel(const bf16_t* __restrict__ x, float* __restrict__ acc,
+                                                              int64_t rows, int64_t N, int32_t rows_per_block) {
+  __shared__ float part[128][8];
+  const int cg = threadIdx.x & 127, rl = threadIdx.x >> 7;
+  const int64_t c0 = (int64_t)blockIdx.x * 1024 + cg * 8;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_block;
+  const int64_t r1 = (r0 + rows_per_block < rows) ? r0 + rows_per_block : rows;
+  float s[8] = {};
+  if (c0 < N) {
+    int64_t r = r0 + rl;
+    for (; r + 6 < r1; r += 8) {
+      float v[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) load8(x + (r + 2 * u) * N + c0, v[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s[j] += v[u][j];
+    }
+    for (; r < r1; r += 2) {
+      float v[8];
+      load8(x + r * N + c0, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s[j] += v[j];
+    }
+  }
+  if (rl == 1) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) part[cg][j] = s[j];
+  }
+  __syncthreads();
+  if (rl == 0 && c0 < N) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) unsafeAtomicAdd(acc + c0 + j, s[j] + part[cg][j]);
+  }
 }
 
 // ---- LayerNorm backward -----------------------------------------------------------------------------
@@ -304,7 +343,7 @@ __global__ __launch_bounds__(256) void ce_loss_kernel(T* __restrict__ logits, co
   se = red[0] + red[1] + red[2] + red[3];
   const int32_t tgt = ids[t + 1];
   const float inv = 1.f / se;
-  if (tid == 0 && tgt >= 0 && tgt < V) atomicAdd(loss_sum, (mx + __logf(se)) - to_f32(row[tgt]));
+  if (tid == 0 && tgt >= 0 && tgt < V) unsafeAtomicAdd(loss_sum, (mx + __logf(se)) - to_f32(row[tgt]));
   __syncthreads();   // the target logit is read before anyone overwrites the row
   for (int64_t c = tid; c < pitch; c += 256) {
     float gval = 0.f;
@@ -328,8 +367,8 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const T* __restrict__ dx
     load8(dx + t * d + c, v);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      if (ok) atomicAdd(dtok + (int64_t)id * d + c + j, v[j]);
-      atomicAdd(dpos + (t % S) * (int64_t)d + c + j, v[j]);
+      if (ok) unsafeAtomicAdd(dtok + (int64_t)id * d + c + j, v[j]);
+      unsafeAtomicAdd(dpos + (t % S) * (int64_t)d + c + j, v[j]);
     }
   }
 }
@@ -403,6 +442,13 @@ hipError_t transpose2d(int32_t dtype, const void* in, void* out, int64_t R, int6
 
 hipError_t colsum_add(int32_t dtype, const void* x, float* acc, int64_t rows, int64_t N, hipStream_t st) {
   if (rows <= 0 || N <= 0) return hipErrorInvalidValue;
+  if (dtype == PF_DTYPE_BF16_ && N % 8 == 0 && ((uintptr_t)x & 15) == 0) {
+    const int32_t rpb = 128;
+    const dim3 grid((unsigned)((N + 1023) / 1024), (unsigned)((rows + rpb - 1) / rpb));
+    if (grid.y > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(colsum_bf16_vec_kernel, grid, dim3(256), 0, st, (const bf16_t*)x, acc, rows, N, rpb);
+    return hipGetLastError();
+  }
   const int32_t rpb = 128;
   const dim3 grid((unsigned)((N + 255) / 256), (unsigned)((rows + rpb - 1) / rpb));
   if (grid.y > 65535) return hipErrorInvalidValue;

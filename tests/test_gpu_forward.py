@@ -107,6 +107,23 @@ def test_gemm_large_tiles_with_ragged_edges(M, N, K):
     assert rel_err(acc.cpu().numpy(), 2 * ref0) < 1e-4
 
 
+# Weight-gradient shapes: small result, K = all tokens; C holds an earlier gradient that must be kept.
+@pytest.mark.parametrize("M,N,K", [(1024, 1024, 8192), (3072, 1024, 8192), (1000, 520, 4096), (256, 256, 2048)])
+def test_gemm_accumulate_long_k(M, N, K):
+    pf, dev = _mods()
+    md = _md("bf16")
+    rng = np.random.default_rng(M + N + K)
+    X, W = _rand(rng, (M, K), "bf16"), _rand(rng, (N, K), "bf16", 0.05)
+    dX, dW = dev.storage_tensor(X, md), dev.storage_tensor(W, md)
+    ref0 = X.astype(np.float64) @ W.astype(np.float64).T
+    before = rng.standard_normal((M, N)).astype(np.float32)
+    acc = torch.from_numpy(before).cuda()
+    for _ in range(2):
+        pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), acc.data_ptr(), M, N, K, out_f32=1, accumulate=1)
+    torch.cuda.synchronize()
+    assert rel_err(acc.cpu().numpy(), before + 2 * ref0) < 1e-4
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("rows,d", [(5, 8), (1000, 768), (37, 2048), (9, 8192), (130, 1000)])
 def test_layernorm(dtype, rows, d):
