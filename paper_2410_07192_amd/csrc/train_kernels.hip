@@ -352,6 +352,64 @@ __global__ __launch_bounds__(256) void ce_loss_kernel(T* __restrict__ logits, co
   }
 }
 
+// bf16 rows with a pitch that is a multiple of 8: 16-byte accesses, running (max, sum) in one pass over the row,
+// then one pass that rewrites it (two reads and one write of the logits instead of three reads and one write).
+__global__ __launch_bounds__(256) void ce_loss_bf16_vec_kernel(bf16_t* __restrict__ logits, const int32_t* __restrict__ ids,
+                                                               float* __restrict__ loss_sum, int64_t pitch, int32_t V,
+                                                               int32_t S, float inv_n) {
+  __shared__ float red_m[4], red_s[4];
+  const int64_t t = blockIdx.x;
+  bf16_t* row = logits + t * pitch;
+  const int tid = threadIdx.x;
+  const int chunks = (int)(pitch / 8);
+  if ((t % S) == S - 1) {   // no target: zero gradient
+    for (int c = tid; c < chunks; c += 256) *(uint4*)(row + c * 8) = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  float mx = -INFINITY, se = 0.f;
+  for (int c = tid; c < chunks; c += 256) {
+    float v[8];
+    load8(row + c * 8, v);
+    float cm = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c * 8 + j < V) cm = fmaxf(cm, v[j]);
+    if (cm > mx) {
+      se *= __expf(mx - cm);   // mx = -inf: se is 0 and stays 0
+      mx = cm;
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (c * 8 + j < V) se += __expf(v[j] - mx);
+  }
+  // combine the lanes: (max, sum) pairs
+  const float wm = wave_max(mx);
+  se = wave_sum(mx == -INFINITY ? 0.f : se * __expf(mx - wm));
+  if ((tid & 63) == 0) {
+    red_m[tid >> 6] = wm;
+    red_s[tid >> 6] = se;
+  }
+  const int32_t tgt = ids[t + 1];
+  const float tgt_logit = (tgt >= 0 && tgt < V) ? to_f32(row[tgt]) : 0.f;   // read before the row is rewritten
+  __syncthreads();
+  const float m = fmaxf(fmaxf(red_m[0], red_m[1]), fmaxf(red_m[2], red_m[3]));
+  float sum = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) sum += red_s[w] * __expf(red_m[w] - m);
+  const float inv = 1.f / sum;
+  if (tid == 0 && tgt >= 0 && tgt < V) unsafeAtomicAdd(loss_sum, (m + __logf(sum)) - tgt_logit);
+  for (int c = tid; c < chunks; c += 256) {
+    float v[8];
+    load8(row + c * 8, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int col = c * 8 + j;
+      v[j] = (col < V) ? (__expf(v[j] - m) * inv - (col == tgt ? 1.f : 0.f)) * inv_n : 0.f;
+    }
+    store8(row + c * 8, v);
+  }
+}
+
 // ---- embedding backward: dtok[ids[t]] += dx[t], dpos[t mod S] += dx[t] --------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const T* __restrict__ dx, const int32_t* __restrict__ ids,
@@ -529,6 +587,10 @@ hipError_t ce_loss_inplace(int32_t dtype, void* logits, const int32_t* ids, floa
                            int64_t pitch, int32_t V, int32_t S, float inv_n, hipStream_t st) {
   if (tokens <= 0 || pitch < V || V <= 0 || S <= 1) return hipErrorInvalidValue;
   const dim3 grid((unsigned)tokens), block(256);
+  if (dtype == PF_DTYPE_BF16_ && pitch % 8 == 0 && ((uintptr_t)logits & 15) == 0) {
+    hipLaunchKernelGGL(ce_loss_bf16_vec_kernel, grid, block, 0, st, (bf16_t*)logits, ids, loss_sum, pitch, V, S, inv_n);
+    return hipGetLastError();
+  }
   PF_BY_DTYPE(dtype,
               hipLaunchKernelGGL(ce_loss_kernel<bf16_t>, grid, block, 0, st, (bf16_t*)logits, ids, loss_sum, pitch, V, S, inv_n),
               hipLaunchKernelGGL(ce_loss_kernel<float>, grid, block, 0, st, (float*)logits, ids, loss_sum, pitch, V, S, inv_n));
