@@ -192,8 +192,8 @@ template <typename OutT>
 hipError_t launch_generic(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
                           hipStream_t stream) {
   static bool attr = false;
-  return launch_tiles<OutT>(gemm_bf16_nt_generic_kernel<2, 2, 2, 2, OutT>, 128, 128, 256, &attr, X, W, C, M, N, K, ep,
-                      stream);
+  return launch_tiles<OutT>(gemm_bf16_nt_generic_kernel<2, 2, 2, 2, OutT>, 128, 128, 256, &attr, X, W, C, M, N, K, ep, 1,
+                            stream);
 }
 
 template <typename OutT>

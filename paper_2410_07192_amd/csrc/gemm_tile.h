@@ -164,6 +164,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   const int wm = wave % WGM, wn = wave / WGM;
   const int lr = lane & 31, lk = lane >> 5;
 
+  // split K (accumulating fp32 epilogue only): workgroup y works on columns [y, y+1) * K / gridDim.y of both operands
+  const int64_t k_len = K / gridDim.y;
+  X += (int64_t)blockIdx.y * k_len;
+  W += (int64_t)blockIdx.y * k_len;
+
   // global source of this lane for each 1 KB group the wave moves per K step
   const bf16_t* src[GPW];
 #pragma unroll
@@ -236,7 +241,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   using I2 = std::integral_constant<int, 2>;
   using I3 = std::integral_constant<int, 3>;
 
-  const int64_t nk = K / 64;
+  const int64_t nk = k_len / 64;
   // prologue: stage 0 completely; of stage 1 the share the block after a barrier issues
   static_for<0, GPW>([&](auto i) { issue1(i, 0, 0); });
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -277,6 +282,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
   // Indices into acc must be compile-time constants or the accumulators leave the register file.
   const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
+  // Split K: the fp32 tile goes through LDS (row-major, 16-byte units XOR-swizzled by row) and is added to C with
+  // hardware fp32 atomics, 64 consecutive columns of a row per wave instruction.  A lane-per-row atomic would touch 32
+  // cache lines per instruction.  Only tiles whose fp32 image fits the two LDS stages split K (the launcher knows).
+  if constexpr (std::is_same<OutT, float>::value && EPI == E_ACC && BM * BN * 4 <= 2 * STAGE * 16) {
+    if (gridDim.y > 1) {
+      float* stf = (float*)smem;
+      constexpr int UNITS = BN / 4, NT = 64 * NW;
+      static_for<0, TN>([&](auto a) {
+        static_for<0, TM>([&](auto b) {
+          const int row = (wm * TM + b) * 32 + lr;
+          static_for<0, 4>([&](auto rg) {
+            const int unit = ((wn * TN + a) * 32 + rg * 8 + lk * 4) / 4;
+            *(float4*)(stf + row * BN + ((unit ^ (row & (UNITS - 1))) * 4)) =
+                make_float4(acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2], acc[a][b][rg * 4 + 3]);
+          });
+        });
+      });
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_s_barrier();
+#pragma unroll 8
+      for (int i = 0; i < BM * BN / NT; ++i) {
+        const int e = i * NT + tid, row = e / BN, col = e % BN;
+        const float v = stf[row * BN + (((col >> 2) ^ (row & (UNITS - 1))) * 4) + (col & 3)];
+        if (m0 + row < M && n0 + col < N) unsafeAtomicAdd((float*)C + (m0 + row) * N + n0 + col, v);
+      }
+      return;
+    }
+  }
   // Staged epilogue (bf16 output, no per-element side inputs other than bias / residual): bias and GELU
   // are applied in registers, the bf16 tile goes through LDS (free after the K loop; 16-byte slots
   // XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the tile, the residual
@@ -398,7 +431,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
 
 template <typename OutT, typename Kern>
 hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, const void* X, const void* W, void* C,
-                        int64_t M, int64_t N, int64_t K, const EpiDev& ep, hipStream_t stream) {
+                        int64_t M, int64_t N, int64_t K, const EpiDev& ep, int32_t splits, hipStream_t stream) {
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   const size_t lds = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
   if (!*attr_set) {   // raise the dynamic-LDS limit once per instantiation
@@ -407,7 +440,7 @@ hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, 
     *attr_set = true;
   }
   const int32_t group_m = 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(threads), lds, stream, (const bf16_t*)X,
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n), (unsigned)splits), dim3(threads), lds, stream, (const bf16_t*)X,
                      (const bf16_t*)W, (OutT*)C, M, N, K, ep,
                      (int32_t)tiles_m, (int32_t)tiles_n, group_m);
   return hipGetLastError();
@@ -415,33 +448,49 @@ hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, 
 
 // Main kernel for one epilogue combination.  Tile shapes: 256x256 (8 waves as 2x4, wave tile 128x64), 256x192
 // (8 waves as 4x2, wave tile 64x96), both one workgroup per CU, and 128x128 (4 waves, two workgroups per CU).
-// A launch takes ceil(tiles / resident workgroups) rounds; the shape with the least estimated time
-// rounds x area in flight per CU / efficiency is taken.  Efficiencies are measured on MI355X relative to the
-// 256x256 tile (0.96 and 0.85); a shape that leaves partial tiles along N pays for their slower epilogue.
-// E.g. N = 768 or 2304 fills whole rounds with 192-wide tiles but wastes a quarter of the last round with
-// 256-wide ones, and a 8192 x 1024 result gives every CU work only with the small tile.
+// A launch takes ceil(workgroups / resident workgroups) rounds of (K steps + a fixed cost of about 4 steps); the
+// shape with the least estimated time rounds x steps x area in flight per CU / efficiency is taken.  Efficiencies
+// are measured on MI355X relative to the 256x256 tile (0.96 and 0.85); a shape that leaves partial tiles along N
+// pays for their slower epilogue.  E.g. N = 768 or 2304 fills whole rounds with 192-wide tiles but wastes a quarter
+// of the last round with 256-wide ones, and a 8192 x 1024 result gives every CU work only with the small tile.
+// Accumulating fp32 launches (weight gradients: small M x N, K = all tokens) may split K over up to 8 workgroups
+// per 128x128 tile while that fills idle CUs and leaves each >= 8 K steps; the slices add into C with fp32 atomics
+// (order-dependent in the last bits, like the other atomic reductions over tokens).
 template <typename OutT, int EPI>
 hipError_t launch_fast(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
                        hipStream_t stream) {
   static bool attr_big = false, attr_wide = false, attr_small = false;
-  auto rounds = [](int64_t tiles, int64_t resident) { return (tiles + resident - 1) / resident; };
-  const int64_t tm256 = (M + 255) / 256, tm128 = (M + 127) / 128;
-  const int64_t t256 = tm256 * ((N + 255) / 256), t192 = tm256 * ((N + 191) / 192), t128 = tm128 * ((N + 127) / 128);
-  // time estimates in units of (output elements per CU) x 100 / efficiency
-  int64_t c256 = rounds(t256, 256) * 256 * 256 * 100;
-  int64_t c192 = rounds(t192, 256) * 256 * 192 * 104;
-  int64_t c128 = rounds(t128, 512) * 2 * 128 * 128 * 118;
-  if (N % 256) c256 += c256 * 3 / 10;
-  if (N % 192) c192 += c192 * 3 / 10;
-  if (N % 128) c128 += c128 * 3 / 10;
-  if (c256 <= c192 && c256 <= c128)
+  struct Shape { int bm, bn, resident, eff100; } const shapes[3] = {{256, 256, 256, 100}, {256, 192, 256, 104},
+                                                                      {128, 128, 512, 118}};
+  int best = 0, best_splits = 1;
+  int64_t best_cost = -1;
+  for (int i = 0; i < 3; ++i) {
+    const Shape& sh = shapes[i];
+    const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((N + sh.bn - 1) / sh.bn);
+    int splits = 1;
+    if constexpr (std::is_same<OutT, float>::value && EPI == E_ACC) {
+      if (i == 2)
+        while (splits < 8 && tiles * splits * 2 <= sh.resident && K % (128 * splits) == 0 && K / (128 * splits) >= 8)
+          splits *= 2;
+    }
+    const int64_t rounds = (tiles * splits + sh.resident - 1) / sh.resident;
+    const int64_t steps = K / (64 * splits) + 4;
+    int64_t cost = rounds * steps * (sh.resident / 256) * sh.bm * sh.bn * sh.eff100;
+    if (N % sh.bn) cost += cost * 3 / 10;
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = i;
+      best_splits = splits;
+    }
+  }
+  if (best == 0)
     return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 4, 4, 2, OutT, EPI>, 256, 256, 512, &attr_big, X, W, C, M, N, K, ep,
-                        stream);
-  if (c192 <= c128)
+                              1, stream);
+  if (best == 1)
     return launch_tiles<OutT>(gemm_bf16_nt_kernel<4, 2, 2, 3, OutT, EPI>, 256, 192, 512, &attr_wide, X, W, C, M, N, K, ep,
-                        stream);
+                              1, stream);
   return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 2, 2, 2, OutT, EPI>, 128, 128, 256, &attr_small, X, W, C, M, N, K, ep,
-                      stream);
+                            best_splits, stream);
 }
 
 }  // namespace gemm
