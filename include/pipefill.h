@@ -158,6 +158,36 @@ int32_t pf_plan_bubbles(const pf_bubble* B, int32_t nB, const pf_node* F, int32_
                         int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
                         pf_chunk* out, int32_t cap, int32_t* n_out, int32_t* replicas);
 
+/* ---- Scheduler (Sec. 4.4) and event-driven simulation (Sec. 5.1) --------------------------------- */
+enum { PF_POLICY_FIFO = 0, PF_POLICY_SJF = 1, PF_POLICY_MAKESPAN = 2 };
+typedef struct pf_job { int64_t arrival_ns; int64_t deadline_ns; /* < 0: none (kept for callers; no policy here reads it) */ } pf_job;
+typedef struct pf_job_run { int64_t start_ns, finish_ns; int32_t device, reserved; } pf_job_run;
+
+/* Processing time of a fill job on a device (Sec. 4.4: computed from the job's profile, the
+ * partitioning algorithm and the device's bubble description): the chain F is planned onto the
+ * cycle `bubbles` by Algorithm 1 from bubble 0; one pass of the plan completes replicas *
+ * samples_per_replica samples in ceil(chunks / fillable bubbles) cycles; the job needs
+ * ceil(total_samples / that) passes; a cycle lasts iter_ns (one iteration of the main job).
+ * *proc_ns (host, out) = passes * cycles * iter_ns.  Planner errors pass through
+ * (PF_ERR_INFEASIBLE: the job does not fit this device). */
+int32_t pf_job_time(const pf_bubble* bubbles, int32_t n_bubbles, const pf_node* F, int32_t nF,
+                    int64_t samples_per_replica, int64_t total_samples, int64_t iter_ns, int64_t fill_ppm,
+                    int64_t switch_ns, int64_t* proc_ns);
+
+/* Event-driven simulation of n_jobs fill jobs on n_dev Executors.  proc_ns (host): [n_jobs][n_dev]
+ * positive processing times.  Events are arrivals and completions; at an event every idle device, in
+ * index order, is given the waiting job with the largest policy score f(j, s, i):
+ *   PF_POLICY_FIFO      earliest arrival;
+ *   PF_POLICY_SJF       1 / min(j.proc_times);
+ *   PF_POLICY_MAKESPAN  1 / max(j.proc_times[i], max(s.rem_times)), rem_times = remaining busy time of
+ *                       every Executor at that moment.
+ * Ties: earlier arrival, then lower job index.  runs (host, out): device, start and finish per job.
+ * makespan_ns / sum_completion_ns (host, out, may be NULL): latest finish; sum over jobs of finish -
+ * arrival.  Jobs are not preempted and run whole on one device. */
+int32_t pf_sched_simulate(int32_t policy, const pf_job* jobs, int32_t n_jobs, int32_t n_dev,
+                          const int64_t* proc_ns, pf_job_run* runs, int64_t* makespan_ns,
+                          int64_t* sum_completion_ns);
+
 /* Bubble characterisation by the doubling probe (Sec. 4.2, "Bubble characterization"): how long
  * can stage `stage` of a p-stage, m-microbatch 1F1B pipeline (forward tf_ns, backward tb_ns per
  * microbatch and stage, no communication time) hold back at each of its bubble instructions before

@@ -19,9 +19,10 @@ PF_BUBBLE_FWD_BWD, PF_BUBBLE_GAP, PF_BUBBLE_FILL_DRAIN, PF_BUBBLE_EXPLICIT = 0, 
 PF_OP_EMBED, PF_OP_LAYER_FWD, PF_OP_FINAL_LN, PF_OP_HEAD_LOSS, PF_OP_LAYER_BWD, PF_OP_OPT = range(6)
 PF_DTYPE_F32, PF_DTYPE_BF16 = 0, 1
 PF_INSTR_FWD, PF_INSTR_BWD, PF_INSTR_BUBBLE = 0, 1, 2
+PF_POLICY_FIFO, PF_POLICY_SJF, PF_POLICY_MAKESPAN = 0, 1, 2
 
 EXPORTS = [
-    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from", "pf_probe_bubbles",
+    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from", "pf_probe_bubbles", "pf_job_time", "pf_sched_simulate",
     "pf_select_config", "pf_build_chain", "pf_layer_blob_layout", "pf_ctx_arena_bytes", "pf_ctx_create",
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
@@ -51,6 +52,14 @@ class pf_node(C.Structure):
 class pf_chunk(C.Structure):
     _fields_ = [("bubble", C.c_int32), ("cycle", C.c_int32), ("node_begin", C.c_int32), ("node_end", C.c_int32),
                 ("dur_ns", C.c_int64), ("mem_bytes", C.c_int64)]
+
+
+class pf_job(C.Structure):
+    _fields_ = [("arrival_ns", C.c_int64), ("deadline_ns", C.c_int64)]
+
+
+class pf_job_run(C.Structure):
+    _fields_ = [("start_ns", C.c_int64), ("finish_ns", C.c_int64), ("device", C.c_int32), ("reserved", C.c_int32)]
 
 
 class pf_model_desc(C.Structure):
@@ -95,6 +104,8 @@ def _load():
     lib.pf_schedule_1f1b.argtypes = [I32, I32, I32, I64, I64, I64, I32, I64, P(pf_bubble), I32, P(I32)]
     lib.pf_schedule_gpipe.argtypes = [I32, I32, I32, I64, I64, I64, P(pf_bubble), I32, P(I32)]
     lib.pf_plan_bubbles.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, P(pf_chunk), I32, P(I32), P(I32)]
+    lib.pf_job_time.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I64, I64, I64, P(I64)]
+    lib.pf_sched_simulate.argtypes = [I32, P(pf_job), I32, I32, P(I64), P(pf_job_run), P(I64), P(I64)]
     lib.pf_probe_bubbles.argtypes = [I32, I32, I32, I64, I64, I64, I64, P(I64), I32, P(I32)]
     lib.pf_plan_bubbles_from.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, I64, P(pf_chunk), I32, P(I32),
                                          P(I32)]
@@ -176,6 +187,27 @@ def pf_schedule_gpipe(p, m, stage, tf_ns, tb_ns, free_bytes, cap=2):
     n = C.c_int32(0)
     _check(lib.pf_schedule_gpipe(p, m, stage, tf_ns, tb_ns, free_bytes, out, cap, C.byref(n)))
     return [_bubble_dict(out[i]) for i in range(n.value)]
+
+
+def pf_job_time(bubbles, F, samples_per_replica, total_samples, iter_ns, fill_ppm=1_000_000, switch_ns=0):
+    t = C.c_int64(0)
+    _check(lib.pf_job_time(bubbles_to_c(bubbles), len(bubbles), nodes_to_c(F), len(F), samples_per_replica,
+                           total_samples, iter_ns, fill_ppm, switch_ns, C.byref(t)))
+    return t.value
+
+
+def pf_sched_simulate(policy, jobs, proc, n_dev):
+    """jobs: list of dicts (arrival[, deadline]); proc[j][i].  Returns ([(device, start, finish)], makespan, sum)."""
+    n = len(jobs)
+    cj = (pf_job * max(1, n))()
+    for i, j in enumerate(jobs):
+        cj[i].arrival_ns = j["arrival"]
+        cj[i].deadline_ns = j.get("deadline", -1)
+    flat = (C.c_int64 * max(1, n * n_dev))(*[proc[j][d] for j in range(n) for d in range(n_dev)])
+    runs = (pf_job_run * max(1, n))()
+    mk, sm = C.c_int64(0), C.c_int64(0)
+    _check(lib.pf_sched_simulate(policy, cj, n, n_dev, flat, runs, C.byref(mk), C.byref(sm)))
+    return [(runs[i].device, runs[i].start_ns, runs[i].finish_ns) for i in range(n)], mk.value, sm.value
 
 
 def pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm=0):

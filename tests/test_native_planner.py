@@ -250,3 +250,38 @@ def test_probe_bubbles_bit_exact_and_errors():
     nn = C.c_int32(0)
     buf = (C.c_int64 * 1)()
     assert pf.lib.pf_probe_bubbles(4, 8, 0, 10, 20, 1, 0, buf, 1, C.byref(nn)) == pf.PF_ERR_CAPACITY and nn.value == 4
+
+
+def test_scheduler_bit_exact_and_errors():
+    import random
+    from oracle import scheduler as sc
+    rnd = random.Random(9)
+    for trial in range(400):
+        n, d = rnd.randint(1, 12), rnd.randint(1, 4)
+        jobs = [dict(arrival=rnd.randint(0, 40) * rnd.choice([0, 1, 1])) for _ in range(n)]
+        proc = [[rnd.randint(1, 25) for _ in range(d)] for _ in range(n)]
+        for policy in (pf.PF_POLICY_FIFO, pf.PF_POLICY_SJF, pf.PF_POLICY_MAKESPAN):
+            assert pf.pf_sched_simulate(policy, jobs, proc, d) == sc.simulate(policy, jobs, proc, d), (trial, policy)
+    # processing times from plans, on cfg2's eight stages with a synthetic chain
+    p, m, tf, tb, free = synth.SCHEDULES["cfg2"]
+    F = [(150_000, 1 << 30)] + [(231_000 + 1000 * l, 3 << 30) for l in range(12)] + [(40_000, 1 << 30)]
+    iter_ns = op.iteration_time(p, m, tf, tb)
+    for s in range(p):
+        B = op.windows_1f1b(p, m, s, tf, tb, free)
+        for total in (1, 32 * 500, 10**7):
+            assert pf.pf_job_time(B, F, 32, total, iter_ns, 900_000, 20_000) == sc.job_time(B, F, 32, total, iter_ns, 900_000, 20_000)
+    with pytest.raises(pf.PipeFillError) as e:
+        pf.pf_job_time([dict(dur=10, free=5)], [(10, 5)], 1, 1, 100)
+    assert e.value.code == pf.PF_ERR_INFEASIBLE
+    for kw in (dict(samples_per_replica=0), dict(total_samples=0), dict(iter_ns=0)):
+        args = dict(samples_per_replica=1, total_samples=1, iter_ns=1)
+        args.update(kw)
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_job_time([dict(dur=100, free=5)], [(10, 5)], **args)
+        assert e.value.code == pf.PF_ERR_ARG
+    for bad in (dict(policy=3), dict(proc=[[0]]), dict(jobs=[dict(arrival=-1)])):
+        kw = dict(policy=0, jobs=[dict(arrival=0)], proc=[[5]], n_dev=1)
+        kw.update(bad)
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_sched_simulate(**kw)
+        assert e.value.code == pf.PF_ERR_ARG
