@@ -190,6 +190,7 @@ def run_cfg2(args, np, torch, pf, dev, synth):
     # only the roofline kernel is bracketed by events during the timed steps (every pair costs a few
     # microseconds on the fill stream); the other classes are measured in two extra steps afterwards
     model.ctx.pf_ctx_kernel_timing(1 << pf.PF_K_GEMM_FFN1)
+    model.ctx.pf_ctx_kernel_timing_every(8)     # one FFN1 launch in eight: an event pair costs ~10 us of stream time
     torch.cuda.synchronize()
     agg = dict.fromkeys(AGG_KEYS, 0)
     t0 = time.perf_counter()
@@ -205,6 +206,7 @@ def run_cfg2(args, np, torch, pf, dev, synth):
     tokens = agg["replicas_done"] * shape.tokens
     dominant = kernel_rates(model.ctx, pf, shape)
     model.ctx.pf_ctx_kernel_timing(0x7f)
+    model.ctx.pf_ctx_kernel_timing_every(1)
     run_step.reset()
     for i in range(2):
         run_step(0)

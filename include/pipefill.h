@@ -362,6 +362,11 @@ int32_t pf_ctx_train_state(pf_ctx* ctx, double* loss, int64_t* steps);
 int32_t pf_ctx_read_params(pf_ctx* ctx, int32_t what, int32_t layer, void* dst, int64_t dst_bytes,
                            void* stream);
 
+/* Sampling for pf_ctx_kernel_timing: only every n-th launch of an enabled class is bracketed by events
+ * (n >= 1, default 1).  An event pair costs about 10 us of stream time around the launch it brackets, so a
+ * caller that times a kernel inside a throughput measurement samples it. */
+int32_t pf_ctx_kernel_timing_every(pf_ctx* ctx, int32_t n);
+
 /* Per-kernel-class timing.  mask: bit k enables class PF_K_k; enabled launches are bracketed by HIP
  * events on the stream they run on (a fixed pool of 16384 pairs between two reads; launches
  * beyond it run untimed).  pf_ctx_kernel_stats synchronises the device, folds the pool into the

@@ -26,7 +26,7 @@ EXPORTS = [
     "pf_select_config", "pf_build_chain", "pf_layer_blob_layout", "pf_ctx_arena_bytes", "pf_ctx_create",
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
-    "pf_ctx_set_replan", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
+    "pf_ctx_set_replan", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
     "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd",
 ]
 PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
@@ -127,6 +127,7 @@ def _load():
     lib.pf_timeline_run.argtypes = [VP, VP, VP, I32, I32, I32, I64, I64, P(pf_bubble), I32, P(pf_chunk), I32,
                                     P(pf_node), I32, P(I32), VP, VP, P(pf_timeline_stats)]
     lib.pf_ctx_set_replan.argtypes = [VP, I32, I64, I64]
+    lib.pf_ctx_kernel_timing_every.argtypes = [VP, I32]
     lib.pf_ctx_train_state.argtypes = [VP, P(C.c_double), P(I64)]
     lib.pf_ctx_read_params.argtypes = [VP, I32, I32, VP, I64, VP]
     lib.pf_ctx_kernel_timing.argtypes = [VP, C.c_uint32]
@@ -408,6 +409,9 @@ class Context:
         t = C.c_int64(0)
         _check(lib.pf_ctx_kernel_stats(self.handle, cls, C.byref(n), C.byref(t)))
         return n.value, t.value
+
+    def pf_ctx_kernel_timing_every(self, n):
+        _check(lib.pf_ctx_kernel_timing_every(self.handle, n))
 
     def pf_ctx_set_replan(self, enable, fill_ppm=1000000, switch_ns=0):
         _check(lib.pf_ctx_set_replan(self.handle, int(bool(enable)), fill_ppm, switch_ns))

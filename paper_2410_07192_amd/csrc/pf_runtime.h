@@ -104,6 +104,8 @@ struct pf_ctx {
   // optional per-kernel-class timing with HIP events on the launching stream
   struct TimedPair { hipEvent_t a, b; int32_t cls; };
   uint32_t timing_mask = 0;
+  int32_t timing_every = 1;                      // bracket every n-th launch of an enabled class
+  uint64_t cls_seen[PF_KERNEL_CLASSES] = {};
   std::vector<TimedPair> timing_pool;
   size_t timing_used = 0;
   int64_t cls_count[PF_KERNEL_CLASSES] = {};

@@ -285,6 +285,7 @@ struct TimedScope {
   hipEvent_t end = nullptr;
   TimedScope(pf_ctx* ctx, int32_t cls, hipStream_t s) : c(ctx), st(s) {
     if (!((c->timing_mask >> cls) & 1u) || c->timing_used >= c->timing_pool.size()) return;
+    if (c->timing_every > 1 && (c->cls_seen[cls]++ % c->timing_every) != 0) return;   // sampled launches only
     pf_ctx::TimedPair& p = c->timing_pool[c->timing_used];
     if (hipEventRecord(p.a, st) != hipSuccess) return;
     p.cls = cls;
@@ -816,6 +817,13 @@ int32_t pf_ctx_kernel_timing(pf_ctx* c, uint32_t mask) {
     c->cls_ms[i] = 0.0;
   }
   c->timing_mask = mask;
+  return PF_OK;
+}
+
+int32_t pf_ctx_kernel_timing_every(pf_ctx* c, int32_t n) {
+  if (!c || n < 1) return pf::fail(PF_ERR_ARG, "pf_ctx_kernel_timing_every: bad argument");
+  c->timing_every = n;
+  for (int i = 0; i < PF_KERNEL_CLASSES; ++i) c->cls_seen[i] = 0;
   return PF_OK;
 }
 
