@@ -223,6 +223,9 @@ def run_cfg2(args, np, torch, pf, dev, synth):
         "fill_tflops_in_bubbles": agg["replicas_done"] * shape.n_layers * layer_fwd_flops(shape) /
         (agg["offered_ns"] * 1e-9) * 1e-12,
         "chain_ms": chain_ns * 1e-6, "planner_ms_all_stages": t_plan * 1e3,
+        # the same job with the GPU to itself (profiled chain, back to back): what a bubble-second is worth against it
+        "exclusive_tokens_per_s": shape.tokens / (chain_ns * 1e-9),
+        "fill_vs_exclusive": (tokens / (agg["offered_ns"] * 1e-9)) / (shape.tokens / (chain_ns * 1e-9)),
         "roofline": ffn1_roofline(kernels, shape, traffic=FFN1_CFG2_TRAFFIC_BYTES), "kernels": kernels})
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs)
@@ -366,6 +369,8 @@ def run_cfg4(args, np, torch, pf, dev, synth):
         **fill_stats(agg), "main_slowdown_pct": None,
         "fill_tflops_in_bubbles": agg["replicas_done"] * step_flops / (agg["offered_ns"] * 1e-9) * 1e-12,
         "chain_ms": chain_ns * 1e-6, "optimizer_steps": steps1 - steps0, "mean_loss": loss,
+        "exclusive_tokens_per_s": shape.tokens / (chain_ns * 1e-9),
+        "fill_vs_exclusive": (tokens / (agg["offered_ns"] * 1e-9)) / (shape.tokens / (chain_ns * 1e-9)),
         "arena_gib": model.arena_bytes / GIB,
         "node_ms": {"layer_fwd": model.chain[1].dur_ns * 1e-6, "head_loss": model.chain[L + 2].dur_ns * 1e-6,
                     "layer_bwd": model.chain[L + 3].dur_ns * 1e-6, "opt": model.chain[len(model.chain) - 1].dur_ns * 1e-6},
