@@ -7,14 +7,18 @@
 //    swizzle that keeps the later MFMA operand reads free of bank conflicts is applied on the global
 //    side (lane -> which chunk of the row it fetches).  Rows beyond M / N are clamped to the last
 //    valid row (their products are never stored).
-//  * Two LDS stages: the loads of step k+2 are issued right after the barrier that ends the reads
-//    of step k and have a whole step to land.  They are written as inline assembly so that the
-//    compiler does not serialise every later LDS read behind them; vmcnt is waited by hand.
+//  * Two LDS stages: the loads of step k+2 go into the stage that the barrier ending step k has
+//    freed.  They are issued one at a time between the MFMAs of the following blocks (a burst
+//    blocks every wave at the address unit) and are inline assembly so that the compiler does not
+//    serialise every later LDS read behind them; vmcnt is waited by hand.
 //  * Operand fragments are double buffered in registers: the 16-byte LDS reads of sub-step kk+1
 //    are in flight while the MFMAs of sub-step kk issue.
 //  * The weight tile is the MFMA "A" operand and the activation tile the "B" operand, so each lane
-//    ends up with 4 consecutive output columns of one output row: bias / GELU / residual are applied
-//    in registers and stored as 8-byte pieces.
+//    ends up with 4 consecutive output columns of one output row: bias / GELU are applied in
+//    registers; bf16 tiles then pass through LDS and leave as 16-byte row-contiguous stores (the
+//    residual is added on the way out), other epilogues store 8- or 16-byte pieces directly.
+//  * Three tile shapes (256x256, 256x192, 128x128), chosen per launch by an estimate of rounds x
+//    steps x area; accumulating fp32 launches may split K (gemm_tile.h).
 //  * Workgroup ids are remapped so that each of the 8 XCDs (ids are dealt round-robin to them) works
 //    on a contiguous range of tiles and its L2 sees each operand panel once.
 // bf16 generic path (any K multiple of 8): register-staged LDS tiles, same MFMA layout.
@@ -52,7 +56,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_generic_kernel(
   // buffer b: X tile at smem + b*(BM+BN)*8, W tile right after it
 
   // tile coordinates: contiguous range per XCD, grouped so `group_m` row tiles share the sweep over N
-  const int64_t tile = xcd_tile(blockIdx.x, (int64_t)tiles_m * tiles_n);
+  const int64_t tile = xcd_contiguous(blockIdx.x, (int64_t)tiles_m * tiles_n);
   const int64_t per_group = (int64_t)group_m * tiles_n;
   const int64_t grp = tile / per_group;
   const int32_t first_m = (int32_t)(grp * group_m);

@@ -131,12 +131,6 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// workgroup id -> tile id such that XCD x (ids congruent x mod 8) gets a contiguous tile range
-__device__ __forceinline__ int64_t xcd_tile(int64_t pid, int64_t n_tiles) {
-  const int64_t q = n_tiles >> 3, rem = n_tiles & 7;
-  const int64_t x = pid & 7, local = pid >> 3;
-  return x * q + (x < rem ? x : rem) + local;
-}
 
 // ------------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -151,7 +145,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   static_assert(G % NW == 0 && GPW <= 32, "tile / wave mismatch");
   extern __shared__ uint4 smem[];
 
-  const int64_t tile = xcd_tile(blockIdx.x, (int64_t)tiles_m * tiles_n);
+  const int64_t tile = xcd_contiguous(blockIdx.x, (int64_t)tiles_m * tiles_n);
   const int64_t per_group = (int64_t)group_m * tiles_n;
   const int64_t grp = tile / per_group;
   const int32_t first_m = (int32_t)(grp * group_m);
