@@ -125,9 +125,9 @@ def kernel_rates(ctx, pf, shape):
 
 # HBM-side traffic of one FFN1 launch of the default workload (M=16384, N=3072, K=768), from two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a plain
-# 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0): 108.6 MiB fetched + 96.0 MiB written.  Algorithmic:
+# 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0): 108.3 MiB fetched + 96.0 MiB written.  Algorithmic:
 # 28.5 MiB read (X, W, bias) + 96 MiB written.  A profiler run is needed to refresh it.
-FFN1_CFG2_TRAFFIC_BYTES = int((108.6 + 96.0) * (1 << 20))
+FFN1_CFG2_TRAFFIC_BYTES = int((108.3 + 96.0) * (1 << 20))
 
 
 def ffn1_roofline(kernels, shape, tile="2,4,4,2", traffic=None):
