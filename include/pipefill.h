@@ -230,7 +230,7 @@ int32_t pf_select_config(const pf_bubble* B, int32_t nB, const pf_node* const* c
                          int32_t* best, int32_t* replicas_out, int32_t* cycles_out,
                          int32_t* chunks_out);
 
-/* ---- job description -> chain of nodes (Sec. 4.3 "linearizes the computational graph") ---- */
+/* ---- job description -> chain of nodes (Sec. 4.3: the job's graph is flattened into a chain) ---- */
 /* Writes the node list of one replica (g microbatches): [EMBED] L x LAYER_FWD FINAL_LN, and for
  * training HEAD_LOSS, L x LAYER_BWD (last layer first), OPT.  mem_bytes is the node's peak HBM
  * footprint including everything kept resident between bubbles; dur_ns is left 0 (fill it with
@@ -271,7 +271,7 @@ int32_t pf_ctx_set_io(pf_ctx* ctx, const void* in, int32_t n_in, void* out, int3
 int32_t pf_load_layer_async(pf_ctx* ctx, int32_t layer, int32_t slot, void* copy_stream);
 
 /* Run one chunk's forward-type nodes (EMBED, LAYER_FWD, FINAL_LN, HEAD_LOSS) on fill_stream
- * (Sec. 4.3: "execute the current graph partition on the current bubble").  F/nF: the chain the
+ * (Sec. 4.3: the Executor runs the current partition in the current bubble).  F/nF: the chain the
  * plan was made from (host).  The hidden states cut by the end of the chunk stay in the
  * context until the next chunk (inter-bubble context).  act_in (device, may be NULL): overrides
  * the source of the chunk's first node (token ids for EMBED, else hidden states

@@ -21,7 +21,7 @@ Readings where the paper is silent (each is listed in the design notes):
   - stages are 0-based; communication, gradient-sync and optimizer time are 0;
   - time tests are strict (<), the memory test is <=, exactly as in the
     listing of Algorithm 1; memory is tested per node;
-  - the "fraction of the bubble the Executor tries to fill" (Sec. 6.1) scales
+  - the share of each bubble that the Executor is allowed to fill (Sec. 6.1) scales
     every bubble duration by fill_ppm/1e6 with floor division, and a fixed
     per-bubble switch cost may be subtracted;
   - a node that fits no bubble would make Algorithm 1 loop forever; here the
@@ -330,8 +330,8 @@ def stage_program_1f1b(p, m, s):
 def pipeline_period_with_waits(p, m, tf, tb, s, waits, iterations=4):
     """Steady-state iteration period of a p-stage 1F1B pipeline in which stage s, at its
     bubble instruction k, does not proceed before waits[k] has passed since its previous
-    instruction ended (Sec. 4.2: "wait a certain amount of time before proceeding to
-    execute the next instruction").  Plain dependency simulation: forward j of stage q needs
+    instruction ended (Sec. 4.2: during profiling the engine holds back the instruction
+    after a bubble instruction for a set time).  Plain dependency simulation: forward j of stage q needs
     forward j of stage q-1, backward j of stage q needs backward j of stage q+1, each stage
     runs its instructions in order, iterations follow each other without a gap.  Returns the
     time between the ends of the last two simulated iterations."""

@@ -2,7 +2,7 @@
 event-driven simulation of Sec. 5.1, in plain Python integers.
 
 A job's processing time on a device follows from the device's bubble cycle, the job's profile
-and Algorithm 1 (Sec. 4.4: "precisely calculate any fill-job's processing-time on any device").
+and Algorithm 1 (Sec. 4.4: the Scheduler can work out exactly how long any fill job takes on any device).
 When a device is free and jobs wait, the job with the largest policy score is submitted to it:
   FIFO      score = -arrival
   SJF       score = 1 / min(j.proc_times)                      (Sec. 4.4, first formula)
