@@ -205,6 +205,27 @@ int32_t pf_probe_bubbles(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int
                          int64_t first_wait_ns, int64_t tol_ppm, int64_t* est_ns, int32_t cap,
                          int32_t* n_out);
 
+/* Plan of the main job's optimizer-state offload (Sec. 4.2, "Main job offloading"): the moment
+ * estimates are only read by the optimizer update, so part of them leaves the device while the
+ * iteration runs and the idle windows gain that memory.  One slice leaves with each of the m
+ * forward instructions of stage `stage` (1F1B, p stages), on a stream of its own; everything comes
+ * back during the gradient synchronisation of sync_ns that follows the stage's last backward.
+ * A slice is the largest multiple of 256 bytes that d2h_bytes_per_s moves within tf_ns (its copy
+ * is over when its forward is, so no bubble instruction waits for it); the total is the smallest
+ * of state_bytes rounded down to 256, m slices, and what h2d_bytes_per_s moves within sync_ns
+ * rounded down to 256 (the optimizer update does not wait either); the forwards take full slices
+ * first to last until the total is used up.
+ * slice_bytes (host, out, m values): bytes leaving with forward 0..m-1.
+ * extra_free (host, out, one value per idle window, same order and count as pf_schedule_1f1b):
+ * bytes that are off the device while that window is open = the slices of the forwards before it
+ * in program order; 0 for the fill-drain window, which follows the optimizer update.  The caller
+ * adds them to the windows' free_bytes.
+ * PF_ERR_CAPACITY (count in *n_windows) if cap is too small; PF_ERR_ARG on a bad argument
+ * (non-positive tf_ns, negative sizes or rates, state_bytes >= 2^62). */
+int32_t pf_offload_plan(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int64_t sync_ns,
+                        int64_t state_bytes, int64_t d2h_bytes_per_s, int64_t h2d_bytes_per_s,
+                        int64_t* slice_bytes, int64_t* extra_free, int32_t cap, int32_t* n_windows);
+
 /* Algorithm 1 for a job that arrives when its first bubble is partly gone (Sec. 4.3: the Executor
  * takes the next job as soon as one completes, which is in the middle of a bubble): exactly
  * pf_plan_bubbles, except that the FIRST visit of bubble `first_bubble` has the duration

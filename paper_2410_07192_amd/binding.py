@@ -22,7 +22,7 @@ PF_INSTR_FWD, PF_INSTR_BWD, PF_INSTR_BUBBLE = 0, 1, 2
 PF_POLICY_FIFO, PF_POLICY_SJF, PF_POLICY_MAKESPAN = 0, 1, 2
 
 EXPORTS = [
-    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from", "pf_probe_bubbles", "pf_job_time", "pf_sched_simulate",
+    "pf_last_error", "pf_version", "pf_schedule_1f1b", "pf_schedule_gpipe", "pf_plan_bubbles", "pf_plan_bubbles_from", "pf_probe_bubbles", "pf_offload_plan", "pf_job_time", "pf_sched_simulate",
     "pf_select_config", "pf_build_chain", "pf_layer_blob_layout", "pf_ctx_arena_bytes", "pf_ctx_create",
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
@@ -107,6 +107,7 @@ def _load():
     lib.pf_job_time.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I64, I64, I64, P(I64)]
     lib.pf_sched_simulate.argtypes = [I32, P(pf_job), I32, I32, P(I64), P(pf_job_run), P(I64), P(I64)]
     lib.pf_probe_bubbles.argtypes = [I32, I32, I32, I64, I64, I64, I64, P(I64), I32, P(I32)]
+    lib.pf_offload_plan.argtypes = [I32, I32, I32, I64, I64, I64, I64, I64, P(I64), P(I64), I32, P(I32)]
     lib.pf_plan_bubbles_from.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, I64, P(pf_chunk), I32, P(I32),
                                          P(I32)]
     lib.pf_select_config.argtypes = [P(pf_bubble), I32, P(P(pf_node)), P(I32), P(I64), I32, I64, I64, I32,
@@ -220,6 +221,20 @@ def pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm=0):
     out = (C.c_int64 * max(1, n.value))()
     _check(lib.pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm, out, n.value, C.byref(n)))
     return [int(out[i]) for i in range(n.value)]
+
+
+def pf_offload_plan(p, m, stage, tf_ns, sync_ns, state_bytes, d2h_bytes_per_s, h2d_bytes_per_s):
+    """(bytes leaving with each forward, bytes off the device in each idle window of the stage)."""
+    n = C.c_int32(0)
+    sl = (C.c_int64 * max(1, m))()
+    rc = lib.pf_offload_plan(p, m, stage, tf_ns, sync_ns, state_bytes, d2h_bytes_per_s, h2d_bytes_per_s, sl, None, 0,
+                             C.byref(n))
+    if rc not in (PF_OK, PF_ERR_CAPACITY):
+        raise PipeFillError(rc, lib.pf_last_error().decode())
+    ex = (C.c_int64 * max(1, n.value))()
+    _check(lib.pf_offload_plan(p, m, stage, tf_ns, sync_ns, state_bytes, d2h_bytes_per_s, h2d_bytes_per_s, sl, ex,
+                               n.value, C.byref(n)))
+    return [int(sl[j]) for j in range(m)], [int(ex[k]) for k in range(n.value)]
 
 
 def pf_plan_bubbles(bubbles, F, fill_ppm=1_000_000, switch_ns=0, first_bubble=0, cap=None, raw=False,

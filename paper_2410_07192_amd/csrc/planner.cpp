@@ -296,6 +296,42 @@ int32_t pf_probe_bubbles(int32_t p, int32_t m, int32_t s, int64_t tf, int64_t tb
   return PF_OK;
 }
 
+int32_t pf_offload_plan(int32_t p, int32_t m, int32_t s, int64_t tf, int64_t sync_ns, int64_t state_bytes,
+                        int64_t d2h, int64_t h2d, int64_t* slice_bytes, int64_t* extra_free, int32_t cap,
+                        int32_t* n_windows) {
+  if (p < 1 || m < 1 || s < 0 || s >= p || tf <= 0 || sync_ns < 0 || state_bytes < 0 || state_bytes >= ((int64_t)1 << 62) || d2h < 0 || h2d < 0 ||
+      !slice_bytes || !n_windows || cap < 0 || (cap > 0 && !extra_free))
+    return pf::fail(PF_ERR_ARG, "pf_offload_plan: bad argument");
+  constexpr int64_t ALIGN = 256, NS = 1000000000;
+  auto moved = [&](int64_t rate, int64_t dur) {
+    const __int128 b = (__int128)rate * dur / NS;
+    const __int128 lim = (__int128)1 << 62;   // above any state_bytes accepted here, so the clamp never shows
+    return (int64_t)((b < lim ? b : lim) / ALIGN * ALIGN);
+  };
+  const int64_t per_fwd = moved(d2h, tf);
+  __int128 total = state_bytes / ALIGN * ALIGN;
+  if ((__int128)per_fwd * m < total) total = (__int128)per_fwd * m;
+  if (moved(h2d, sync_ns) < total) total = moved(h2d, sync_ns);
+  int64_t left = (int64_t)total;
+  for (int32_t j = 0; j < m; ++j) {
+    slice_bytes[j] = left < per_fwd ? left : per_fwd;
+    left -= slice_bytes[j];
+  }
+  const std::vector<StageOp> ops = stage_ops(p, m, s);
+  int32_t n = 0;
+  for (const StageOp& o : ops) n += (o.op == 2);
+  *n_windows = n;
+  if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_offload_plan: %d windows, capacity %d", n, cap);
+  int64_t gone = 0;
+  int32_t k = 0;
+  for (const StageOp& o : ops) {
+    if (o.op == 0) gone += slice_bytes[o.idx];
+    else if (o.op == 2) extra_free[k++] = gone;
+  }
+  if (s > 0) extra_free[n - 1] = 0;   // the fill-drain window follows the optimizer update: the state is back
+  return PF_OK;
+}
+
 int32_t pf_select_config(const pf_bubble* B, int32_t nB, const pf_node* const* chains, const int32_t* n_nodes,
                          const int64_t* samples, int32_t n_cfg, int64_t fill_ppm, int64_t switch_ns,
                          int32_t first_bubble, int32_t* best, int32_t* replicas_out, int32_t* cycles_out,

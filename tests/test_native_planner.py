@@ -1,6 +1,7 @@
 """Native planner (C ABI) against the CPU checker, bit for bit; host-only error paths; exports."""
 import ctypes as C
 import itertools
+import random
 import os
 import re
 
@@ -285,3 +286,35 @@ def test_scheduler_bit_exact_and_errors():
         with pytest.raises(pf.PipeFillError) as e:
             pf.pf_sched_simulate(**kw)
         assert e.value.code == pf.PF_ERR_ARG
+
+
+# ---- main job's optimizer-state offload plan ----------------------------------------------------------
+def test_offload_plan_bit_exact():
+    from oracle import offload as OO
+    rng = random.Random(77)
+    for _ in range(300):
+        p = rng.randint(1, 16)
+        m = rng.randint(1, 40)
+        s = rng.randrange(p)
+        tf = rng.randint(1, 10**8)
+        sync = rng.choice([0, rng.randint(1, 10**9)])
+        state = rng.choice([0, rng.randint(0, 1 << 20), rng.randint(0, 1 << 40), (1 << 62) - 1])
+        d2h = rng.choice([0, rng.randint(1, 10**12), rng.randint(1, 1 << 62)])
+        h2d = rng.choice([0, rng.randint(1, 10**12), rng.randint(1, 1 << 62)])
+        sl, ex = pf.pf_offload_plan(p, m, s, tf, sync, state, d2h, h2d)
+        want = OO.offload_slices(state, m, tf, sync, d2h, h2d)
+        assert sl == want
+        assert ex == OO.extra_free_bytes(p, m, s, want)
+
+
+def test_offload_plan_errors():
+    for bad in [(0, 4, 0, 10, 10, 100, 1, 1), (4, 0, 0, 10, 10, 100, 1, 1), (4, 4, 4, 10, 10, 100, 1, 1),
+                (4, 4, 0, 0, 10, 100, 1, 1), (4, 4, 0, 10, -1, 100, 1, 1), (4, 4, 0, 10, 10, -1, 1, 1),
+                (4, 4, 0, 10, 10, 1 << 62, 1, 1), (4, 4, 0, 10, 10, 100, -1, 1), (4, 4, 0, 10, 10, 100, 1, -1)]:
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_offload_plan(*bad)
+        assert e.value.code == pf.PF_ERR_ARG
+    n = C.c_int32(0)
+    sl = (C.c_int64 * 4)()
+    rc = pf.lib.pf_offload_plan(4, 4, 1, 10, 10, 100, 1, 1, sl, None, 0, C.byref(n))
+    assert rc == pf.PF_ERR_CAPACITY and n.value == 4
