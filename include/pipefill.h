@@ -55,7 +55,7 @@ enum { PF_K_GEMM_QKV = 0, PF_K_GEMM_OUT = 1, PF_K_GEMM_FFN1 = 2, PF_K_GEMM_FFN2 
 
 /* instructions of the emulated main-job stage (Sec. 4.2: forward / backward of a microbatch,
  * and the pipeline bubble instruction) */
-enum { PF_INSTR_FWD = 0, PF_INSTR_BWD = 1, PF_INSTR_BUBBLE = 2 };
+enum { PF_INSTR_FWD = 0, PF_INSTR_BWD = 1, PF_INSTR_BUBBLE = 2, PF_INSTR_OPT = 3 };
 
 /* One bubble of the cycle that repeats every main-job iteration (the lists B and M of
  * Algorithm 1): start relative to the global iteration start, duration, free HBM. */
@@ -322,7 +322,9 @@ int32_t pf_profile_chain(pf_ctx* ctx, pf_node* F, int32_t nF, int32_t warmup, in
  * layers are the stage's layers.  PF_INSTR_FWD: forward of microbatch `index` through all
  * layers, keeping per-layer checkpoints; PF_INSTR_BWD: recompute + backward of microbatch
  * `index`, accumulating weight gradients.  `io`: device hidden states [batch][seq][d] (input
- * for FWD; upstream gradient for BWD).  Enqueues on main_stream and returns.
+ * for FWD; upstream gradient for BWD).  PF_INSTR_OPT: Adam update of all the stage's parameters
+ * from the gradients accumulated over `index` microbatches (index >= 1; io is ignored and may be
+ * NULL), working copies recast, accumulators cleared.  Enqueues on main_stream and returns.
  * PF_INSTR_BUBBLE is handled by pf_timeline_run and is rejected here with PF_ERR_ARG. */
 int32_t pf_main_stage_step(pf_ctx* ctx, int32_t instr, int32_t index, const void* io,
                            void* main_stream);
@@ -337,7 +339,32 @@ typedef struct pf_timeline_stats {
   int64_t main_busy_ns;     /* main-stream busy time (0 when the main stage is a placeholder)    */
   int32_t chunks_run;       /* non-empty chunks executed                                         */
   int32_t replicas_done;    /* replicas of the chain completed in this iteration                 */
+  int64_t offload_wait_ns;  /* host time the main stage was held up by its own offload copies:
+                               at bubble instructions and before the optimizer update            */
+  int64_t offloaded_bytes;  /* optimizer-state bytes that left the device and came back          */
 } pf_timeline_stats;
+
+/* Optimizer phase of the emulated main stage, and offload of its optimizer state around it
+ * (Sec. 4.2, "Main job offloading" and step 2 of "Bubble signaling").
+ * pf_main_opt_state_bytes: *bytes = size of the stage's Adam moment estimates (two fp32 values
+ * per parameter), seen as one byte string: first and second moments of layer 0, of layer 1, ...
+ * pf_ctx_set_main_offload, sync_ns >= 0: from now on pf_timeline_run with this main_ctx ends the
+ * stage's work of an iteration, after its last backward and before the fill-drain window, with a
+ * gradient synchronisation (no peers here: the main stream idles for sync_ns) followed by
+ * PF_INSTR_OPT over the m microbatches.  sync_ns < 0 switches the phase off again (the default).
+ * slice_bytes/n_slices (host; n_slices == 0: no offload, else n_slices must equal the m of the
+ * timeline, e.g. from pf_offload_plan): with forward instruction j the next slice_bytes[j] bytes
+ * of the string are copied to host_buf (pinned host memory the caller owns and keeps alive,
+ * host_bytes >= the sum) on a stream of the context's own; every bubble instruction first waits
+ * for the copies under way; the synchronisation starts the copies back and the optimizer update
+ * waits for them.  Time the main stage loses to either wait is reported as offload_wait_ns.
+ * scrub != 0: at each bubble instruction what has left the device is overwritten there with 0xff
+ * bytes (as a fill job using that memory would), so a caller can check that the state comes back
+ * intact.  Slices must be multiples of 4 bytes and sum to at most the state.
+ * Errors: PF_ERR_ARG, PF_ERR_STATE (not a main-stage context), PF_ERR_CAPACITY (host_bytes). */
+int32_t pf_main_opt_state_bytes(pf_ctx* main_ctx, int64_t* bytes);
+int32_t pf_ctx_set_main_offload(pf_ctx* main_ctx, int64_t sync_ns, void* host_buf, int64_t host_bytes,
+                                const int64_t* slice_bytes, int32_t n_slices, int32_t scrub);
 
 /* What the Executor does when a plan completes (all its replicas ran) in the middle of a bubble
  * cycle.  enable == 0 (the default): the same plan is reused and the remaining windows of the
@@ -378,7 +405,8 @@ int32_t pf_timeline_run(pf_ctx* fill_ctx, pf_ctx* main_ctx, const void* main_io,
 int32_t pf_ctx_train_state(pf_ctx* ctx, double* loss, int64_t* steps);
 
 /* Copy parameter gradients / master weights of layer `layer` (blob layout, fp32 elements at the
- * same element order) to `dst` (device, fp32).  what: 0 accumulated gradients, 1 master weights.
+ * same element order) to `dst` (device, fp32).  what: 0 accumulated gradients, 1 master weights,
+ * 2 first-moment estimates, 3 second-moment estimates.
  * layer == -1: tok_emb | pos_emb | lnf_g | lnf_b concatenated.  For tests of training jobs. */
 int32_t pf_ctx_read_params(pf_ctx* ctx, int32_t what, int32_t layer, void* dst, int64_t dst_bytes,
                            void* stream);

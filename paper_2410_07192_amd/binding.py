@@ -18,7 +18,7 @@ PF_OK, PF_ERR_ARG, PF_ERR_CAPACITY, PF_ERR_INFEASIBLE, PF_ERR_NOMEM, PF_ERR_HIP,
 PF_BUBBLE_FWD_BWD, PF_BUBBLE_GAP, PF_BUBBLE_FILL_DRAIN, PF_BUBBLE_EXPLICIT = 0, 1, 2, 3
 PF_OP_EMBED, PF_OP_LAYER_FWD, PF_OP_FINAL_LN, PF_OP_HEAD_LOSS, PF_OP_LAYER_BWD, PF_OP_OPT = range(6)
 PF_DTYPE_F32, PF_DTYPE_BF16 = 0, 1
-PF_INSTR_FWD, PF_INSTR_BWD, PF_INSTR_BUBBLE = 0, 1, 2
+PF_INSTR_FWD, PF_INSTR_BWD, PF_INSTR_BUBBLE, PF_INSTR_OPT = 0, 1, 2, 3
 PF_POLICY_FIFO, PF_POLICY_SJF, PF_POLICY_MAKESPAN = 0, 1, 2
 
 EXPORTS = [
@@ -26,7 +26,7 @@ EXPORTS = [
     "pf_select_config", "pf_build_chain", "pf_layer_blob_layout", "pf_ctx_arena_bytes", "pf_ctx_create",
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
-    "pf_ctx_set_replan", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
+    "pf_ctx_set_replan", "pf_main_opt_state_bytes", "pf_ctx_set_main_offload", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
     "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd",
 ]
 PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
@@ -85,7 +85,8 @@ class pf_adam(C.Structure):
 class pf_timeline_stats(C.Structure):
     _fields_ = [("iter_ns", C.c_int64), ("offered_ns", C.c_int64), ("idle_ns", C.c_int64),
                 ("fill_busy_ns", C.c_int64), ("overrun_ns", C.c_int64), ("main_busy_ns", C.c_int64),
-                ("chunks_run", C.c_int32), ("replicas_done", C.c_int32)]
+                ("chunks_run", C.c_int32), ("replicas_done", C.c_int32), ("offload_wait_ns", C.c_int64),
+                ("offloaded_bytes", C.c_int64)]
 
     def asdict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_}
@@ -128,6 +129,8 @@ def _load():
     lib.pf_timeline_run.argtypes = [VP, VP, VP, I32, I32, I32, I64, I64, P(pf_bubble), I32, P(pf_chunk), I32,
                                     P(pf_node), I32, P(I32), VP, VP, P(pf_timeline_stats)]
     lib.pf_ctx_set_replan.argtypes = [VP, I32, I64, I64]
+    lib.pf_main_opt_state_bytes.argtypes = [VP, P(I64)]
+    lib.pf_ctx_set_main_offload.argtypes = [VP, I64, VP, I64, P(I64), I32, I32]
     lib.pf_ctx_kernel_timing_every.argtypes = [VP, I32]
     lib.pf_ctx_train_state.argtypes = [VP, P(C.c_double), P(I64)]
     lib.pf_ctx_read_params.argtypes = [VP, I32, I32, VP, I64, VP]
@@ -436,6 +439,16 @@ class Context:
         steps = C.c_int64(0)
         _check(lib.pf_ctx_train_state(self.handle, C.byref(loss), C.byref(steps)))
         return loss.value, steps.value
+
+    def pf_main_opt_state_bytes(self):
+        n = C.c_int64(0)
+        _check(lib.pf_main_opt_state_bytes(self.handle, C.byref(n)))
+        return n.value
+
+    def pf_ctx_set_main_offload(self, sync_ns, host_ptr=None, host_bytes=0, slice_bytes=(), scrub=False):
+        n = len(slice_bytes)
+        arr = (C.c_int64 * max(1, n))(*slice_bytes)
+        _check(lib.pf_ctx_set_main_offload(self.handle, sync_ns, host_ptr, host_bytes, arr, n, int(bool(scrub))))
 
     def pf_ctx_read_params(self, what, layer, dst_ptr, dst_bytes, stream=None):
         _check(lib.pf_ctx_read_params(self.handle, what, layer, dst_ptr, dst_bytes, stream))

@@ -60,6 +60,14 @@ int32_t train_fwd_node(pf_ctx* c, const pf_node& n, int64_t replica, hipStream_t
 int32_t train_bwd_node(pf_ctx* c, const pf_node& n, int64_t replica, const void* grad_in, hipStream_t st);
 int32_t train_main_step(pf_ctx* c, int32_t instr, int32_t index, const void* io, hipStream_t st);
 int32_t train_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, hipStream_t st);
+// Optimizer state of a training context as one byte string: first and second moments of layer 0, of layer 1, ...
+int64_t train_opt_state_bytes(const pf_ctx* c);
+// copies bytes [off, off + len) of that string to (to_host) or from `host + off` (pinned host memory)
+int32_t train_opt_state_copy(pf_ctx* c, int64_t off, int64_t len, char* host, bool to_host, hipStream_t st);
+// overwrites bytes [off, off + len) of it with `byte`
+int32_t train_opt_state_fill(pf_ctx* c, int64_t off, int64_t len, int32_t byte, hipStream_t st);
+// optimizer update of an emulated main stage after `microbatches` accumulated backward passes
+int32_t train_main_opt(pf_ctx* c, int32_t microbatches, hipStream_t st);
 // one pre-LN layer forward for one microbatch with the weights at wb (blob layout)
 int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st);
 }  // namespace pf
@@ -101,6 +109,15 @@ struct pf_ctx {
   // the hidden states currently carried come from here when the next node starts a replica
   int32_t device = 0;
   pf::TrainState* tr = nullptr;   // training contexts only
+  // emulated main stage: optimizer phase after the last backward, and offload of the optimizer state around it
+  struct MainOffload {
+    bool opt_phase = false;          // gradient synchronisation (a wait of sync_ns) + optimizer update each iteration
+    int64_t sync_ns = 0;
+    char* host = nullptr;            // caller's pinned host buffer
+    std::vector<int64_t> slices;     // bytes leaving with forward j (empty: nothing is offloaded)
+    bool scrub = false;              // overwrite what has left the device until it comes back
+    hipStream_t stream = nullptr;    // the copies' own stream
+  } off;
   // optional per-kernel-class timing with HIP events on the launching stream
   struct TimedPair { hipEvent_t a, b; int32_t cls; };
   uint32_t timing_mask = 0;

@@ -202,6 +202,7 @@ int32_t pf_ctx_destroy(pf_ctx* c) {
   for (hipEvent_t ev : c->slot_ready) if (ev) (void)hipEventDestroy(ev);
   for (hipEvent_t ev : c->slot_free) if (ev) (void)hipEventDestroy(ev);
   if (c->copy_stream) (void)hipStreamDestroy(c->copy_stream);
+  if (c->off.stream) (void)hipStreamDestroy(c->off.stream);
   if (c->tr) pf::train_destroy(c);
   for (auto& p : c->timing_pool) {
     if (p.a) (void)hipEventDestroy(p.a);
@@ -569,13 +570,54 @@ static void wait_until(int64_t deadline) {
 }
 
 int32_t pf_main_stage_step(pf_ctx* c, int32_t instr, int32_t index, const void* io, void* main_stream) {
-  if (!c || !io || index < 0) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: bad argument");
+  if (!c || index < 0 || (!io && instr != PF_INSTR_OPT)) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: bad argument");
   if (instr == PF_INSTR_BUBBLE)
     return pf::fail(PF_ERR_ARG, "pf_main_stage_step: the bubble instruction is executed by pf_timeline_run");
-  if (instr != PF_INSTR_FWD && instr != PF_INSTR_BWD) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: unknown instruction");
+  if (instr != PF_INSTR_FWD && instr != PF_INSTR_BWD && instr != PF_INSTR_OPT)
+    return pf::fail(PF_ERR_ARG, "pf_main_stage_step: unknown instruction");
   if (!c->tr || c->md.vocab != 0)
     return pf::fail(PF_ERR_STATE, "pf_main_stage_step: needs a training context without vocabulary");
+  if (instr == PF_INSTR_OPT) {
+    if (index < 1) return pf::fail(PF_ERR_ARG, "pf_main_stage_step: the optimizer update needs the number of microbatches");
+    return pf::train_main_opt(c, index, (hipStream_t)main_stream);
+  }
   return pf::train_main_step(c, instr, index, io, (hipStream_t)main_stream);
+}
+
+int32_t pf_main_opt_state_bytes(pf_ctx* c, int64_t* bytes) {
+  if (!c || !bytes) return pf::fail(PF_ERR_ARG, "pf_main_opt_state_bytes: bad argument");
+  if (!c->tr || c->md.vocab != 0)
+    return pf::fail(PF_ERR_STATE, "pf_main_opt_state_bytes: needs a training context without vocabulary");
+  *bytes = pf::train_opt_state_bytes(c);
+  return PF_OK;
+}
+
+int32_t pf_ctx_set_main_offload(pf_ctx* c, int64_t sync_ns, void* host_buf, int64_t host_bytes,
+                                const int64_t* slice_bytes, int32_t n_slices, int32_t scrub) {
+  if (!c || n_slices < 0 || (n_slices > 0 && (!slice_bytes || !host_buf || sync_ns < 0)))
+    return pf::fail(PF_ERR_ARG, "pf_ctx_set_main_offload: bad argument");
+  if (!c->tr || c->md.vocab != 0)
+    return pf::fail(PF_ERR_STATE, "pf_ctx_set_main_offload: needs a training context without vocabulary");
+  int64_t total = 0;
+  for (int32_t j = 0; j < n_slices; ++j) {
+    if (slice_bytes[j] < 0 || slice_bytes[j] % 4 != 0)
+      return pf::fail(PF_ERR_ARG, "pf_ctx_set_main_offload: slice %d has %lld bytes (must be >= 0 and a multiple of 4)", j,
+                      (long long)slice_bytes[j]);
+    total += slice_bytes[j];
+    if (total > pf::train_opt_state_bytes(c))
+      return pf::fail(PF_ERR_ARG, "pf_ctx_set_main_offload: the slices exceed the optimizer state of %lld bytes",
+                      (long long)pf::train_opt_state_bytes(c));
+  }
+  if (total > host_bytes)
+    return pf::fail(PF_ERR_CAPACITY, "pf_ctx_set_main_offload: %lld host bytes needed", (long long)total);
+  PF_HIP(hipDeviceSynchronize());
+  if (n_slices > 0 && !c->off.stream) PF_HIP(hipStreamCreateWithFlags(&c->off.stream, hipStreamNonBlocking));
+  c->off.opt_phase = sync_ns >= 0;
+  c->off.sync_ns = sync_ns >= 0 ? sync_ns : 0;
+  c->off.host = (char*)host_buf;
+  c->off.slices.assign(slice_bytes, slice_bytes + n_slices);
+  c->off.scrub = scrub != 0;
+  return PF_OK;
 }
 
 int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, int32_t m, int32_t stage,
@@ -603,6 +645,7 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   // instruction list of the stage in 1F1B order, bubbles where the schedule has idle windows
   struct Instr { int32_t kind, index; };
   constexpr int32_t INSTR_WAIT = 100;   // explicit cycle: the closed interval before window `index`
+  constexpr int32_t INSTR_SYNC = 101;   // main stage: gradient synchronisation, the optimizer state comes back meanwhile
   std::vector<Instr> prog;
   if (explicit_cycle) {
     for (int32_t k = 0; k < nW; ++k) {
@@ -625,6 +668,15 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
       prog.push_back({PF_INSTR_FWD, fnext++});
       fwd_before = true;
     }
+  }
+  const bool opt_phase = mc && mc->off.opt_phase;
+  const bool offload = opt_phase && !mc->off.slices.empty();
+  if (offload && (int32_t)mc->off.slices.size() != m)
+    return pf::fail(PF_ERR_ARG, "pf_timeline_run: the main stage has %d offload slices for %d forwards",
+                    (int32_t)mc->off.slices.size(), m);
+  if (opt_phase) {   // after the last backward: gradient synchronisation, then the optimizer update
+    prog.push_back({INSTR_SYNC, 0});
+    prog.push_back({PF_INSTR_OPT, m});
   }
   if (stage > 0 && !explicit_cycle) prog.push_back({PF_INSTR_BUBBLE, nb++});
   if (!explicit_cycle && nb != nW)
@@ -650,6 +702,7 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   std::vector<std::pair<hipEvent_t, hipEvent_t>> main_ev;
   const int64_t t_start = now_ns();
   int64_t t_sched = t_start;          // scheduled time of the next instruction (placeholder main stage)
+  int64_t gone = 0, scrubbed = 0;     // bytes of the main job's optimizer state off the device / overwritten there
   for (size_t pc = 0; pc < prog.size() && rc == PF_OK; ++pc) {
     const Instr in = prog[pc];
     if (in.kind == INSTR_WAIT) {
@@ -658,7 +711,26 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
       wait_until(t_sched);
       continue;
     }
+    if (in.kind == INSTR_SYNC) {
+      hipck(hipStreamSynchronize(mstr), "main sync");
+      const int64_t t0 = now_ns();
+      if (offload && gone > 0 && rc == PF_OK) rc = pf::train_opt_state_copy(mc, 0, gone, mc->off.host, false, mc->off.stream);
+      wait_until(t0 + mc->off.sync_ns);
+      if (offload) {   // the optimizer update needs the state: whatever is still on its way holds the main job up
+        const int64_t t1 = now_ns();
+        hipck(hipStreamSynchronize(mc->off.stream), "offload sync");
+        stats->offload_wait_ns += now_ns() - t1;
+        stats->offloaded_bytes = gone;
+        gone = scrubbed = 0;
+      }
+      continue;
+    }
     if (in.kind != PF_INSTR_BUBBLE) {
+      if (mc && offload && in.kind == PF_INSTR_FWD && mc->off.slices[in.index] > 0 && rc == PF_OK) {
+        // this forward's slice of the optimizer state leaves on the copies' stream while the forward runs
+        rc = pf::train_opt_state_copy(mc, gone, mc->off.slices[in.index], mc->off.host, true, mc->off.stream);
+        gone += mc->off.slices[in.index];
+      }
       if (mc) {
         hipEvent_t a = nullptr, b = nullptr;
         hipck(hipEventCreate(&a), "event");
@@ -677,6 +749,15 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
     // the bubble opens when the stage has nothing left to run
     if (mc) {
       hipck(hipStreamSynchronize(mstr), "main sync");
+      if (offload) {   // copies still under way are waited for before the Executor is signalled
+        const int64_t t0 = now_ns();
+        hipck(hipStreamSynchronize(mc->off.stream), "offload sync");
+        stats->offload_wait_ns += now_ns() - t0;
+        if (mc->off.scrub && gone > scrubbed && rc == PF_OK) {
+          rc = pf::train_opt_state_fill(mc, scrubbed, gone - scrubbed, 0xff, mc->off.stream);
+          scrubbed = gone;
+        }
+      }
       t_sched = now_ns();
     }
     const int64_t deadline = t_sched + w.dur_ns;
@@ -794,7 +875,7 @@ int32_t pf_ctx_train_state(pf_ctx* c, double* loss, int64_t* steps) {
 }
 
 int32_t pf_ctx_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, void* stream) {
-  if (!c || !dst || (what != 0 && what != 1) || layer < -1)
+  if (!c || !dst || what < 0 || what > 3 || layer < -1)
     return pf::fail(PF_ERR_ARG, "pf_ctx_read_params: bad argument");
   if (!c->tr) return pf::fail(PF_ERR_STATE, "pf_ctx_read_params: not a training context");
   return pf::train_read_params(c, what, layer, dst, dst_bytes, (hipStream_t)stream);

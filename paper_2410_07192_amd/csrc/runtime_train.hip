@@ -420,17 +420,58 @@ int32_t train_main_step(pf_ctx* c, int32_t instr, int32_t index, const void* io,
   return PF_OK;
 }
 
+int64_t train_opt_state_bytes(const pf_ctx* c) { return c->md.n_layers * 2 * c->tr->blob32; }
+
+// Calls f(device address, offset in the string, length) for every contiguous piece of [off, off + len): a layer's
+// two moment arrays lie next to each other in the arena, different layers do not.
+template <class Fn>
+static int32_t for_opt_state_pieces(pf_ctx* c, int64_t off, int64_t len, Fn&& f) {
+  TrainState& t = *c->tr;
+  const int64_t per_layer = 2 * t.blob32;
+  if (off < 0 || len < 0 || off + len > train_opt_state_bytes(c)) return fail(PF_ERR_ARG, "optimizer state: range out of bounds");
+  while (len > 0) {
+    const int64_t l = off / per_layer, in_layer = off % per_layer;
+    const int64_t n = std::min(len, per_layer - in_layer);
+    if ((char*)t.v[l] != (char*)t.m[l] + t.blob32) return fail(PF_ERR_STATE, "optimizer state: moments are not adjacent");
+    int32_t rc = f((char*)t.m[l] + in_layer, off, n);
+    if (rc != PF_OK) return rc;
+    off += n;
+    len -= n;
+  }
+  return PF_OK;
+}
+
+int32_t train_opt_state_copy(pf_ctx* c, int64_t off, int64_t len, char* host, bool to_host, hipStream_t st) {
+  return for_opt_state_pieces(c, off, len, [&](char* dev, int64_t o, int64_t n) -> int32_t {
+    if (to_host) PF_HIP(hipMemcpyAsync(host + o, dev, (size_t)n, hipMemcpyDeviceToHost, st));
+    else PF_HIP(hipMemcpyAsync(dev, host + o, (size_t)n, hipMemcpyHostToDevice, st));
+    return PF_OK;
+  });
+}
+
+int32_t train_opt_state_fill(pf_ctx* c, int64_t off, int64_t len, int32_t byte, hipStream_t st) {
+  return for_opt_state_pieces(c, off, len, [&](char* dev, int64_t, int64_t n) -> int32_t {
+    PF_HIP(hipMemsetAsync(dev, byte, (size_t)n, st));
+    return PF_OK;
+  });
+}
+
+int32_t train_main_opt(pf_ctx* c, int32_t microbatches, hipStream_t st) {
+  c->tr->mb_accum = microbatches;
+  return optimizer_step(c, st);
+}
+
 int32_t train_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, hipStream_t st) {
   TrainState& t = *c->tr;
   const void* src;
   int64_t n;
   if (layer >= 0) {
     if (layer >= c->md.n_layers) return fail(PF_ERR_ARG, "pf_ctx_read_params: layer out of range");
-    src = what == 0 ? t.grad[layer] : t.master[layer];
+    src = what == 0 ? t.grad[layer] : what == 1 ? t.master[layer] : what == 2 ? t.m[layer] : t.v[layer];
     n = t.blob32;
   } else {
     if (!t.Vp) return fail(PF_ERR_STATE, "pf_ctx_read_params: the model has no embeddings");
-    src = what == 0 ? t.embg : t.embM;
+    src = what == 0 ? t.embg : what == 1 ? t.embM : what == 2 ? t.embm : t.embv;
     n = t.emb32;
   }
   if (dst_bytes < n) return fail(PF_ERR_CAPACITY, "pf_ctx_read_params: %lld bytes needed", (long long)n);

@@ -187,6 +187,158 @@ def test_main_stage_forward_backward(dtype, tol):
         m.close()
 
 
+def test_main_stage_optimizer_update():
+    """PF_INSTR_OPT of the emulated main stage: Adam on the mean of the accumulated microbatch gradients."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(2, 128, 2, 256, 64, 2, 0, True, "f32")
+    params = synth.make_model_params(shape, seed=43, std=0.08)
+    P = ot.cast_params(params)
+    m = dev.DeviceModel(shape, params, g=2, training=True, adam=pf.pf_adam(1e-3, 0.9, 0.999, 1e-8, 1))
+    try:
+        xs = [synth.make_hidden(shape, seed=160 + i) for i in range(2)]
+        dys = [synth.make_hidden(shape, seed=180 + i) for i in range(2)]
+        dxs = [dev.storage_tensor(x, m.md) for x in xs]
+        ddy = [dev.storage_tensor(x, m.md) for x in dys]
+        st = torch.cuda.Stream()
+        for j in range(2):
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, j, dxs[j].data_ptr(), st.cuda_stream)
+        for j in range(2):
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, j, ddy[j].data_ptr(), st.cuda_stream)
+        m.ctx.pf_main_stage_step(pf.PF_INSTR_OPT, 2, None, st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        Gsum = [None, None]
+        for j in range(2):
+            x = xs[j].astype(np.float64)
+            caches = []
+            for l in range(2):
+                x, c = ot.layer_forward(x, P["layers"][l], shape.n_heads, True, shape.eps, keep=True)
+                caches.append(c)
+            dx = dys[j].astype(np.float64)
+            for l in (1, 0):
+                dx, G = ot.layer_backward(dx, caches[l], P["layers"][l], shape.n_heads)
+                Gsum[l] = G if Gsum[l] is None else {k: Gsum[l][k] + G[k] for k in G}
+        for l in range(2):
+            got, m1, v1 = read_layer(m, 1, l), read_layer(m, 2, l), read_layer(m, 3, l)
+            for k in Gsum[l]:
+                gmean = 0.5 * Gsum[l][k]
+                th1, mo, vo = ot.adam_step(P["layers"][l][k], 0.0, 0.0, gmean, 1, lr=1e-3)
+                assert rel_err(m1[k], mo) < 1e-4 and rel_err(v1[k], vo) < 2e-4, (l, k)
+                big = np.abs(gmean) > 1e-3 * np.abs(gmean).max()
+                upd = got[k].astype(np.float64) - P["layers"][l][k]
+                assert np.abs(upd - (th1 - P["layers"][l][k]))[big].max() < 0.05 * 1e-3, (l, k)
+            assert not any(np.any(v) for v in read_layer(m, 0, l).values())      # accumulators cleared
+        _, steps = m.ctx.pf_ctx_train_state()
+        assert steps == 1
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_OPT, 0, None, st.cuda_stream)
+        assert e.value.code == pf.PF_ERR_ARG
+    finally:
+        m.close()
+
+
+def _moments(m, n_layers):
+    """The stage's optimizer state as the library strings it: per layer, first then second moments."""
+    pf, dev = _mods()
+    md32 = pf.pf_model_desc.from_buffer_copy(m.md)
+    md32.dtype = pf.PF_DTYPE_F32
+    size, _ = pf.pf_layer_blob_layout(md32)
+    out = []
+    for l in range(n_layers):
+        for what in (2, 3):
+            buf = torch.empty(size, dtype=torch.uint8, device="cuda")
+            m.ctx.pf_ctx_read_params(what, l, buf.data_ptr(), size)
+            m.ctx.pf_ctx_sync()
+            out.append(buf.cpu().numpy())
+    return np.concatenate(out)
+
+
+def test_main_stage_offload_round_trip():
+    """Optimizer-state offload of the emulated main stage: slices leave with the forwards, what has left is
+    overwritten on the device during the windows, everything is back for the optimizer update.  The bytes
+    that reach the host are exactly the state of the iteration before, and the training run is the same as
+    one without offload (up to the summation order of the gradient atomics)."""
+    import ctypes as C
+    pf, dev = _mods()
+    shape = synth.ModelShape(2, 128, 2, 256, 64, 2, 0, True, "bf16")
+    params = synth.make_model_params(shape, seed=47, std=0.08)
+    p, mm, stage, tf, tb = 4, 4, 1, 3_000_000, 6_000_000
+    windows = pf.pf_schedule_1f1b(p, mm, stage, tf, tb, 1 << 30, True, 0)
+    runs = {}
+    for mode in ("plain", "offload"):
+        m = dev.DeviceModel(shape, params, g=mm, training=True, adam=pf.pf_adam(1e-3, 0.9, 0.999, 1e-8, 1))
+        try:
+            io = dev.storage_tensor(synth.make_hidden(shape, seed=190), m.md)
+            S = m.ctx.pf_main_opt_state_bytes()
+            md32 = pf.pf_model_desc.from_buffer_copy(m.md)
+            md32.dtype = pf.PF_DTYPE_F32
+            assert S == 2 * 2 * pf.pf_layer_blob_layout(md32)[0]
+            host = torch.zeros(S, dtype=torch.uint8, pin_memory=True)
+            slices = []
+            if mode == "offload":
+                # 0.4 S per forward (so a slice straddles the two layers), everything may come back
+                per = int(0.4 * S) // 256 * 256
+                d2h = -(-per * 10**9 // tf)
+                slices, extra = pf.pf_offload_plan(p, mm, stage, tf, 10**9, S, d2h, 10**12)
+                assert slices[0] == slices[1] == per and sum(slices) == S // 256 * 256 and slices[3] == 0
+                assert extra == [sum(slices)] * 3 + [0]
+            m.ctx.pf_ctx_set_main_offload(2_000_000, host.data_ptr(), S, slices, scrub=True)
+            st, main = torch.cuda.Stream(), torch.cuda.Stream()
+            cursor = C.c_int32(0)
+            states, stats = [], []
+            for _ in range(3):
+                stats.append(pf.pf_timeline_run(None, m.ctx, io.data_ptr(), p, mm, stage, tf, tb, windows, None, 0, None,
+                                                cursor, st.cuda_stream, main.cuda_stream))
+                states.append(_moments(m, 2))
+                if mode == "offload" and len(states) >= 2:
+                    n = sum(slices)
+                    # what reached the host during this iteration is the state the iteration before left behind
+                    assert np.array_equal(host.numpy()[:n], states[-2][:n])
+            _, steps = m.ctx.pf_ctx_train_state()
+            assert steps == 3
+            assert all(s["offloaded_bytes"] == sum(slices) for s in stats)
+            assert all(s["iter_ns"] >= 2_000_000 for s in stats)
+            runs[mode] = (states, [read_layer(m, 1, l) for l in range(2)])
+        finally:
+            m.close()
+    a, b = runs["plain"], runs["offload"]
+    for it in range(3):
+        fa, fb = a[0][it].view(np.float32), b[0][it].view(np.float32)
+        assert np.isfinite(fb).all()
+        assert rel_err(fb, fa) < 1e-3, it
+    for l in range(2):
+        for k in a[1][l]:
+            assert np.isfinite(b[1][l][k]).all()
+            assert np.abs(b[1][l][k] - a[1][l][k]).max() < 2e-4, (l, k)      # three steps of at most lr = 1e-3 each
+
+
+def test_main_offload_argument_errors():
+    pf, dev = _mods()
+    shape = synth.ModelShape(1, 64, 2, 128, 64, 1, 0, True, "bf16")
+    m = dev.DeviceModel(shape, synth.make_model_params(shape, seed=5, std=0.05), training=True)
+    try:
+        S = m.ctx.pf_main_opt_state_bytes()
+        host = torch.zeros(S, dtype=torch.uint8, pin_memory=True)
+        for args, code in [((0, host.data_ptr(), S, [S + 256]), pf.PF_ERR_ARG), ((0, host.data_ptr(), S, [6]), pf.PF_ERR_ARG),
+                           ((0, host.data_ptr(), 100, [256]), pf.PF_ERR_CAPACITY), ((0, None, S, [256]), pf.PF_ERR_ARG),
+                           ((-1, host.data_ptr(), S, [256]), pf.PF_ERR_ARG)]:
+            with pytest.raises(pf.PipeFillError) as e:
+                m.ctx.pf_ctx_set_main_offload(*args)
+            assert e.value.code == code, args
+        # a slice count that does not match the timeline's m is refused by the timeline
+        import ctypes as C
+        m.ctx.pf_ctx_set_main_offload(0, host.data_ptr(), S, [256, 256])
+        io = dev.storage_tensor(synth.make_hidden(shape, seed=1), m.md)
+        st, main = torch.cuda.Stream(), torch.cuda.Stream()
+        windows = pf.pf_schedule_1f1b(2, 3, 0, 10**6, 10**6, 1 << 30, True, 0)
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_timeline_run(None, m.ctx, io.data_ptr(), 2, 3, 0, 10**6, 10**6, windows, None, 0, None, C.c_int32(0),
+                               st.cuda_stream, main.cuda_stream)
+        assert e.value.code == pf.PF_ERR_ARG
+        m.ctx.pf_ctx_set_main_offload(-1)          # phase off again
+    finally:
+        m.close()
+
+
 ATT_BWD = [("bf16", 2, 200, 3, 64), ("bf16", 1, 321, 2, 128), ("bf16", 2, 64, 2, 64), ("bf16", 1, 130, 2, 16),
            ("f32", 2, 100, 2, 32), ("f32", 1, 70, 1, 64)]
 
