@@ -417,18 +417,53 @@ def run_cfg5(args, np, torch, pf, dev, synth):
     shape3, models = make_cfg3_models(torch, pf, dev, synth, gs=(2,))
     fm = models[0]
     fm.ctx.pf_profile_chain(fm.chain, 1, 3, fill.cuda_stream)
-    windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, 8 * GIB, True, 2 * max(n.dur_ns for n in fm.chain))
+    cap = int(args.cap_gib * GIB)
+    windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, cap, True, 2 * max(n.dur_ns for n in fm.chain))
+    offload = None
+    if args.main_offload:
+        # measured copy rates (1 GiB, pinned host memory), planned at 85 % of them
+        hbuf = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+        dbuf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        rates = []
+        for dst, src in ((hbuf, dbuf), (dbuf, hbuf)):
+            ts = []
+            for _ in range(4):
+                ev[0].record(main_s)
+                with torch.cuda.stream(main_s):
+                    dst.copy_(src, non_blocking=True)
+                ev[1].record(main_s)
+                torch.cuda.synchronize()
+                ts.append(ev[0].elapsed_time(ev[1]))
+            rates.append(int((1 << 30) / (sorted(ts[1:])[1] * 1e-3)))
+        del hbuf, dbuf
+        d2h, h2d = (int(0.85 * r) for r in rates)
+        sync_ns = int(args.sync_ms * 1e6)
+        state = main.ctx.pf_main_opt_state_bytes()
+        slices, extra = pf.pf_offload_plan(p, m, stage, tf, sync_ns, state, d2h, h2d)
+        host = torch.empty(max(256, sum(slices)), dtype=torch.uint8, pin_memory=True)
+        offload = dict(state=state, slices=slices, extra=extra, host=host, sync_ns=sync_ns, rates=rates)
+        for w, e in zip(windows, extra):
+            w["free"] += e
     plan, n_plan, k = pf.pf_plan_bubbles(windows, fm.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
     cursor = C.c_int32(0)
     fm.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
+
+    def set_offload(on):
+        if offload:
+            main.ctx.pf_ctx_set_main_offload(offload["sync_ns"], host.data_ptr(), host.numel(),
+                                             offload["slices"] if on else [])
 
     def run_iter(with_fill):
         return pf.pf_timeline_run(fm.ctx if with_fill else None, main.ctx, x.data_ptr(), p, m, stage, tf, tb, windows,
                                   plan, n_plan, fm.chain, cursor, fill.cuda_stream, main_s.cuda_stream)
 
+    set_offload(True)
     for _ in range(args.warmup):
         run_iter(True)
+    set_offload(False)       # baseline: same iteration (with its optimizer phase), nothing offloaded, nothing filled
     base = [run_iter(False) for _ in range(args.steps)]
+    set_offload(True)
+    off_only = [run_iter(False) for _ in range(args.steps)] if offload else []
     torch.cuda.synchronize()
     agg = dict.fromkeys(AGG_KEYS, 0)
     t0 = time.perf_counter()
@@ -450,9 +485,19 @@ def run_cfg5(args, np, torch, pf, dev, synth):
         "config": {"workload": f"cfg5: main-job stage of 3 layers d=8192 h=64 ff=32768 seq=2048 microbatch=1 bf16 fwd+bwd "
                                f"(recomputing backward) on its own stream, emulated 1F1B p={p} m={m} stage {stage} with "
                                f"measured t_f={tf_ms:.1f} ms t_b={tb_ms:.1f} ms; fill = cfg3 job (streamed weights, g=2), "
-                               f"8 GiB cap",
+                               f"{args.cap_gib:g} GiB free" + (
+                                   f"; main job ends the iteration with a {args.sync_ms:g} ms gradient synchronisation and an "
+                                   f"Adam update, and offloads {sum(offload['slices']) / GIB:.2f} of its "
+                                   f"{offload['state'] / GIB:.2f} GiB of optimizer state" if offload else ""),
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns},
         **fill_stats(agg),
+        **({"main_offload": {
+            "d2h_gb_per_s": offload["rates"][0] * 1e-9, "h2d_gb_per_s": offload["rates"][1] * 1e-9,
+            "slice_mib": offload["slices"][0] / (1 << 20), "slices_used": sum(1 for c in offload["slices"] if c),
+            "extra_free_gib_per_window": sorted({round(e / GIB, 3) for e in offload["extra"]}),
+            "slowdown_pct_offload_alone": 100.0 * (sum(s_["iter_ns"] for s_ in off_only) / len(off_only) - t_base) / t_base,
+            "offload_wait_ms_per_iter": sum(s_["offload_wait_ns"] for s_ in filled) / len(filled) * 1e-6,
+            "offloaded_gib_per_iter": filled[-1]["offloaded_bytes"] / GIB}} if offload else {}),
         "main_slowdown_pct": 100.0 * (t_fill - t_base) / t_base,
         "main_iter_ms_without_fill": t_base * 1e-6, "main_iter_ms_with_fill": t_fill * 1e-6,
         "main_busy_ms_without_fill": mb_base * 1e-6, "main_busy_ms_with_fill": mb_fill * 1e-6,
@@ -479,7 +524,11 @@ def main():
     ap.add_argument("--cpu-seqs", type=int, default=4)
     ap.add_argument("--verbose", action="store_true", help="per-step statistics on stderr (cfg2)")
     ap.add_argument("--bubble-ms", type=float, default=40.0, help="cfg3: duration of the explicit bubbles")
-    ap.add_argument("--cap-gib", type=float, default=8.0, help="cfg3: free memory inside the bubbles")
+    ap.add_argument("--cap-gib", type=float, default=8.0, help="cfg3, cfg5: free memory inside the bubbles")
+    ap.add_argument("--main-offload", action="store_true",
+                    help="cfg5: the main stage ends each iteration with a gradient synchronisation and an optimizer "
+                         "update, and offloads optimizer state to pinned host memory around them")
+    ap.add_argument("--sync-ms", type=float, default=100.0, help="cfg5 --main-offload: gradient synchronisation time")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device-to-device copy 10 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
