@@ -443,6 +443,15 @@ int32_t pf_op_attention(int32_t dtype, const void* qkv, void* out, float* lse, i
 int32_t pf_op_attention_bwd(int32_t dtype, const void* qkv, const void* out, const void* dout, const float* lse,
                             float* dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
                             void* stream);
+/* Backward of pf_op_layernorm from the saved row statistics: dx = rstd * (g*dy - mean(g*dy) -
+ * xhat * mean(g*dy*xhat)) (+ resid, same shape, may be NULL), dg += sum over rows of dy*xhat,
+ * db += sum over rows of dy (dg, db: fp32 [d], accumulated into).  dx may alias resid or dy.
+ * partial: fp32 scratch of 512 * 2 * d elements.  d a multiple of 8, at most 8192. */
+int32_t pf_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
+                            const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
+                            int64_t rows, int32_t d, void* stream);
+/* out[c][r] = in[r][c] for in [rows][cols], out [cols][rows] (distinct buffers); rows <= 64 * 65535. */
+int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, void* stream);
 /* x[t] = tok[ids[t]] + pos[t mod S]; ids int32 [tokens]; ids outside [0,V) contribute zeros. */
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
                     int64_t tokens, int32_t S, int32_t d, int32_t V, void* stream);

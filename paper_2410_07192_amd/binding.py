@@ -27,7 +27,7 @@ EXPORTS = [
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
     "pf_ctx_set_replan", "pf_main_opt_state_bytes", "pf_ctx_set_main_offload", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
-    "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd",
+    "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd", "pf_op_layernorm_bwd", "pf_op_transpose",
 ]
 PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
 
@@ -140,6 +140,8 @@ def _load():
     lib.pf_op_layernorm.argtypes = [I32, VP, VP, VP, VP, VP, VP, I64, I32, C.c_float, VP]
     lib.pf_op_attention.argtypes = [I32, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_attention_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
+    lib.pf_op_layernorm_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, VP, VP, VP, VP, I64, I32, VP]
+    lib.pf_op_transpose.argtypes = [I32, VP, VP, I64, I64, VP]
     lib.pf_op_embed.argtypes = [I32, VP, VP, VP, VP, I64, I32, I32, I32, VP]
     return lib
 
@@ -517,6 +519,14 @@ def unpack_embedding_f32(md, raw):
                 pos_emb=raw[o1:o1 + S * d * 4].view(np.float32).reshape(S, d).copy(),
                 lnf_g=raw[o2:o2 + d * 4].view(np.float32).copy(),
                 lnf_b=raw[o3:o3 + d * 4].view(np.float32).copy()), total
+
+
+def pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream=None):
+    _check(lib.pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream))
+
+
+def pf_op_transpose(dtype, src, dst, rows, cols, stream=None):
+    _check(lib.pf_op_transpose(dtype, src, dst, rows, cols, stream))
 
 
 def pf_op_attention_bwd(dtype, qkv, out, dout, lse, dsum, dqkv, B, S, h, dh, causal, stream=None):

@@ -964,6 +964,23 @@ int32_t pf_op_attention_bwd(int32_t dtype, const void* qkv, const void* out, con
   return PF_OK;
 }
 
+int32_t pf_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
+                            const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
+                            int64_t rows, int32_t d, void* stream) {
+  if (bad_dtype(dtype) || !dy || !x || !g || !mean || !rstd || !dx || !dg || !db || !partial || rows <= 0 || d <= 0 ||
+      d % 8 != 0 || d > 8192)
+    return pf::fail(PF_ERR_ARG, "pf_op_layernorm_bwd: bad argument");
+  PF_HIP(pf::layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, (hipStream_t)stream));
+  return PF_OK;
+}
+
+int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, void* stream) {
+  if (bad_dtype(dtype) || !in || !out || in == out || rows <= 0 || cols <= 0 || (rows + 63) / 64 > 65535)
+    return pf::fail(PF_ERR_ARG, "pf_op_transpose: bad argument");
+  PF_HIP(pf::transpose2d(dtype, in, out, rows, cols, (hipStream_t)stream));
+  return PF_OK;
+}
+
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int64_t tokens,
                     int32_t S, int32_t d, int32_t V, void* stream) {
   if (bad_dtype(dtype) || !ids || !tok || !pos || !x || tokens <= 0 || S <= 0 || d <= 0 || d % 8 != 0 || V <= 0)

@@ -32,6 +32,39 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
   }
 }
 
+// bf16 with R and Cn multiples of 8 and 16-byte aligned pointers: 64x64 tiles, 16-byte global accesses on both
+// sides (a row of the tile is one 128-byte line), the transposition itself happens in LDS (dword writes,
+// 2-byte reads at a pitch of 33 dwords, which spreads the eight row groups a wave reads over distinct banks).
+__global__ __launch_bounds__(256) void transpose_bf16_vec_kernel(const uint16_t* __restrict__ in,
+                                                                 uint16_t* __restrict__ out, int64_t R, int64_t Cn) {
+  constexpr int PITCH = 66;   // elements
+  __shared__ uint32_t tile32[64 * PITCH / 2];
+  const uint16_t* tile = reinterpret_cast<const uint16_t*>(tile32);
+  const int t = threadIdx.x;
+  const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int q = t + k * 256, r = q >> 3, cc = (q & 7) * 8;
+    if (r0 + r < R && c0 + cc < Cn) {
+      const uint4 v = *reinterpret_cast<const uint4*>(in + (r0 + r) * Cn + c0 + cc);
+      uint32_t* dst = tile32 + (r * PITCH + cc) / 2;
+      dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int q = t + k * 256, c = q >> 3, rr = (q & 7) * 8;
+    if (c0 + c < Cn && r0 + rr < R) {
+      uint32_t w[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        w[j] = (uint32_t)tile[(rr + 2 * j) * PITCH + c] | ((uint32_t)tile[(rr + 2 * j + 1) * PITCH + c] << 16);
+      *reinterpret_cast<uint4*>(out + (c0 + c) * R + r0 + rr) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+  }
+}
+
 // ---- column sums: acc[n] += sum_t x[t][n] -----------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ x, float* __restrict__ acc, int64_t rows,
@@ -86,35 +119,63 @@ __global__ __launch_bounds__(256) void colsum_bf16_vec_kernel(const bf16_t* __re
 
 // ---- LayerNorm backward -----------------------------------------------------------------------------
 // dx = rstd * (g*dy - mean(g*dy) - xhat * mean(g*dy*xhat)) [+ resid];  dg += sum dy*xhat;  db += sum dy.
-// One wave per row, rows strided over the grid; per-lane partial dg/db live in registers, each wave
-// writes its partial row to `partial` ([waves][2][d]) and a second kernel sums the rows in a fixed
-// order (deterministic) into dg / db.
-template <typename T, int ITER>
-__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
-                                                            const T* __restrict__ g, const float* __restrict__ mean,
-                                                            const float* __restrict__ rstd, const T* resid, T* dx,
-                                                            float* __restrict__ partial, int64_t rows, int32_t d) {
-  const int lane = threadIdx.x & 63;
-  const int64_t wave0 = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int64_t nwaves = (int64_t)gridDim.x * 4;
-  float pg[ITER][8], pb[ITER][8], gg[ITER][8];
+// One workgroup of NW waves per row, rows strided over the grid; a thread keeps ITER groups of 8 columns
+// and its partial dg/db in registers; the next row's x and dy are fetched before this row's two sums are
+// reduced (wave shuffle, then through LDS across the waves: one barrier per row, the LDS slots alternate).
+// Each workgroup writes one partial row to `partial` ([workgroups][2][d]) and a second kernel sums the rows
+// in a fixed order (deterministic) into dg / db.
+template <typename T, int NW, int ITER>
+__global__ __launch_bounds__(64 * NW) void layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                                const T* __restrict__ g, const float* __restrict__ mean,
+                                                                const float* __restrict__ rstd, const T* resid, T* dx,
+                                                                float* __restrict__ partial, int64_t rows, int32_t d) {
+  __shared__ float red[2][NW][2];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  float pg[ITER][8], pb[ITER][8], gg[ITER][8], xn[ITER][8], dn[ITER][8];
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
-    const int c = (i * 64 + lane) * 8;
+    const int c = (i * 64 * NW + t) * 8;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) pg[i][j] = pb[i][j] = gg[i][j] = 0.f;
+    for (int j = 0; j < 8; ++j) pg[i][j] = pb[i][j] = gg[i][j] = xn[i][j] = dn[i][j] = 0.f;
     if (c < d) load8(g + c, gg[i]);
   }
-  for (int64_t row = wave0; row < rows; row += nwaves) {
+  auto fetch = [&](int64_t r) {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int c = (i * 64 * NW + t) * 8;
+      if (c < d) {
+        load8(x + r * d + c, xn[i]);
+        load8(dy + r * d + c, dn[i]);
+      }
+    }
+  };
+  int64_t row = blockIdx.x;
+  if (row < rows) fetch(row);
+  int par = 0;
+  for (; row < rows; row += gridDim.x) {
     const float mu = mean[row], rs = rstd[row];
-    float xh[ITER][8], dv[ITER][8];
+    float xh[ITER][8], dv[ITER][8], rr[ITER][8];
+#pragma unroll
+    for (int i = 0; i < ITER; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        xh[i][j] = xn[i][j];
+        dv[i][j] = dn[i][j];
+        rr[i][j] = 0.f;
+      }
+    if (row + gridDim.x < rows) fetch(row + gridDim.x);
+    if (resid) {
+#pragma unroll
+      for (int i = 0; i < ITER; ++i) {
+        const int c = (i * 64 * NW + t) * 8;
+        if (c < d) load8(resid + row * d + c, rr[i]);
+      }
+    }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int c = (i * 64 + lane) * 8;
+      const int c = (i * 64 * NW + t) * 8;
       if (c < d) {
-        load8(x + row * d + c, xh[i]);
-        load8(dy + row * d + c, dv[i]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           xh[i][j] = (xh[i][j] - mu) * rs;
@@ -126,29 +187,39 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict_
         }
       }
     }
-    s1 = wave_sum(s1) / (float)d;
-    s2 = wave_sum(s2) / (float)d;
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if constexpr (NW > 1) {
+      if (lane == 0) {
+        red[par][wv][0] = s1;
+        red[par][wv][1] = s2;
+      }
+      __syncthreads();
+      s1 = s2 = 0.f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        s1 += red[par][w][0];
+        s2 += red[par][w][1];
+      }
+      par ^= 1;
+    }
+    s1 /= (float)d;
+    s2 /= (float)d;
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int c = (i * 64 + lane) * 8;
+      const int c = (i * 64 * NW + t) * 8;
       if (c < d) {
         float o[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (dv[i][j] - s1 - xh[i][j] * s2) * rs;
-        if (resid) {
-          float r[8];
-          load8(resid + row * d + c, r);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) o[j] += r[j];
-        }
+        for (int j = 0; j < 8; ++j) o[j] = (dv[i][j] - s1 - xh[i][j] * s2) * rs + rr[i][j];
         store8(dx + row * d + c, o);
       }
     }
   }
-  float* pr = partial + wave0 * 2 * (int64_t)d;
+  float* pr = partial + (int64_t)blockIdx.x * 2 * (int64_t)d;
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
-    const int c = (i * 64 + lane) * 8;
+    const int c = (i * 64 * NW + t) * 8;
     if (c < d) {
       store8(pr + c, pg[i]);
       store8(pr + d + c, pb[i]);
@@ -492,6 +563,10 @@ hipError_t transpose2d(int32_t dtype, const void* in, void* out, int64_t R, int6
   if (R <= 0 || Cn <= 0) return hipErrorInvalidValue;
   const dim3 grid((unsigned)((Cn + 63) / 64), (unsigned)((R + 63) / 64));
   if (grid.y > 65535) return hipErrorInvalidValue;
+  if (dtype == PF_DTYPE_BF16_ && R % 8 == 0 && Cn % 8 == 0 && (((uintptr_t)in | (uintptr_t)out) & 15) == 0) {
+    hipLaunchKernelGGL(transpose_bf16_vec_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, R, Cn);
+    return hipGetLastError();
+  }
   PF_BY_DTYPE(dtype,
               hipLaunchKernelGGL(transpose_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)in, (bf16_t*)out, R, Cn),
               hipLaunchKernelGGL(transpose_kernel<float>, grid, dim3(256), 0, st, (const float*)in, (float*)out, R, Cn));
@@ -520,22 +595,21 @@ template <typename T>
 static hipError_t launch_ln_bwd(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
                                 const void* resid, void* dx, float* dg, float* db, float* partial, int64_t rows,
                                 int32_t d, hipStream_t st) {
-  int64_t blocks = (rows + 3) / 4;
-  if (blocks > LN_BWD_MAX_BLOCKS) blocks = LN_BWD_MAX_BLOCKS;
-  const dim3 grid((unsigned)blocks), block(256);
-  const int iters = (d + 511) / 512;
-#define PF_LNB(I)                                                                                              \
-  hipLaunchKernelGGL((layernorm_bwd_kernel<T, I>), grid, block, 0, st, (const T*)dy, (const T*)x, (const T*)g, \
+  int64_t blocks = rows;
+  if (blocks > LN_BWD_MAX_BLOCKS * 4) blocks = LN_BWD_MAX_BLOCKS * 4;   // rows of `partial`
+  const dim3 grid((unsigned)blocks);
+#define PF_LNB(NW, I)                                                                                                   \
+  hipLaunchKernelGGL((layernorm_bwd_kernel<T, NW, I>), grid, dim3(64 * NW), 0, st, (const T*)dy, (const T*)x, (const T*)g, \
                      mean, rstd, (const T*)resid, (T*)dx, partial, rows, d)
-  if (iters <= 1) PF_LNB(1);
-  else if (iters <= 2) PF_LNB(2);
-  else if (iters <= 4) PF_LNB(4);
-  else if (iters <= 8) PF_LNB(8);
-  else if (iters <= 16) PF_LNB(16);
+  if (d <= 512) PF_LNB(1, 1);
+  else if (d <= 1024) PF_LNB(2, 1);
+  else if (d <= 2048) PF_LNB(4, 1);
+  else if (d <= 4096) PF_LNB(4, 2);
+  else if (d <= 8192) PF_LNB(4, 4);
   else return hipErrorInvalidValue;
 #undef PF_LNB
   hipLaunchKernelGGL(reduce_rows_add_kernel, dim3((unsigned)((2 * d + 63) / 64)), dim3(1024), 0, st, partial, dg, db,
-                     (int32_t)(blocks * 4), d);
+                     (int32_t)blocks, d);
   return hipGetLastError();
 }
 

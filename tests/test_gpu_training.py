@@ -376,3 +376,75 @@ def test_attention_backward_kernel(dtype, B, S, h, dh, causal):
     tol = 2e-2 if dtype == "bf16" else 1e-4
     for i, ref in enumerate((dq, dk, dv)):
         assert rel_err(got[..., i * d:(i + 1) * d], ot.merge_heads(ref)) < tol, "qkv"[i]
+
+
+# d covers every workgroup shape of the kernel: 1 wave (<= 512), 2 waves (<= 1024), 4 waves with 1, 2 and 4
+# column groups per thread (<= 2048, <= 4096, <= 8192); rows cover fewer rows than workgroups, a ragged
+# multiple, and more rows than the 512 partial rows
+LN_BWD = [("f32", 5, 64), ("f32", 70, 520), ("bf16", 3, 256), ("bf16", 700, 768), ("bf16", 1500, 1024),
+          ("bf16", 130, 1536), ("bf16", 600, 2048), ("bf16", 90, 2560), ("bf16", 520, 4096), ("bf16", 33, 4104),
+          ("bf16", 64, 8192)]
+
+
+@pytest.mark.parametrize("with_resid", [False, True])
+@pytest.mark.parametrize("dtype,rows,d", LN_BWD)
+def test_layernorm_backward_kernel(dtype, rows, d, with_resid):
+    pf, dev = _mods()
+    md = pf.pf_model_desc()
+    md.dtype = pf.PF_DTYPE_BF16 if dtype == "bf16" else pf.PF_DTYPE_F32
+    rng = np.random.default_rng(rows * 31 + d)
+    rnd = lambda *s: (synth.round_to_bf16(rng.standard_normal(s).astype(np.float32)) if dtype == "bf16"
+                      else rng.standard_normal(s).astype(np.float32))
+    x, dy, res = rnd(rows, d) * 1.5 + 0.3, rnd(rows, d), rnd(rows, d)
+    if dtype == "bf16":
+        x = synth.round_to_bf16(x.astype(np.float32))
+    g = (1.0 + 0.1 * rnd(d)).astype(np.float32)
+    if dtype == "bf16":
+        g = synth.round_to_bf16(g)
+    b = np.zeros(d, np.float32)
+    dx_, ddy, dg_, dres = (dev.storage_tensor(a, md) for a in (x, dy, g, res))
+    db_ = dev.storage_tensor(b, md)
+    y = dev.empty_storage((rows, d), md)
+    mean = torch.empty(rows, dtype=torch.float32, device="cuda")
+    rstd = torch.empty(rows, dtype=torch.float32, device="cuda")
+    pf.pf_op_layernorm(md.dtype, dx_.data_ptr(), dg_.data_ptr(), db_.data_ptr(), y.data_ptr(), rows, d, 1e-5,
+                       mean.data_ptr(), rstd.data_ptr())
+    dxo = dev.empty_storage((rows, d), md)
+    # dg / db are accumulated into: start from a known value
+    acc_g = torch.full((d,), 2.0, dtype=torch.float32, device="cuda")
+    acc_b = torch.full((d,), -1.0, dtype=torch.float32, device="cuda")
+    partial = torch.empty(512 * 2 * d, dtype=torch.float32, device="cuda")
+    pf.pf_op_layernorm_bwd(md.dtype, ddy.data_ptr(), dx_.data_ptr(), dg_.data_ptr(), mean.data_ptr(), rstd.data_ptr(),
+                           dres.data_ptr() if with_resid else None, dxo.data_ptr(), acc_g.data_ptr(), acc_b.data_ptr(),
+                           partial.data_ptr(), rows, d)
+    torch.cuda.synchronize()
+    x64 = x.astype(np.float64)
+    _, xhat, rs = ot.layer_norm(x64, g.astype(np.float64), b.astype(np.float64), 1e-5)
+    dx_ref, dg_ref, db_ref = ot.layer_norm_backward(dy.astype(np.float64), xhat, rs, g.astype(np.float64))
+    if with_resid:
+        dx_ref = dx_ref + res
+    tol = 2e-2 if dtype == "bf16" else 1e-4
+    assert rel_err(dev.read_storage(dxo, md), dx_ref) < tol
+    assert rel_err(acc_g.cpu().numpy() - 2.0, dg_ref) < (1e-3 if dtype == "bf16" else 1e-4)
+    assert rel_err(acc_b.cpu().numpy() + 1.0, db_ref) < (1e-3 if dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("dtype,R,Cn", [("bf16", 64, 64), ("bf16", 200, 136), ("bf16", 8, 8), ("bf16", 1000, 3072),
+                                         ("bf16", 37, 50), ("bf16", 129, 72), ("f32", 100, 36), ("f32", 64, 200)])
+def test_transpose_kernel(dtype, R, Cn):
+    """Byte work: exact.  Shapes with both sides a multiple of 8 take the vectorised kernel (tiles inside, on the
+    edge and ragged in both directions), the others the element-wise one."""
+    pf, dev = _mods()
+    rng = np.random.default_rng(R * 13 + Cn)
+    if dtype == "bf16":
+        a = rng.integers(0, 1 << 16, size=(R, Cn), dtype=np.uint16)
+        code = pf.PF_DTYPE_BF16
+    else:
+        a = rng.standard_normal((R, Cn)).astype(np.float32)
+        code = pf.PF_DTYPE_F32
+    src = dev.to_device(a)
+    dst = torch.zeros((Cn, R), dtype=src.dtype, device="cuda")
+    pf.pf_op_transpose(code, src.data_ptr(), dst.data_ptr(), R, Cn)
+    torch.cuda.synchronize()
+    got = dst.cpu().numpy()
+    assert np.array_equal(got.view(a.dtype) if got.dtype != a.dtype else got, a.T)
