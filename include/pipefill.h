@@ -450,8 +450,11 @@ int32_t pf_op_attention_bwd(int32_t dtype, const void* qkv, const void* out, con
 int32_t pf_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
                             const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
                             int64_t rows, int32_t d, void* stream);
-/* out[c][r] = in[r][c] for in [rows][cols], out [cols][rows] (distinct buffers); rows <= 64 * 65535. */
-int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, void* stream);
+/* out[c][r] = in[r][c] for in [rows][cols], out [cols][rows] (distinct buffers); rows <= 64 * 65535.
+ * colsum_acc (device fp32 [cols], may be NULL): colsum_acc[c] += sum over r of in[r][c] (fp32 atomics:
+ * the order of the additions, and with it the last bits, can differ between calls). */
+int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, float* colsum_acc,
+                        void* stream);
 /* x[t] = tok[ids[t]] + pos[t mod S]; ids int32 [tokens]; ids outside [0,V) contribute zeros. */
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
                     int64_t tokens, int32_t S, int32_t d, int32_t V, void* stream);

@@ -141,7 +141,7 @@ def _load():
     lib.pf_op_attention.argtypes = [I32, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_attention_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_layernorm_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, VP, VP, VP, VP, I64, I32, VP]
-    lib.pf_op_transpose.argtypes = [I32, VP, VP, I64, I64, VP]
+    lib.pf_op_transpose.argtypes = [I32, VP, VP, I64, I64, VP, VP]
     lib.pf_op_embed.argtypes = [I32, VP, VP, VP, VP, I64, I32, I32, I32, VP]
     return lib
 
@@ -525,8 +525,8 @@ def pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial,
     _check(lib.pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream))
 
 
-def pf_op_transpose(dtype, src, dst, rows, cols, stream=None):
-    _check(lib.pf_op_transpose(dtype, src, dst, rows, cols, stream))
+def pf_op_transpose(dtype, src, dst, rows, cols, colsum_acc=None, stream=None):
+    _check(lib.pf_op_transpose(dtype, src, dst, rows, cols, colsum_acc, stream))
 
 
 def pf_op_attention_bwd(dtype, qkv, out, dout, lse, dsum, dqkv, B, S, h, dh, causal, stream=None):

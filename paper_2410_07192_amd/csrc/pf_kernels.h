@@ -46,6 +46,9 @@ hipError_t embed_fwd(int32_t dtype, const int32_t* ids, const void* tok, const v
 hipError_t transpose2d(int32_t dtype, const void* in, void* out, int64_t R, int64_t C, hipStream_t stream);
 // acc[n] += sum over rows of x[row][n]   (fp32 atomics)
 hipError_t colsum_add(int32_t dtype, const void* x, float* acc, int64_t rows, int64_t N, hipStream_t stream);
+// both at once: out[c][r] = in[r][c] and acc[c] += sum over r of in[r][c]
+hipError_t transpose2d_colsum(int32_t dtype, const void* in, void* out, float* acc, int64_t R, int64_t C,
+                              hipStream_t stream);
 // LayerNorm backward: dx = LN'(dy) (+ resid), dg += sum dy*xhat, db += sum dy.  dx may alias resid or dy.
 // partial: fp32 scratch of LN_BWD_MAX_BLOCKS * 4 * 2 * d elements.
 constexpr int64_t LN_BWD_MAX_BLOCKS = 128;

@@ -974,10 +974,12 @@ int32_t pf_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const 
   return PF_OK;
 }
 
-int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, void* stream) {
+int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, float* colsum_acc,
+                        void* stream) {
   if (bad_dtype(dtype) || !in || !out || in == out || rows <= 0 || cols <= 0 || (rows + 63) / 64 > 65535)
     return pf::fail(PF_ERR_ARG, "pf_op_transpose: bad argument");
-  PF_HIP(pf::transpose2d(dtype, in, out, rows, cols, (hipStream_t)stream));
+  if (colsum_acc) PF_HIP(pf::transpose2d_colsum(dtype, in, out, colsum_acc, rows, cols, (hipStream_t)stream));
+  else PF_HIP(pf::transpose2d(dtype, in, out, rows, cols, (hipStream_t)stream));
   return PF_OK;
 }
 

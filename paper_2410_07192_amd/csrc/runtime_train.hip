@@ -252,32 +252,28 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
   GemmEpilogue b1;
   b1.dact_in = t.u;
   PF_HIP(gemm_nt(dt, G, wt + t.wt_off[3], t.d_mid, T, f, d, b1, st));            // du = (dy W_2) * gelu'(u)
-  PF_HIP(transpose2d(dt, G, t.tA, T, d, st));                                    // dy^T  [d][T]
+  PF_HIP(transpose2d_colsum(dt, G, t.tA, G32(11), T, d, st));                    // dy^T  [d][T], db_2
   PF_HIP(transpose2d(dt, c->ws_mid, t.tB, T, f, st));                            // gelu(u)^T [f][T]
   GemmEpilogue acc;
   acc.out_f32 = 1;
   acc.accumulate = 1;
   PF_HIP(gemm_nt(dt, t.tA, t.tB, G32(10), d, f, T, acc, st));                    // dW_2 [d][f]
-  PF_HIP(colsum_add(dt, G, G32(11), T, d, st));                                  // db_2
-  PF_HIP(transpose2d(dt, t.d_mid, t.tB, T, f, st));                              // du^T [f][T]
+  PF_HIP(transpose2d_colsum(dt, t.d_mid, t.tB, G32(9), T, f, st));               // du^T [f][T], db_1
   PF_HIP(transpose2d(dt, t.ln2, t.tA, T, d, st));                                // bb^T [d][T]
   PF_HIP(gemm_nt(dt, t.tB, t.tA, G32(8), f, d, T, acc, st));                     // dW_1 [f][d]
-  PF_HIP(colsum_add(dt, t.d_mid, G32(9), T, f, st));                             // db_1
   GemmEpilogue none;
   PF_HIP(gemm_nt(dt, t.d_mid, wt + t.wt_off[2], t.d_ln, T, d, f, none, st));     // dbb = du W_1
   PF_HIP(layernorm_bwd(dt, t.d_ln, t.x1, wb + o[6], mean2, rstd2, G, G, G32(6), G32(7), t.ln_partial, T, d, st));
   // G now holds dx1.   x1 = x + c W_o + b_o
-  PF_HIP(transpose2d(dt, G, t.tA, T, d, st));                                    // dx1^T
+  PF_HIP(transpose2d_colsum(dt, G, t.tA, G32(5), T, d, st));                     // dx1^T, db_o
   PF_HIP(transpose2d(dt, c->ws_attn, t.tB, T, d, st));                           // c^T
   PF_HIP(gemm_nt(dt, t.tA, t.tB, G32(4), d, d, T, acc, st));                     // dW_o [d][d]
-  PF_HIP(colsum_add(dt, G, G32(5), T, d, st));                                   // db_o
   PF_HIP(gemm_nt(dt, G, wt + t.wt_off[1], t.d_attn, T, d, d, none, st));         // dc = dx1 W_o
   PF_HIP(attention_bwd(dt, c->ws_qkv, c->ws_attn, t.d_attn, t.lse, t.Dsum, t.d_qkv, m.batch, m.seq_len, m.n_heads, dh,
                        m.causal, st));
-  PF_HIP(transpose2d(dt, t.d_qkv, t.tA, T, 3 * d, st));                          // dqkv^T [3d][T]
+  PF_HIP(transpose2d_colsum(dt, t.d_qkv, t.tA, G32(3), T, 3 * d, st));           // dqkv^T [3d][T], db_qkv
   PF_HIP(transpose2d(dt, c->ws_ln, t.tB, T, d, st));                             // a^T [d][T]
   PF_HIP(gemm_nt(dt, t.tA, t.tB, G32(2), 3 * d, d, T, acc, st));                 // dW_qkv [3d][d]
-  PF_HIP(colsum_add(dt, t.d_qkv, G32(3), T, 3 * d, st));                         // db_qkv
   PF_HIP(gemm_nt(dt, t.d_qkv, wt + t.wt_off[0], t.d_ln, T, d, 3 * d, none, st)); // da = dqkv W_qkv
   PF_HIP(layernorm_bwd(dt, t.d_ln, x, wb + o[0], mean1, rstd1, G, G, G32(0), G32(1), t.ln_partial, T, d, st));
   return PF_OK;

@@ -35,8 +35,12 @@ __global__ __launch_bounds__(256) void transpose_kernel(const T* __restrict__ in
 // bf16 with R and Cn multiples of 8 and 16-byte aligned pointers: 64x64 tiles, 16-byte global accesses on both
 // sides (a row of the tile is one 128-byte line), the transposition itself happens in LDS (dword writes,
 // 2-byte reads at a pitch of 33 dwords, which spreads the eight row groups a wave reads over distinct banks).
+// COLSUM: acc[c] += sum over r of in[r][c] on the way (fp32 atomics, one per column and 64-row tile): the
+// bias gradient of a linear layer is the column sum of the very tensor whose transpose feeds its weight gradient.
+template <bool COLSUM>
 __global__ __launch_bounds__(256) void transpose_bf16_vec_kernel(const uint16_t* __restrict__ in,
-                                                                 uint16_t* __restrict__ out, int64_t R, int64_t Cn) {
+                                                                 uint16_t* __restrict__ out, int64_t R, int64_t Cn,
+                                                                 float* __restrict__ acc) {
   constexpr int PITCH = 66;   // elements
   __shared__ uint32_t tile32[64 * PITCH / 2];
   const uint16_t* tile = reinterpret_cast<const uint16_t*>(tile32);
@@ -55,12 +59,21 @@ __global__ __launch_bounds__(256) void transpose_bf16_vec_kernel(const uint16_t*
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
     const int q = t + k * 256, c = q >> 3, rr = (q & 7) * 8;
+    float sum = 0.f;
     if (c0 + c < Cn && r0 + rr < R) {
       uint32_t w[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
+      for (int j = 0; j < 4; ++j) {
         w[j] = (uint32_t)tile[(rr + 2 * j) * PITCH + c] | ((uint32_t)tile[(rr + 2 * j + 1) * PITCH + c] << 16);
+        if constexpr (COLSUM) sum += __uint_as_float(w[j] << 16) + __uint_as_float(w[j] & 0xffff0000u);
+      }
       *reinterpret_cast<uint4*>(out + (c0 + c) * R + r0 + rr) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    if constexpr (COLSUM) {   // the eight lanes that share column c hold its eight row groups
+      sum += __shfl_xor(sum, 1, 64);
+      sum += __shfl_xor(sum, 2, 64);
+      sum += __shfl_xor(sum, 4, 64);
+      if ((t & 7) == 0 && c0 + c < Cn) unsafeAtomicAdd(acc + c0 + c, sum);
     }
   }
 }
@@ -564,7 +577,8 @@ hipError_t transpose2d(int32_t dtype, const void* in, void* out, int64_t R, int6
   const dim3 grid((unsigned)((Cn + 63) / 64), (unsigned)((R + 63) / 64));
   if (grid.y > 65535) return hipErrorInvalidValue;
   if (dtype == PF_DTYPE_BF16_ && R % 8 == 0 && Cn % 8 == 0 && (((uintptr_t)in | (uintptr_t)out) & 15) == 0) {
-    hipLaunchKernelGGL(transpose_bf16_vec_kernel, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, R, Cn);
+    hipLaunchKernelGGL(transpose_bf16_vec_kernel<false>, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, R,
+                       Cn, (float*)nullptr);
     return hipGetLastError();
   }
   PF_BY_DTYPE(dtype,
@@ -589,6 +603,20 @@ hipError_t colsum_add(int32_t dtype, const void* x, float* acc, int64_t rows, in
               hipLaunchKernelGGL(colsum_kernel<bf16_t>, grid, dim3(256), 0, st, (const bf16_t*)x, acc, rows, N, rpb),
               hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, st, (const float*)x, acc, rows, N, rpb));
   return hipGetLastError();
+}
+
+hipError_t transpose2d_colsum(int32_t dtype, const void* in, void* out, float* acc, int64_t R, int64_t Cn,
+                              hipStream_t st) {
+  if (R <= 0 || Cn <= 0 || !acc) return hipErrorInvalidValue;
+  if (dtype == PF_DTYPE_BF16_ && R % 8 == 0 && Cn % 8 == 0 && (((uintptr_t)in | (uintptr_t)out) & 15) == 0) {
+    const dim3 grid((unsigned)((Cn + 63) / 64), (unsigned)((R + 63) / 64));
+    if (grid.y > 65535) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(transpose_bf16_vec_kernel<true>, grid, dim3(256), 0, st, (const uint16_t*)in, (uint16_t*)out, R, Cn,
+                       acc);
+    return hipGetLastError();
+  }
+  hipError_t e = transpose2d(dtype, in, out, R, Cn, st);
+  return e != hipSuccess ? e : colsum_add(dtype, in, acc, R, Cn, st);
 }
 
 template <typename T>

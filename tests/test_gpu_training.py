@@ -433,18 +433,28 @@ def test_layernorm_backward_kernel(dtype, rows, d, with_resid):
                                          ("bf16", 37, 50), ("bf16", 129, 72), ("f32", 100, 36), ("f32", 64, 200)])
 def test_transpose_kernel(dtype, R, Cn):
     """Byte work: exact.  Shapes with both sides a multiple of 8 take the vectorised kernel (tiles inside, on the
-    edge and ragged in both directions), the others the element-wise one."""
+    edge and ragged in both directions), the others the element-wise one.  With an accumulator the column sums
+    come along (fp32 atomics: compared within fp32 rounding of a sum of R terms)."""
     pf, dev = _mods()
     rng = np.random.default_rng(R * 13 + Cn)
     if dtype == "bf16":
-        a = rng.integers(0, 1 << 16, size=(R, Cn), dtype=np.uint16)
+        vals = synth.round_to_bf16(rng.standard_normal((R, Cn)).astype(np.float32))
+        a = (vals.view(np.uint32) >> 16).astype(np.uint16)
         code = pf.PF_DTYPE_BF16
     else:
-        a = rng.standard_normal((R, Cn)).astype(np.float32)
+        vals = a = rng.standard_normal((R, Cn)).astype(np.float32)
         code = pf.PF_DTYPE_F32
     src = dev.to_device(a)
-    dst = torch.zeros((Cn, R), dtype=src.dtype, device="cuda")
-    pf.pf_op_transpose(code, src.data_ptr(), dst.data_ptr(), R, Cn)
-    torch.cuda.synchronize()
-    got = dst.cpu().numpy()
-    assert np.array_equal(got.view(a.dtype) if got.dtype != a.dtype else got, a.T)
+    for with_sum in (False, True):
+        dst = torch.zeros((Cn, R), dtype=src.dtype, device="cuda")
+        acc = torch.full((Cn,), 3.0, dtype=torch.float32, device="cuda")
+        pf.pf_op_transpose(code, src.data_ptr(), dst.data_ptr(), R, Cn, acc.data_ptr() if with_sum else None)
+        torch.cuda.synchronize()
+        got = dst.cpu().numpy()
+        assert np.array_equal(got.view(a.dtype) if got.dtype != a.dtype else got, a.T)
+        if with_sum:
+            ref = vals.astype(np.float64).sum(axis=0)
+            scale = np.abs(vals.astype(np.float64)).sum(axis=0).max()
+            assert np.abs(acc.cpu().numpy() - 3.0 - ref).max() < 1e-6 * scale + 1e-6
+        else:
+            assert bool((acc == 3.0).all())
