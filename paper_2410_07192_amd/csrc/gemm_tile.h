@@ -449,7 +449,10 @@ hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, 
 // of the last round with 256-wide ones, and a 8192 x 1024 result gives every CU work only with the small tile.
 // Accumulating fp32 launches (weight gradients: small M x N, K = all tokens) may split K over up to 8 workgroups
 // per 128x128 tile while that fills idle CUs and leaves each >= 8 K steps; the slices add into C with fp32 atomics
-// (order-dependent in the last bits, like the other atomic reductions over tokens).
+// (order-dependent in the last bits, like the other atomic reductions over tokens).  Those atomics go at about
+// 1.5 TB/s on MI355X, far below plain stores, so the estimate charges every slice for its tile: two slices usually
+// pay, eight rarely do.  (256-wide tiles with split K were measured too: their atomic bursts at the end of the one
+// round are not hidden by anything and they lose to the small tile on every weight-gradient shape tried.)
 template <typename OutT, int EPI>
 hipError_t launch_fast(const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K, const EpiDev& ep,
                        hipStream_t stream) {
@@ -461,20 +464,27 @@ hipError_t launch_fast(const void* X, const void* W, void* C, int64_t M, int64_t
   for (int i = 0; i < 3; ++i) {
     const Shape& sh = shapes[i];
     const int64_t tiles = ((M + sh.bm - 1) / sh.bm) * ((N + sh.bn - 1) / sh.bn);
-    int splits = 1;
-    if constexpr (std::is_same<OutT, float>::value && EPI == E_ACC) {
-      if (i == 2)
-        while (splits < 8 && tiles * splits * 2 <= sh.resident && K % (128 * splits) == 0 && K / (128 * splits) >= 8)
-          splits *= 2;
-    }
-    const int64_t rounds = (tiles * splits + sh.resident - 1) / sh.resident;
-    const int64_t steps = K / (64 * splits) + 4;
-    int64_t cost = rounds * steps * (sh.resident / 256) * sh.bm * sh.bn * sh.eff100;
-    if (N % sh.bn) cost += cost * 3 / 10;
-    if (best_cost < 0 || cost < best_cost) {
-      best_cost = cost;
-      best = i;
-      best_splits = splits;
+    int max_splits = 1;
+    if constexpr (std::is_same<OutT, float>::value && EPI == E_ACC) max_splits = (i == 2) ? 8 : 1;
+    for (int splits = 1; splits <= max_splits; splits *= 2) {
+      // a slice keeps >= 8 K steps, and splitting only fills CUs that would otherwise idle
+      if (splits > 1 && (K % (128 * splits) != 0 || K / (128 * splits) < 8 || tiles * splits > sh.resident)) break;
+      const int64_t wgs = tiles * splits;
+      const int64_t rounds = (wgs + sh.resident - 1) / sh.resident;
+      const int64_t steps = K / (64 * splits) + 4;
+      // area in flight per CU x relative cost: a 128x128 workgroup that has its CU to itself runs 1.4x as fast as
+      // one of a pair, not twice
+      int64_t per_step = (int64_t)(sh.resident / 256) * sh.bm * sh.bn * sh.eff100;
+      if (i == 2 && wgs <= 256) per_step = (int64_t)sh.bm * sh.bn * 165;
+      int64_t cost = rounds * steps * per_step;
+      if (N % sh.bn) cost += cost * 3 / 10;
+      // every slice adds its whole fp32 tile with atomics: about 0.67 us per MiB, in the units of this estimate
+      if (splits > 1) cost += M * N * splits * 10;
+      if (best_cost < 0 || cost < best_cost) {
+        best_cost = cost;
+        best = i;
+        best_splits = splits;
+      }
     }
   }
   if (best == 0)
