@@ -1,8 +1,9 @@
 """One-GPU sweeps over the Executor's knobs, the analogues of the paper's sensitivity studies: main-job
 slowdown and fill throughput against the fraction of each bubble the Executor tries to fill (Sec. 6.1,
-Fig. 5), fill throughput against the bubble size and against the free memory (Sec. 6.4, Fig. 10).
+Fig. 5), fill throughput against the bubble size and against the free memory (Sec. 6.4, Fig. 10), and
+the main job's optimizer-state offload (Sec. 4.2) against the time its gradient synchronisation takes.
 
-    python -m paper_2410_07192_amd.sweeps [--which fill,bubble,memory] > sweeps.jsonl
+    python -m paper_2410_07192_amd.sweeps [--which fill,bubble,memory,offload] > sweeps.jsonl
 
 Every point is one run of bench.py (a child process, so each point starts from a fresh context); one JSON
 object per point on stdout: the sweep's name, the knob's value and the fields of bench.py's line that the
@@ -30,12 +31,14 @@ def run_point(name, knob, value, extra):
         line = json.loads(out.stdout.strip().splitlines()[-1])
         rec.update({k: line.get(k) for k in KEEP})
         rec["microbatches_per_layer_visit"] = line.get("config", {}).get("microbatches_per_layer_visit")
+        if "main_offload" in line:
+            rec["main_offload"] = line["main_offload"]
     print(json.dumps(rec), flush=True)
 
 
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--which", default="fill,bubble,memory")
+    ap.add_argument("--which", default="fill,bubble,memory,offload")
     args = ap.parse_args()
     which = set(args.which.split(","))
     if "fill" in which:      # real main-stage kernels (cfg5) with the streamed fill job inside its bubbles
@@ -48,6 +51,10 @@ def main():
     if "memory" in which:    # the same job with less and less free memory
         for gib in (1, 2, 3, 4, 6, 8):
             run_point("free_memory", "cap_gib", gib, ["--workload", "cfg3", "--cap-gib", str(gib), "--steps", "20"])
+    if "offload" in which:   # cfg5 with 1 GiB free: the fill job only fits the windows that the offload enlarges
+        for ms in (10, 25, 50, 100, 200, 400):
+            run_point("main_offload", "sync_ms", ms, ["--workload", "cfg5", "--main-offload", "--cap-gib", "1", "--sync-ms",
+                                                       str(ms), "--steps", "2", "--warmup", "1"])
 
 
 if __name__ == "__main__":
