@@ -685,7 +685,6 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   std::memset(stats, 0, sizeof *stats);
   struct Rec { hipEvent_t fs0, fs1, dead; bool used; };
   std::vector<Rec> recs(nW, Rec{nullptr, nullptr, nullptr, false});
-  hipEvent_t mb0 = nullptr, mb1 = nullptr;
   hipStream_t tstream = nullptr;   // idle stream: an event recorded on it is stamped "now"
   int32_t rc = PF_OK;
   auto hipck = [&](hipError_t e, const char* what) {
@@ -843,7 +842,6 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
     if (pr.first) (void)hipEventDestroy(pr.first);
     if (pr.second) (void)hipEventDestroy(pr.second);
   }
-  (void)mb0; (void)mb1;
   if (tstream) (void)hipStreamDestroy(tstream);
   return rc;
 }
