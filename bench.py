@@ -86,6 +86,9 @@ def stage_stepper(pf, model, stages, args, p, m, tf, tb, fill, main_s):
             state["stage"] = s
             state["cursor"] = C.c_int32(0)
             model.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
+        if st.get("explicit"):     # windows with their own start times (GPipe): the library's explicit cycle
+            return pf.pf_timeline_run(model.ctx, None, None, 0, 0, 0, 0, 0, st["windows"], st["plan"], st["n_plan"],
+                                      model.chain, state["cursor"], fill.cuda_stream, main_s.cuda_stream)
         return pf.pf_timeline_run(model.ctx, None, None, p, m, st["stage"], tf, tb, st["windows"], st["plan"],
                                   st["n_plan"], model.chain, state["cursor"], fill.cuda_stream, main_s.cuda_stream)
 
@@ -176,11 +179,15 @@ def run_cfg2(args, np, torch, pf, dev, synth):
     chain_ns = sum(n.dur_ns for n in model.chain)
     stages, t_plan = [], 0.0
     for s in range(p):
-        windows = pf.pf_schedule_1f1b(p, m, s, tf, tb, free, not args.paper_mode, 2 * max(n.dur_ns for n in model.chain))
+        if args.schedule == "gpipe":
+            windows = pf.pf_schedule_gpipe(p, m, s, tf, tb, free)
+        else:
+            windows = pf.pf_schedule_1f1b(p, m, s, tf, tb, free, not args.paper_mode, 2 * max(n.dur_ns for n in model.chain))
         t0 = time.perf_counter()
         plan, n_plan, k = pf.pf_plan_bubbles(windows, model.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
         t_plan += time.perf_counter() - t0
-        stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, cursor=C.c_int32(0)))
+        stages.append(dict(stage=s, windows=windows, plan=plan, n_plan=n_plan, cursor=C.c_int32(0),
+                           explicit=args.schedule == "gpipe"))
 
     run_step = stage_stepper(pf, model, stages, args, p, m, tf, tb, fill, main_s)
 
@@ -215,7 +222,8 @@ def run_cfg2(args, np, torch, pf, dev, synth):
     kernels["gemm_ffn1"] = dominant["gemm_ffn1"]
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": f"{name}: 12-layer bf16 encoder inference fill job d=768 h=12 ff=3072 seq=512 "
-                               f"batch=32, weights resident, 1F1B p={p} m={m} t_f=15ms t_b=30ms, 24 GiB free, "
+                               f"batch=32, weights resident, {'GPipe' if args.schedule == 'gpipe' else '1F1B'} p={p} m={m} "
+                               f"t_f=15ms t_b=30ms, 24 GiB free, "
                                f"all {p} stages, {max(1, args.steps // p)} consecutive iteration(s) each",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
                    "windows": "contiguous only" if args.paper_mode else "all idle windows"},
@@ -519,6 +527,8 @@ def main():
     ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
     ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
     ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles (cfg2)")
+    ap.add_argument("--schedule", default="1f1b", choices=["1f1b", "gpipe"],
+                    help="cfg2: main-job schedule whose idle windows are filled (Sec. 4.5; GPipe has two contiguous windows per stage)")
     ap.add_argument("--stage", type=int, default=7, help="pipeline stage emulated by cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=4)
