@@ -455,6 +455,14 @@ int32_t pf_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const 
  * the order of the additions, and with it the last bits, can differ between calls). */
 int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, int64_t cols, float* colsum_acc,
                         void* stream);
+/* C[M][N] (device fp32, accumulated into) += A^T B for A [K][M] and B [K][N], row-major bf16: the weight
+ * gradient dW = dY^T X of a linear layer from dY [tokens][n_out] and X [tokens][n_in] as they lie in memory.
+ * colsum_acc (device fp32 [M], may be NULL): colsum_acc[m] += sum over k of A[k][m] (the bias gradient).
+ * dtype must be PF_DTYPE_BF16, M and N multiples of 8, K a multiple of 64, A and B 16-byte aligned
+ * (PF_ERR_ARG otherwise).  K may be split over workgroups that add into C with fp32 atomics: the last bits
+ * of C and colsum_acc depend on the order of the additions. */
+int32_t pf_op_gemm_tn(int32_t dtype, const void* A, const void* B, float* C, float* colsum_acc, int64_t M, int64_t N,
+                      int64_t K, void* stream);
 /* x[t] = tok[ids[t]] + pos[t mod S]; ids int32 [tokens]; ids outside [0,V) contribute zeros. */
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x,
                     int64_t tokens, int32_t S, int32_t d, int32_t V, void* stream);

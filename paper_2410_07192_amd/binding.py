@@ -27,7 +27,7 @@ EXPORTS = [
     "pf_ctx_destroy", "pf_ctx_sync", "pf_ctx_set_io", "pf_load_layer_async", "pf_fill_chunk_fwd",
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
     "pf_ctx_set_replan", "pf_main_opt_state_bytes", "pf_ctx_set_main_offload", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
-    "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd", "pf_op_layernorm_bwd", "pf_op_transpose",
+    "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd", "pf_op_layernorm_bwd", "pf_op_transpose", "pf_op_gemm_tn",
 ]
 PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
 
@@ -142,6 +142,7 @@ def _load():
     lib.pf_op_attention_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_layernorm_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, VP, VP, VP, VP, I64, I32, VP]
     lib.pf_op_transpose.argtypes = [I32, VP, VP, I64, I64, VP, VP]
+    lib.pf_op_gemm_tn.argtypes = [I32, VP, VP, VP, VP, I64, I64, I64, VP]
     lib.pf_op_embed.argtypes = [I32, VP, VP, VP, VP, I64, I32, I32, I32, VP]
     return lib
 
@@ -523,6 +524,10 @@ def unpack_embedding_f32(md, raw):
 
 def pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream=None):
     _check(lib.pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream))
+
+
+def pf_op_gemm_tn(dtype, A, B, Cp, M, N, K, colsum_acc=None, stream=None):
+    _check(lib.pf_op_gemm_tn(dtype, A, B, Cp, colsum_acc, M, N, K, stream))
 
 
 def pf_op_transpose(dtype, src, dst, rows, cols, colsum_acc=None, stream=None):

@@ -23,6 +23,14 @@ struct GemmEpilogue {
 hipError_t gemm_nt(int32_t dtype, const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K,
                    const GemmEpilogue& ep, hipStream_t stream);
 
+// C[M,N] (fp32) += A^T B with A [K,M] and B [K,N] row-major bf16 (weight gradient dW = dY^T X from the tensors as
+// they lie in memory); colsum (fp32 [M], may be null): colsum[m] += sum over k of A[k][m].  Needs bf16, M and N
+// multiples of 8, K a multiple of 64 and 16-byte aligned operands (gemm_tn_acc_supported); K may be split over
+// workgroups, whose slices meet in C through fp32 atomics.
+bool gemm_tn_acc_supported(int32_t dtype, const void* A, const void* B, int64_t M, int64_t N, int64_t K);
+hipError_t gemm_tn_acc(int32_t dtype, const void* A, const void* B, float* C, float* colsum, int64_t M, int64_t N,
+                       int64_t K, hipStream_t stream);
+
 // ---- LayerNorm ------------------------------------------------------------------------------------
 // y = g * (x - mean) / sqrt(var + eps) + b per row of d elements.  mean_out / rstd_out (fp32 [rows])
 // may be null.

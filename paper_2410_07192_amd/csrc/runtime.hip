@@ -981,6 +981,16 @@ int32_t pf_op_transpose(int32_t dtype, const void* in, void* out, int64_t rows, 
   return PF_OK;
 }
 
+int32_t pf_op_gemm_tn(int32_t dtype, const void* A, const void* B, float* C, float* colsum_acc, int64_t M, int64_t N,
+                      int64_t K, void* stream) {
+  if (bad_dtype(dtype) || !A || !B || !C || M <= 0 || N <= 0 || K <= 0)
+    return pf::fail(PF_ERR_ARG, "pf_op_gemm_tn: bad argument");
+  if (!pf::gemm_tn_acc_supported(dtype, A, B, M, N, K))
+    return pf::fail(PF_ERR_ARG, "pf_op_gemm_tn: needs bf16, M and N multiples of 8, K a multiple of 64, 16-byte aligned operands");
+  PF_HIP(pf::gemm_tn_acc(dtype, A, B, C, colsum_acc, M, N, K, (hipStream_t)stream));
+  return PF_OK;
+}
+
 int32_t pf_op_embed(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int64_t tokens,
                     int32_t S, int32_t d, int32_t V, void* stream) {
   if (bad_dtype(dtype) || !ids || !tok || !pos || !x || tokens <= 0 || S <= 0 || d <= 0 || d % 8 != 0 || V <= 0)

@@ -2,10 +2,12 @@
 // moments, gradient accumulators, working and transposed copies in the model dtype), layer backward
 // with recompute from the layer's checkpoint, tied-head loss, embedding backward and Adam.
 //
-// Every GEMM runs on the one "NT" kernel (both operands contiguous along the contraction):
-//   dX = dY * W      uses the transposed weight copy kept next to the working weights,
-//   dW += dY^T * X   uses transposes of the two activation tensors made just before the GEMM,
-// with fp32 accumulation straight into the gradient accumulators.
+// Forward and dX GEMMs run on the "NT" kernel (both operands contiguous along the contraction):
+//   dX = dY * W      uses the transposed weight copy kept next to the working weights.
+// Weight gradients dW += dY^T * X contract over tokens, the slow index of both tensors: in bf16 the "TN"
+// kernel reads them as they are (and sums dY's columns for the bias gradient on the way); in fp32 transposes
+// of the two tensors, made just before, feed the NT kernel.  Either way fp32 accumulation goes straight into
+// the gradient accumulators.
 #include <cstring>
 #include <new>
 
@@ -252,28 +254,37 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
   GemmEpilogue b1;
   b1.dact_in = t.u;
   PF_HIP(gemm_nt(dt, G, wt + t.wt_off[3], t.d_mid, T, f, d, b1, st));            // du = (dy W_2) * gelu'(u)
-  PF_HIP(transpose2d_colsum(dt, G, t.tA, G32(11), T, d, st));                    // dy^T  [d][T], db_2
-  PF_HIP(transpose2d(dt, c->ws_mid, t.tB, T, f, st));                            // gelu(u)^T [f][T]
   GemmEpilogue acc;
   acc.out_f32 = 1;
   acc.accumulate = 1;
-  PF_HIP(gemm_nt(dt, t.tA, t.tB, G32(10), d, f, T, acc, st));                    // dW_2 [d][f]
-  PF_HIP(transpose2d_colsum(dt, t.d_mid, t.tB, G32(9), T, f, st));               // du^T [f][T], db_1
-  PF_HIP(transpose2d(dt, t.ln2, t.tA, T, d, st));                                // bb^T [d][T]
-  PF_HIP(gemm_nt(dt, t.tB, t.tA, G32(8), f, d, T, acc, st));                     // dW_1 [f][d]
+  // Weight and bias gradient of a linear layer y = x W^T + b from dy [T][n_out] and x [T][n_in]:
+  // dW += dy^T x, db += column sums of dy.  bf16: one kernel on the tensors as they are; otherwise transposed
+  // copies feed the NT kernel and the column sums come out of the first transpose.
+  auto weight_grad = [&](const void* dy, const void* xin, float* dW, float* db, int64_t n_out, int64_t n_in) -> int32_t {
+    if (gemm_tn_acc_supported(dt, dy, xin, n_out, n_in, T)) {
+      PF_HIP(gemm_tn_acc(dt, dy, xin, dW, db, n_out, n_in, T, st));
+      return PF_OK;
+    }
+    PF_HIP(transpose2d_colsum(dt, dy, t.tA, db, T, n_out, st));
+    PF_HIP(transpose2d(dt, xin, t.tB, T, n_in, st));
+    PF_HIP(gemm_nt(dt, t.tA, t.tB, dW, n_out, n_in, T, acc, st));
+    return PF_OK;
+  };
+  int32_t wrc = weight_grad(G, c->ws_mid, G32(10), G32(11), d, f);               // dW_2 [d][f], db_2
+  if (wrc != PF_OK) return wrc;
+  wrc = weight_grad(t.d_mid, t.ln2, G32(8), G32(9), f, d);                       // dW_1 [f][d], db_1
+  if (wrc != PF_OK) return wrc;
   GemmEpilogue none;
   PF_HIP(gemm_nt(dt, t.d_mid, wt + t.wt_off[2], t.d_ln, T, d, f, none, st));     // dbb = du W_1
   PF_HIP(layernorm_bwd(dt, t.d_ln, t.x1, wb + o[6], mean2, rstd2, G, G, G32(6), G32(7), t.ln_partial, T, d, st));
   // G now holds dx1.   x1 = x + c W_o + b_o
-  PF_HIP(transpose2d_colsum(dt, G, t.tA, G32(5), T, d, st));                     // dx1^T, db_o
-  PF_HIP(transpose2d(dt, c->ws_attn, t.tB, T, d, st));                           // c^T
-  PF_HIP(gemm_nt(dt, t.tA, t.tB, G32(4), d, d, T, acc, st));                     // dW_o [d][d]
+  wrc = weight_grad(G, c->ws_attn, G32(4), G32(5), d, d);                        // dW_o [d][d], db_o
+  if (wrc != PF_OK) return wrc;
   PF_HIP(gemm_nt(dt, G, wt + t.wt_off[1], t.d_attn, T, d, d, none, st));         // dc = dx1 W_o
   PF_HIP(attention_bwd(dt, c->ws_qkv, c->ws_attn, t.d_attn, t.lse, t.Dsum, t.d_qkv, m.batch, m.seq_len, m.n_heads, dh,
                        m.causal, st));
-  PF_HIP(transpose2d_colsum(dt, t.d_qkv, t.tA, G32(3), T, 3 * d, st));           // dqkv^T [3d][T], db_qkv
-  PF_HIP(transpose2d(dt, c->ws_ln, t.tB, T, d, st));                             // a^T [d][T]
-  PF_HIP(gemm_nt(dt, t.tA, t.tB, G32(2), 3 * d, d, T, acc, st));                 // dW_qkv [3d][d]
+  wrc = weight_grad(t.d_qkv, c->ws_ln, G32(2), G32(3), 3 * d, d);                // dW_qkv [3d][d], db_qkv
+  if (wrc != PF_OK) return wrc;
   PF_HIP(gemm_nt(dt, t.d_qkv, wt + t.wt_off[0], t.d_ln, T, d, 3 * d, none, st)); // da = dqkv W_qkv
   PF_HIP(layernorm_bwd(dt, t.d_ln, x, wb + o[0], mean1, rstd1, G, G, G32(0), G32(1), t.ln_partial, T, d, st));
   return PF_OK;
@@ -322,12 +333,17 @@ int32_t train_fwd_node(pf_ctx* c, const pf_node& n, int64_t replica, hipStream_t
         PF_HIP(gemm_nt(m.dtype, hf, t.E_w, t.logits, T, t.Vp, d, none, st));                    // logits [T][Vp]
         PF_HIP(ce_loss_inplace(m.dtype, t.logits, ids + mb * T, t.loss, T, t.Vp, m.vocab, m.seq_len, inv_n, st));
         PF_HIP(gemm_nt(m.dtype, t.logits, t.Et, t.d_ln, T, d, t.Vp, none, st));                 // dh = dlogits E
-        PF_HIP(transpose2d(m.dtype, t.logits, t.logitsT, T, t.Vp, st));                         // dlogits^T [Vp][T]
-        PF_HIP(transpose2d(m.dtype, hf, t.tB, T, d, st));                                       // h^T [d][T]
-        GemmEpilogue acc;
-        acc.out_f32 = 1;
-        acc.accumulate = 1;
-        PF_HIP(gemm_nt(m.dtype, t.logitsT, t.tB, (float*)((char*)ge + t.emb32_off[0]), t.Vp, d, T, acc, st));  // dE
+        float* dE = (float*)((char*)ge + t.emb32_off[0]);                                       // dE = dlogits^T h
+        if (gemm_tn_acc_supported(m.dtype, t.logits, hf, t.Vp, d, T)) {
+          PF_HIP(gemm_tn_acc(m.dtype, t.logits, hf, dE, nullptr, t.Vp, d, T, st));
+        } else {
+          PF_HIP(transpose2d(m.dtype, t.logits, t.logitsT, T, t.Vp, st));                       // dlogits^T [Vp][T]
+          PF_HIP(transpose2d(m.dtype, hf, t.tB, T, d, st));                                     // h^T [d][T]
+          GemmEpilogue acc;
+          acc.out_f32 = 1;
+          acc.accumulate = 1;
+          PF_HIP(gemm_nt(m.dtype, t.logitsT, t.tB, dE, t.Vp, d, T, acc, st));
+        }
         // final LayerNorm backward (statistics recomputed from the checkpointed input)
         PF_HIP(layernorm_fwd(m.dtype, ck(mb, L), t.lnf_g_w, t.lnf_b_w, t.ln2, meanf, rstdf, T, d, m.eps, st));
         PF_HIP(layernorm_bwd(m.dtype, t.d_ln, ck(mb, L), t.lnf_g_w, meanf, rstdf, nullptr, t.G + mb * act,

@@ -458,3 +458,52 @@ def test_transpose_kernel(dtype, R, Cn):
             assert np.abs(acc.cpu().numpy() - 3.0 - ref).max() < 1e-6 * scale + 1e-6
         else:
             assert bool((acc == 3.0).all())
+
+
+# (M, N, K): whole tiles, ragged edges in both directions (multiples of 8 only), one K step, K split over
+# workgroups (small M x N with long K), more tiles than resident workgroups
+GEMM_TN = [(128, 128, 64), (256, 384, 512), (200, 136, 192), (8, 8, 64), (72, 1000, 320), (256, 256, 4096),
+           (128, 128, 8192), (1536, 1280, 256)]
+
+
+@pytest.mark.parametrize("with_colsum", [False, True])
+@pytest.mark.parametrize("M,N,K", GEMM_TN)
+def test_gemm_tn_kernel(M, N, K, with_colsum):
+    """Weight-gradient GEMM on K-major operands against the plain float64 product; C and the column sums are
+    accumulated into, so both start from known non-zero values."""
+    pf, dev = _mods()
+    rng = np.random.default_rng(M * 3 + N * 5 + K)
+    A = synth.round_to_bf16(rng.standard_normal((K, M)).astype(np.float32))
+    Bm = synth.round_to_bf16((rng.standard_normal((K, N)) * 0.5).astype(np.float32))
+    md = pf.pf_model_desc()
+    md.dtype = pf.PF_DTYPE_BF16
+    dA, dB = dev.storage_tensor(A, md), dev.storage_tensor(Bm, md)
+    C0 = rng.standard_normal((M, N)).astype(np.float32)
+    dC = dev.to_device(C0)
+    acc = torch.full((M,), 0.5, dtype=torch.float32, device="cuda")
+    for rep in range(2):       # twice: accumulation, and the second call finds LDS and C as the first left them
+        pf.pf_op_gemm_tn(pf.PF_DTYPE_BF16, dA.data_ptr(), dB.data_ptr(), dC.data_ptr(), M, N, K,
+                         acc.data_ptr() if with_colsum else None)
+    torch.cuda.synchronize()
+    ref = C0.astype(np.float64) + 2.0 * (A.astype(np.float64).T @ Bm.astype(np.float64))
+    scale = np.abs(A.astype(np.float64)).T @ np.abs(Bm.astype(np.float64))
+    got = dC.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() <= 5e-5 * scale.max() + 1e-5        # fp32 accumulation of K exact bf16 products
+    if with_colsum:
+        cref = 0.5 + 2.0 * A.astype(np.float64).sum(axis=0)
+        assert np.abs(acc.cpu().numpy() - cref).max() <= 5e-5 * np.abs(A).sum(axis=0).max() + 1e-5
+    else:
+        assert bool((acc == 0.5).all())
+
+
+def test_gemm_tn_argument_errors():
+    pf, dev = _mods()
+    t = torch.zeros(1 << 16, dtype=torch.int16, device="cuda")
+    c = torch.zeros(1 << 16, dtype=torch.float32, device="cuda")
+    for M, N, K, dt in [(12, 8, 64, pf.PF_DTYPE_BF16), (8, 20, 64, pf.PF_DTYPE_BF16), (8, 8, 96, pf.PF_DTYPE_BF16),
+                        (8, 8, 64, pf.PF_DTYPE_F32), (0, 8, 64, pf.PF_DTYPE_BF16)]:
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_op_gemm_tn(dt, t.data_ptr(), t.data_ptr(), c.data_ptr(), M, N, K)
+        assert e.value.code == pf.PF_ERR_ARG
+    with pytest.raises(pf.PipeFillError):
+        pf.pf_op_gemm_tn(pf.PF_DTYPE_BF16, t.data_ptr() + 2, t.data_ptr(), c.data_ptr(), 8, 8, 64)
