@@ -13,7 +13,16 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
                                                             const T* __restrict__ b, T* __restrict__ y,
                                                             float* __restrict__ mean_out,
                                                             float* __restrict__ rstd_out, int64_t rows, int32_t d,
-                                                            float eps) {
+                                                            float eps, const uint4* __restrict__ warm, int64_t warm_n) {
+  // Optional side job: read warm_n 16-byte pieces (the weights of the GEMMs that follow) and drop them, so that
+  // they sit in the memory-side cache when a GEMM's first round of tiles asks for them all at once.  A layer's
+  // weights were last used a whole pass over the model earlier and are long evicted; with cold weights the
+  // QKV and FFN GEMMs of the 12-layer encoder workload take 3-7 us longer each (measured on one machine, in the
+  // same process, with and without), against 1.6 us that the extra reads add to this kernel.
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < warm_n; i += (int64_t)gridDim.x * 256) {
+    const uint4 v = warm[i];
+    asm volatile("" ::"v"(v.x), "v"(v.y), "v"(v.z), "v"(v.w));
+  }
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -64,12 +73,12 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
 
 template <typename T>
 hipError_t launch_ln(const void* x, const void* g, const void* b, void* y, float* mo, float* ro, int64_t rows,
-                     int32_t d, float eps, hipStream_t st) {
+                     int32_t d, float eps, const uint4* warm, int64_t warm_n, hipStream_t st) {
   const dim3 grid((unsigned)((rows + 3) / 4)), block(256);
   const int iters = (d + 511) / 512;
 #define PF_LN(I)                                                                                             \
   hipLaunchKernelGGL((layernorm_fwd_kernel<T, I>), grid, block, 0, st, (const T*)x, (const T*)g, (const T*)b, \
-                     (T*)y, mo, ro, rows, d, eps)
+                     (T*)y, mo, ro, rows, d, eps, warm, warm_n)
   if (iters <= 1) PF_LN(1);
   else if (iters <= 2) PF_LN(2);
   else if (iters <= 4) PF_LN(4);
@@ -107,10 +116,16 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const int32_t* __restric
 }  // namespace
 
 hipError_t layernorm_fwd(int32_t dtype, const void* x, const void* g, const void* b, void* y, float* mean_out,
-                         float* rstd_out, int64_t rows, int32_t d, float eps, hipStream_t stream) {
+                         float* rstd_out, int64_t rows, int32_t d, float eps, hipStream_t stream, const void* warm,
+                         int64_t warm_bytes) {
   if (rows <= 0 || d <= 0 || d % 8 != 0 || d > 8192) return hipErrorInvalidValue;
-  if (dtype == PF_DTYPE_BF16_) return launch_ln<bf16_t>(x, g, b, y, mean_out, rstd_out, rows, d, eps, stream);
-  return launch_ln<float>(x, g, b, y, mean_out, rstd_out, rows, d, eps, stream);
+  // whole 16-byte pieces inside [warm, warm + warm_bytes)
+  const uintptr_t w0 = ((uintptr_t)warm + 15) & ~(uintptr_t)15;
+  const int64_t skip = (int64_t)(w0 - (uintptr_t)warm);
+  const int64_t warm_n = (warm && warm_bytes > skip) ? (warm_bytes - skip) / 16 : 0;
+  if (dtype == PF_DTYPE_BF16_)
+    return launch_ln<bf16_t>(x, g, b, y, mean_out, rstd_out, rows, d, eps, (const uint4*)w0, warm_n, stream);
+  return launch_ln<float>(x, g, b, y, mean_out, rstd_out, rows, d, eps, (const uint4*)w0, warm_n, stream);
 }
 
 hipError_t embed_fwd(int32_t dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int64_t tokens,

@@ -33,10 +33,11 @@ hipError_t gemm_tn_acc(int32_t dtype, const void* A, const void* B, float* C, fl
 
 // ---- LayerNorm ------------------------------------------------------------------------------------
 // y = g * (x - mean) / sqrt(var + eps) + b per row of d elements.  mean_out / rstd_out (fp32 [rows])
-// may be null.
+// may be null.  warm / warm_bytes (optional): the kernel also reads that range and discards it, which leaves it
+// in the memory-side cache; the callers name the weights of the GEMM that consumes y.
 hipError_t layernorm_fwd(int32_t dtype, const void* x, const void* g, const void* b, void* y,
                          float* mean_out, float* rstd_out, int64_t rows, int32_t d, float eps,
-                         hipStream_t stream);
+                         hipStream_t stream, const void* warm = nullptr, int64_t warm_bytes = 0);
 
 // ---- attention ------------------------------------------------------------------------------------
 // qkv: [B*S, 3*d] rows = tokens, columns = Q | K | V blocks, head i at columns i*dh.. of each block.

@@ -234,7 +234,8 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
         *rstd2 = t.stats + 3 * t.stat_stride;
 
   // recompute the forward pass, keeping what the backward needs
-  PF_HIP(layernorm_fwd(dt, x, wb + o[0], wb + o[1], c->ws_ln, mean1, rstd1, T, d, m.eps, st));           // a
+  PF_HIP(layernorm_fwd(dt, x, wb + o[0], wb + o[1], c->ws_ln, mean1, rstd1, T, d, m.eps, st, wb + o[2],
+                       o[4] - o[2]));                                                                  // a (+ warms W_qkv, b_qkv)
   GemmEpilogue e1;
   e1.bias = wb + o[3];
   PF_HIP(gemm_nt(dt, c->ws_ln, wb + o[2], c->ws_qkv, T, 3 * d, d, e1, st));
@@ -243,7 +244,8 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
   e2.bias = wb + o[5];
   e2.resid = x;
   PF_HIP(gemm_nt(dt, c->ws_attn, wb + o[4], t.x1, T, d, d, e2, st));                                      // x1
-  PF_HIP(layernorm_fwd(dt, t.x1, wb + o[6], wb + o[7], t.ln2, mean2, rstd2, T, d, m.eps, st));            // bb
+  PF_HIP(layernorm_fwd(dt, t.x1, wb + o[6], wb + o[7], t.ln2, mean2, rstd2, T, d, m.eps, st, wb + o[8],
+                       c->lay.blob - o[8]));                                                           // bb (+ warms W_1 .. b_2)
   GemmEpilogue e3;
   e3.bias = wb + o[9];
   e3.gelu = 1;
