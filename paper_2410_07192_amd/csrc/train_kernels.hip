@@ -504,14 +504,14 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const T* __restrict__ dx
   if (t >= tokens) return;
   const int32_t id = ids[t];
   const bool ok = id >= 0 && id < V;
-  for (int c = lane * 8; c < d; c += 512) {
-    float v[8];
-    load8(dx + t * d + c, v);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (ok) unsafeAtomicAdd(dtok + (int64_t)id * d + c + j, v[j]);
-      unsafeAtomicAdd(dpos + (t % S) * (int64_t)d + c + j, v[j]);
-    }
+  // one column per lane and instruction: an atomic instruction then covers 256 consecutive bytes of the row
+  // (eight columns per lane would spread it over sixteen cache lines)
+  float* trow = dtok + (int64_t)(ok ? id : 0) * d;
+  float* prow = dpos + (t % S) * (int64_t)d;
+  for (int c = lane; c < d; c += 64) {
+    const float v = to_f32(dx[t * d + c]);
+    if (ok) unsafeAtomicAdd(trow + c, v);
+    unsafeAtomicAdd(prow + c, v);
   }
 }
 
