@@ -431,9 +431,13 @@ int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t
                    const void* bias, const void* resid, int32_t gelu, int32_t out_f32, int32_t accumulate,
                    void* stream);
 /* y = g * (x - mean) / sqrt(var + eps) + b per row; d a multiple of 8, at most 8192.
- * mean_out / rstd_out: fp32 [rows], may be NULL. */
+ * mean_out / rstd_out: fp32 [rows], may be NULL.
+ * warm / warm_bytes (device, may be NULL / 0): the kernel also reads the whole 16-byte pieces inside
+ * [warm, warm + warm_bytes) and discards them, which leaves them in the memory-side cache; the layer passes
+ * the weights of the GEMMs that follow.  The range must be readable device memory; y does not depend on it. */
 int32_t pf_op_layernorm(int32_t dtype, const void* x, const void* g, const void* b, void* y,
-                        float* mean_out, float* rstd_out, int64_t rows, int32_t d, float eps, void* stream);
+                        float* mean_out, float* rstd_out, int64_t rows, int32_t d, float eps, const void* warm,
+                        int64_t warm_bytes, void* stream);
 /* softmax(Q K^T / sqrt(dh) [+ causal mask]) V per (batch, head).  qkv: [B*S][3*h*dh] (Q | K | V
  * column blocks), out: [B*S][h*dh], lse: fp32 [B][h][S] or NULL.  dh in {8,16,32,64,128}. */
 int32_t pf_op_attention(int32_t dtype, const void* qkv, void* out, float* lse, int32_t B, int32_t S,

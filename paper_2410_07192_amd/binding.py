@@ -137,7 +137,7 @@ def _load():
     lib.pf_ctx_kernel_timing.argtypes = [VP, C.c_uint32]
     lib.pf_ctx_kernel_stats.argtypes = [VP, I32, P(I64), P(I64)]
     lib.pf_op_gemm.argtypes = [I32, VP, VP, VP, I64, I64, I64, VP, VP, I32, I32, I32, VP]
-    lib.pf_op_layernorm.argtypes = [I32, VP, VP, VP, VP, VP, VP, I64, I32, C.c_float, VP]
+    lib.pf_op_layernorm.argtypes = [I32, VP, VP, VP, VP, VP, VP, I64, I32, C.c_float, VP, I64, VP]
     lib.pf_op_attention.argtypes = [I32, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_attention_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_layernorm_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, VP, VP, VP, VP, I64, I32, VP]
@@ -475,8 +475,8 @@ def pf_op_gemm(dtype, X, W, Cp, M, N, K, bias=None, resid=None, gelu=0, out_f32=
     _check(lib.pf_op_gemm(dtype, X, W, Cp, M, N, K, bias, resid, gelu, out_f32, accumulate, stream))
 
 
-def pf_op_layernorm(dtype, x, g, b, y, rows, d, eps, mean_out=None, rstd_out=None, stream=None):
-    _check(lib.pf_op_layernorm(dtype, x, g, b, y, mean_out, rstd_out, rows, d, eps, stream))
+def pf_op_layernorm(dtype, x, g, b, y, rows, d, eps, mean_out=None, rstd_out=None, stream=None, warm=None, warm_bytes=0):
+    _check(lib.pf_op_layernorm(dtype, x, g, b, y, mean_out, rstd_out, rows, d, eps, warm, warm_bytes, stream))
 
 
 def pf_op_attention(dtype, qkv, out, B, S, h, dh, causal, lse=None, stream=None):

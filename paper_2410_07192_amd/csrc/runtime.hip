@@ -938,10 +938,11 @@ int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t
 }
 
 int32_t pf_op_layernorm(int32_t dtype, const void* x, const void* g, const void* b, void* y, float* mean_out,
-                        float* rstd_out, int64_t rows, int32_t d, float eps, void* stream) {
-  if (bad_dtype(dtype) || !x || !g || !b || !y || rows <= 0 || d <= 0 || d % 8 != 0 || d > 8192)
+                        float* rstd_out, int64_t rows, int32_t d, float eps, const void* warm, int64_t warm_bytes,
+                        void* stream) {
+  if (bad_dtype(dtype) || !x || !g || !b || !y || rows <= 0 || d <= 0 || d % 8 != 0 || d > 8192 || warm_bytes < 0)
     return pf::fail(PF_ERR_ARG, "pf_op_layernorm: bad argument (d must be a multiple of 8, at most 8192)");
-  PF_HIP(pf::layernorm_fwd(dtype, x, g, b, y, mean_out, rstd_out, rows, d, eps, (hipStream_t)stream));
+  PF_HIP(pf::layernorm_fwd(dtype, x, g, b, y, mean_out, rstd_out, rows, d, eps, (hipStream_t)stream, warm, warm_bytes));
   return PF_OK;
 }
 

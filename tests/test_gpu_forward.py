@@ -146,6 +146,32 @@ def test_layernorm(dtype, rows, d):
     assert rel_err(rstd.cpu().numpy(), rr[:, 0]) < 1e-5
 
 
+@pytest.mark.parametrize("offset,nbytes", [(0, 0), (0, 15), (0, 16), (2, 40), (6, 1 << 20), (0, 8 << 20), (16, (8 << 20) - 16)])
+def test_layernorm_with_a_range_to_warm(offset, nbytes):
+    """The side job of the LayerNorm kernel (reading a byte range and dropping it) changes nothing in its
+    result, whatever the alignment and length of the range: more pieces than threads, fewer, none, a
+    ragged head and tail.  The range lies inside an 8 MiB buffer."""
+    pf, dev = _mods()
+    md = _md("bf16")
+    rows, d = 300, 768
+    rng = np.random.default_rng(17)
+    x = synth.round_to_bf16(_rand(rng, (rows, d), "bf16", 2.0))
+    g, b = _rand(rng, (d,), "bf16"), _rand(rng, (d,), "bf16")
+    dx, dg, db = (dev.storage_tensor(a, md) for a in (x, g, b))
+    buf = torch.full((8 << 20,), 7, dtype=torch.uint8, device="cuda")
+    ys = []
+    for warm in (False, True):
+        y = dev.empty_storage((rows, d), md)
+        pf.pf_op_layernorm(md.dtype, dx.data_ptr(), dg.data_ptr(), db.data_ptr(), y.data_ptr(), rows, d, 1e-5,
+                           warm=buf.data_ptr() + offset if warm else None, warm_bytes=nbytes if warm else 0)
+        torch.cuda.synchronize()
+        ys.append(dev.to_host(y, np.uint16))
+    assert np.array_equal(ys[0], ys[1])
+    assert bool((buf == 7).all())
+    ref, _, _ = ot.layer_norm(x.astype(np.float64), g.astype(np.float64), b.astype(np.float64), 1e-5)
+    assert rel_err(dev.read_storage(dev.to_device(ys[1]), md), ref) < TOL["bf16"] / 2
+
+
 ATT_CASES = [("bf16", 2, 200, 3, 64), ("bf16", 1, 513, 2, 128), ("bf16", 3, 64, 2, 64), ("bf16", 2, 50, 2, 16),
              ("f32", 2, 128, 4, 64), ("f32", 2, 77, 2, 8), ("f32", 1, 130, 1, 128), ("bf16", 1, 1, 1, 64)]
 
