@@ -12,6 +12,7 @@ while the main stage is emulated on the timeline.  The headline value is
 Workloads (--workload):
   cfg2 (default)  12-layer bf16 encoder inference fill job, weights resident, 1F1B p=8 m=16
                   t_f=15 ms t_b=30 ms, 24 GiB free; the steps are shared evenly by the 8 stages.
+                  --schedule gpipe fills the two contiguous windows of a GPipe main job instead.
   cfg3            24-layer d=2048 causal decoder inference, weights streamed from pinned host memory,
                   explicit 40 ms bubbles separated by 20 ms, 8 GiB cap; g microbatches per layer
                   visit chosen by the planner.
@@ -19,7 +20,9 @@ Workloads (--workload):
                   accumulation across bubbles), 1F1B p=16 m=32, 16 GiB free.
   cfg5            real main-job stage (3 layers d=8192, fwd+bwd on its own stream) under emulated
                   1F1B p=16 m=32 with measured t_f/t_b, the cfg3 job filling its bubbles; reports
-                  the main-stage slowdown.
+                  the main-stage slowdown.  --main-offload adds the main job's optimizer phase
+                  (gradient synchronisation of --sync-ms, Adam update) and offloads optimizer state
+                  to pinned host memory around it; the windows gain the offloaded bytes.
 Prints ONE JSON line.
 """
 from __future__ import annotations
