@@ -107,6 +107,30 @@ def test_large_gemm_sampled_rows(M, N, K):
     assert rel_err(got, ref) < 1e-2
 
 
+@pytest.mark.parametrize("M,N,K", [(4096, 1024, 8192), (1024, 4096, 8192), (3072, 1024, 8192), (50304, 1024, 8192)])
+def test_weight_gradient_gemm_full_shapes(M, N, K):
+    """The weight-gradient shapes of the training workload (and of its tied head) on the k-major kernel, with the
+    bias gradient: sampled output rows and the whole column sum against float64."""
+    pf, dev = _mods()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(M + 3 * N + K)
+    A = torch.randn(K, M, device="cuda", generator=gen).to(torch.bfloat16)
+    Bm = (torch.randn(K, N, device="cuda", generator=gen) * 0.1).to(torch.bfloat16)
+    Cm = torch.zeros(M, N, device="cuda", dtype=torch.float32)
+    cs = torch.zeros(M, device="cuda", dtype=torch.float32)
+    pf.pf_op_gemm_tn(pf.PF_DTYPE_BF16, A.data_ptr(), Bm.data_ptr(), Cm.data_ptr(), M, N, K, cs.data_ptr())
+    torch.cuda.synchronize()
+    rows = [0, 1, 127, 128, M // 2 + 5, M - 1]
+    Ah = A[:, rows].float().cpu().numpy().astype(np.float64)
+    Bh = Bm.float().cpu().numpy().astype(np.float64)
+    ref = Ah.T @ Bh
+    got = Cm[rows].cpu().numpy().astype(np.float64)
+    scale = (np.abs(Ah).T @ np.abs(Bh)).max()
+    assert np.abs(got - ref).max() <= 5e-5 * scale
+    cref = A.double().sum(dim=0).cpu().numpy()          # exact enough: float64 sum of bf16 values
+    assert np.abs(cs.cpu().numpy() - cref).max() <= 5e-5 * float(A.double().abs().sum(dim=0).max())
+
+
 def test_explicit_bubble_cycle_timeline():
     """Explicit windows (p = 0): chunks run only inside the given windows, plans are cyclic, results of
     completed replicas match the checker, and the configuration choice agrees with the checker."""
