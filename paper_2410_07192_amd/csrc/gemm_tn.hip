@@ -124,25 +124,33 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tn_acc_kernel(const bf16_t* 
     const int cur = (int)(kt & 1);
     // the other stage was last read before the barrier that ended the previous step
     if (kt + 1 < nk) unrolled<0, 8>([&](auto i) { issue(i, cur ^ 1, kt + 1); });
+    // fragments of substep ks + 1 are requested before the MFMAs of substep ks are issued
+    bf16x8 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+    for (int b = 0; b < TM; ++b) fa[0][b] = frag(cur, offA[b], 0);
 #pragma unroll
-      for (int b = 0; b < TM; ++b) fa[b] = frag(cur, offA[b], ks);
+    for (int a = 0; a < TN; ++a) fb[0][a] = frag(cur, offB[a], 0);
+    unrolled<0, 4>([&](auto ksc) {
+      constexpr int ks = decltype(ksc)::value, buf = ks & 1;
+      if constexpr (ks + 1 < 4) {
 #pragma unroll
-      for (int a = 0; a < TN; ++a) fb[a] = frag(cur, offB[a], ks);
+        for (int b = 0; b < TM; ++b) fa[buf ^ 1][b] = frag(cur, offA[b], ks + 1);
+#pragma unroll
+        for (int a = 0; a < TN; ++a) fb[buf ^ 1][a] = frag(cur, offB[a], ks + 1);
+      }
 #pragma unroll
       for (int a = 0; a < TN; ++a)
 #pragma unroll
         for (int b = 0; b < TM; ++b)
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[a], fa[b], acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][a], fa[buf][b], acc[a][b], 0, 0, 0);
       if constexpr (COLSUM) {
         if (do_sum) {
 #pragma unroll
-          for (int b = 0; b < TM; ++b) csum[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fa[b], csum[b], 0, 0, 0);
+          for (int b = 0; b < TM; ++b)
+            csum[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, fa[buf][b], csum[b], 0, 0, 0);
         }
       }
-    }
+    });
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
   }
