@@ -2,6 +2,7 @@
 (attention couples tokens only inside a sequence, so one whole sequence of the batch is checked), in
 the launch configuration bench.py uses; plus the explicit-bubble timeline."""
 import ctypes as C
+import os
 
 import numpy as np
 import pytest
@@ -275,3 +276,31 @@ def test_next_job_starts_where_the_last_one_ended():
             m.ctx.pf_ctx_set_replan(True, 2_000_000, 0)
     finally:
         m.close()
+
+
+def test_bench_line_contract():
+    """bench.py prints exactly one JSON line with the fields the harness reads, the roofline of the dominant kernel
+    measured in the same run, and the CPU oracle timed beside it."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "8", "--warmup", "1", "--cpu-seqs", "1"],
+                         capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr[-2000:]
+    lines = [l for l in out.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 8 and d["warmup"] == 1 and d["higher_is_better"] is True
+    assert d["vs_baseline"] is None and d["dtype"] == "bf16" and d["data"] == "synthetic"
+    assert "workload" in d["config"] and "model" not in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0.1 < r["frac"] < 1.0
+    assert r["traffic"] is None or r["traffic"] > 0
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1 and c["sample"]
+    assert d["value"] > 1e5 and d["pct_bubble_filled"] > 50.0

@@ -338,3 +338,11 @@ def test_policy_study_runs():
     # shortest-job-first never has a larger mean completion time than FIFO on one queue of waiting jobs ... with
     # several devices of different speed that is not a theorem, so only its direction under overload is checked
     assert recs[1]["mean_jct_s"] <= recs[0]["mean_jct_s"] * 1.05
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert out.returncode != 0 and "ONE GPU" in out.stderr and out.stdout.strip() == ""
