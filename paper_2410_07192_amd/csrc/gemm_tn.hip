@@ -201,6 +201,16 @@ bool gemm_tn_acc_supported(int32_t dtype, const void* A, const void* B, int64_t 
          (((uintptr_t)A | (uintptr_t)B) & 15) == 0;
 }
 
+// The 128x128 tiles of this kernel reach about 650 TFLOP/s; the NT kernel's 256-wide tiles about 900 on results
+// large enough to fill the chip with them, but it needs both operands transposed first (4 K (M + N) bytes at about
+// 4 TB/s).  Equating the two gives M N / (M + N) = 1170: below that, or when 256x256 tiles would leave CUs idle,
+// this kernel is the faster way to a weight gradient.
+bool gemm_tn_acc_preferred(int64_t M, int64_t N, int64_t K) {
+  (void)K;   // both sides of the comparison are proportional to K
+  const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
+  return big_tiles < 256 || M * N < 1170 * (M + N);
+}
+
 hipError_t gemm_tn_acc(int32_t dtype, const void* A, const void* B, float* C, float* colsum, int64_t M, int64_t N,
                        int64_t K, hipStream_t stream) {
   if (!gemm_tn_acc_supported(dtype, A, B, M, N, K)) return hipErrorInvalidValue;

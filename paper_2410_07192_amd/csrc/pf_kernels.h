@@ -28,6 +28,8 @@ hipError_t gemm_nt(int32_t dtype, const void* X, const void* W, void* C, int64_t
 // multiples of 8, K a multiple of 64 and 16-byte aligned operands (gemm_tn_acc_supported); K may be split over
 // workgroups, whose slices meet in C through fp32 atomics.
 bool gemm_tn_acc_supported(int32_t dtype, const void* A, const void* B, int64_t M, int64_t N, int64_t K);
+// whether it beats transposing both operands for the NT kernel (measured rates; large results favour the latter)
+bool gemm_tn_acc_preferred(int64_t M, int64_t N, int64_t K);
 hipError_t gemm_tn_acc(int32_t dtype, const void* A, const void* B, float* C, float* colsum, int64_t M, int64_t N,
                        int64_t K, hipStream_t stream);
 

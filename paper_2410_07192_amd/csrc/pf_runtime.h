@@ -68,6 +68,9 @@ int32_t train_opt_state_copy(pf_ctx* c, int64_t off, int64_t len, char* host, bo
 int32_t train_opt_state_fill(pf_ctx* c, int64_t off, int64_t len, int32_t byte, hipStream_t st);
 // optimizer update of an emulated main stage after `microbatches` accumulated backward passes
 int32_t train_main_opt(pf_ctx* c, int32_t microbatches, hipStream_t st);
+// Weights that a LayerNorm reads ahead for the GEMMs after it: worth it while they are small beside the
+// LayerNorm's own traffic and the cache they are meant to sit in; larger ranges are not warmed (returns 0).
+inline int64_t warm_bytes(int64_t n) { return n <= ((int64_t)12 << 20) ? n : 0; }
 // one pre-LN layer forward for one microbatch with the weights at wb (blob layout)
 int32_t layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_out, hipStream_t st);
 }  // namespace pf

@@ -323,7 +323,7 @@ int32_t pf::layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_o
   {
     TimedScope t(c, PF_K_LAYERNORM, st);
     PF_HIP(pf::layernorm_fwd(dt, x_in, wb + o[0], wb + o[1], c->ws_ln, nullptr, nullptr, T, d, m.eps, st, wb + o[2],
-                             o[4] - o[2]));   // also warms W_qkv, b_qkv
+                             pf::warm_bytes(o[4] - o[2])));   // also warms W_qkv, b_qkv
   }
   pf::GemmEpilogue e1;
   e1.bias = wb + o[3];
@@ -346,7 +346,7 @@ int32_t pf::layer_forward(pf_ctx* c, const char* wb, const void* x_in, void* x_o
   {
     TimedScope t(c, PF_K_LAYERNORM, st);
     PF_HIP(pf::layernorm_fwd(dt, x_out, wb + o[6], wb + o[7], c->ws_ln, nullptr, nullptr, T, d, m.eps, st, wb + o[8],
-                             c->lay.blob - o[8]));   // also warms W_1 .. b_2
+                             pf::warm_bytes(c->lay.blob - o[8]) ? c->lay.blob - o[8] : pf::warm_bytes(o[10] - o[8])));   // W_1 .. b_2, or W_1 alone
   }
   pf::GemmEpilogue e3;
   e3.bias = wb + o[9];

@@ -235,7 +235,7 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
 
   // recompute the forward pass, keeping what the backward needs
   PF_HIP(layernorm_fwd(dt, x, wb + o[0], wb + o[1], c->ws_ln, mean1, rstd1, T, d, m.eps, st, wb + o[2],
-                       o[4] - o[2]));                                                                  // a (+ warms W_qkv, b_qkv)
+                       warm_bytes(o[4] - o[2])));                                                                  // a (+ warms W_qkv, b_qkv)
   GemmEpilogue e1;
   e1.bias = wb + o[3];
   PF_HIP(gemm_nt(dt, c->ws_ln, wb + o[2], c->ws_qkv, T, 3 * d, d, e1, st));
@@ -245,7 +245,7 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
   e2.resid = x;
   PF_HIP(gemm_nt(dt, c->ws_attn, wb + o[4], t.x1, T, d, d, e2, st));                                      // x1
   PF_HIP(layernorm_fwd(dt, t.x1, wb + o[6], wb + o[7], t.ln2, mean2, rstd2, T, d, m.eps, st, wb + o[8],
-                       c->lay.blob - o[8]));                                                           // bb (+ warms W_1 .. b_2)
+                       warm_bytes(o[10] - o[8])));                                                           // bb (+ warms W_1, b_1)
   GemmEpilogue e3;
   e3.bias = wb + o[9];
   e3.gelu = 1;
@@ -263,7 +263,7 @@ static int32_t layer_backward(pf_ctx* c, int32_t l, const char* x, char* G, hipS
   // dW += dy^T x, db += column sums of dy.  bf16: one kernel on the tensors as they are; otherwise transposed
   // copies feed the NT kernel and the column sums come out of the first transpose.
   auto weight_grad = [&](const void* dy, const void* xin, float* dW, float* db, int64_t n_out, int64_t n_in) -> int32_t {
-    if (gemm_tn_acc_supported(dt, dy, xin, n_out, n_in, T)) {
+    if (gemm_tn_acc_supported(dt, dy, xin, n_out, n_in, T) && gemm_tn_acc_preferred(n_out, n_in, T)) {
       PF_HIP(gemm_tn_acc(dt, dy, xin, dW, db, n_out, n_in, T, st));
       return PF_OK;
     }
@@ -336,7 +336,7 @@ int32_t train_fwd_node(pf_ctx* c, const pf_node& n, int64_t replica, hipStream_t
         PF_HIP(ce_loss_inplace(m.dtype, t.logits, ids + mb * T, t.loss, T, t.Vp, m.vocab, m.seq_len, inv_n, st));
         PF_HIP(gemm_nt(m.dtype, t.logits, t.Et, t.d_ln, T, d, t.Vp, none, st));                 // dh = dlogits E
         float* dE = (float*)((char*)ge + t.emb32_off[0]);                                       // dE = dlogits^T h
-        if (gemm_tn_acc_supported(m.dtype, t.logits, hf, t.Vp, d, T)) {
+        if (gemm_tn_acc_supported(m.dtype, t.logits, hf, t.Vp, d, T) && gemm_tn_acc_preferred(t.Vp, d, T)) {
           PF_HIP(gemm_tn_acc(m.dtype, t.logits, hf, dE, nullptr, t.Vp, d, T, st));
         } else {
           PF_HIP(transpose2d(m.dtype, t.logits, t.logitsT, T, t.Vp, st));                       // dlogits^T [Vp][T]
