@@ -534,7 +534,7 @@ def main():
                     help="cfg2: main-job schedule whose idle windows are filled (Sec. 4.5; GPipe has two contiguous windows per stage)")
     ap.add_argument("--stage", type=int, default=7, help="pipeline stage emulated by cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=4)
+    ap.add_argument("--cpu-seqs", type=int, default=24)
     ap.add_argument("--verbose", action="store_true", help="per-step statistics on stderr (cfg2)")
     ap.add_argument("--bubble-ms", type=float, default=40.0, help="cfg3: duration of the explicit bubbles")
     ap.add_argument("--cap-gib", type=float, default=8.0, help="cfg3, cfg5: free memory inside the bubbles")
