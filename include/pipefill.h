@@ -426,10 +426,14 @@ int32_t pf_ctx_kernel_stats(pf_ctx* ctx, int32_t cls, int64_t* count, int64_t* t
 /* ---- single kernels (the steps a layer visit is made of; used by tests and by the roofline
  * measurement).  All pointers device; `dtype` = storage type; fp32 accumulation throughout. ------ */
 /* C[M,N] = X[M,K] * W[N,K]^T (+ bias[N]) (GELU if gelu) (+ resid[M,N]); C is fp32 if out_f32 (then
- * accumulate != 0 adds to C's old contents), else dtype.  bf16: K must be a multiple of 8. */
+ * accumulate != 0 adds to C's old contents), else dtype.  bf16: K must be a multiple of 8.
+ * The two forms the training backward uses (both may be NULL):
+ * preact_out [M,N] (dtype): also receives X W^T + bias, the value before the GELU (kept for the backward pass);
+ * dact_in [M,N] (dtype): the result is multiplied element-wise by GELU'(dact_in) (backward through the
+ * activation: dU = (dY W_2) * GELU'(U)); not combined with bias, gelu, resid or preact_out. */
 int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K,
                    const void* bias, const void* resid, int32_t gelu, int32_t out_f32, int32_t accumulate,
-                   void* stream);
+                   const void* dact_in, void* preact_out, void* stream);
 /* y = g * (x - mean) / sqrt(var + eps) + b per row; d a multiple of 8, at most 8192.
  * mean_out / rstd_out: fp32 [rows], may be NULL.
  * warm / warm_bytes (device, may be NULL / 0): the kernel also reads the whole 16-byte pieces inside

@@ -136,7 +136,7 @@ def _load():
     lib.pf_ctx_read_params.argtypes = [VP, I32, I32, VP, I64, VP]
     lib.pf_ctx_kernel_timing.argtypes = [VP, C.c_uint32]
     lib.pf_ctx_kernel_stats.argtypes = [VP, I32, P(I64), P(I64)]
-    lib.pf_op_gemm.argtypes = [I32, VP, VP, VP, I64, I64, I64, VP, VP, I32, I32, I32, VP]
+    lib.pf_op_gemm.argtypes = [I32, VP, VP, VP, I64, I64, I64, VP, VP, I32, I32, I32, VP, VP, VP]
     lib.pf_op_layernorm.argtypes = [I32, VP, VP, VP, VP, VP, VP, I64, I32, C.c_float, VP, I64, VP]
     lib.pf_op_attention.argtypes = [I32, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_attention_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
@@ -471,8 +471,9 @@ def pf_timeline_run(fill_ctx, main_ctx, main_io, p, m, stage, tf_ns, tb_ns, wind
 
 
 # ------------------------------------------------------------------------------------------ kernels
-def pf_op_gemm(dtype, X, W, Cp, M, N, K, bias=None, resid=None, gelu=0, out_f32=0, accumulate=0, stream=None):
-    _check(lib.pf_op_gemm(dtype, X, W, Cp, M, N, K, bias, resid, gelu, out_f32, accumulate, stream))
+def pf_op_gemm(dtype, X, W, Cp, M, N, K, bias=None, resid=None, gelu=0, out_f32=0, accumulate=0, stream=None, dact_in=None,
+               preact_out=None):
+    _check(lib.pf_op_gemm(dtype, X, W, Cp, M, N, K, bias, resid, gelu, out_f32, accumulate, dact_in, preact_out, stream))
 
 
 def pf_op_layernorm(dtype, x, g, b, y, rows, d, eps, mean_out=None, rstd_out=None, stream=None, warm=None, warm_bytes=0):

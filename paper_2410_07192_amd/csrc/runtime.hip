@@ -923,9 +923,10 @@ static bool bad_dtype(int32_t dt) { return dt != PF_DTYPE_F32 && dt != PF_DTYPE_
 
 int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t M, int64_t N, int64_t K,
                    const void* bias, const void* resid, int32_t gelu, int32_t out_f32, int32_t accumulate,
-                   void* stream) {
+                   const void* dact_in, void* preact_out, void* stream) {
   if (bad_dtype(dtype) || !X || !W || !C || M <= 0 || N <= 0 || K <= 0 || (dtype == PF_DTYPE_BF16 && K % 8 != 0) ||
-      (accumulate && !out_f32 && dtype != PF_DTYPE_F32))
+      (accumulate && !out_f32 && dtype != PF_DTYPE_F32) ||
+      (dact_in && (bias || resid || gelu || preact_out || out_f32)) || (preact_out && out_f32))
     return pf::fail(PF_ERR_ARG, "pf_op_gemm: bad argument");
   pf::GemmEpilogue e;
   e.bias = bias;
@@ -933,6 +934,8 @@ int32_t pf_op_gemm(int32_t dtype, const void* X, const void* W, void* C, int64_t
   e.gelu = gelu;
   e.out_f32 = out_f32;
   e.accumulate = accumulate;
+  e.dact_in = dact_in;
+  e.preact_out = preact_out;
   PF_HIP(pf::gemm_nt(dtype, X, W, C, M, N, K, e, (hipStream_t)stream));
   return PF_OK;
 }

@@ -107,6 +107,44 @@ def test_gemm_large_tiles_with_ragged_edges(M, N, K):
     assert rel_err(acc.cpu().numpy(), 2 * ref0) < 1e-4
 
 
+# The two epilogues of the training backward, on whole 256-wide tiles (both tile shapes), with ragged edges
+# along M and N, with N not a multiple of 8, and on a shape that only the generic kernel takes.
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("M,N,K", [(512, 512, 128), (768, 384, 64), (8292, 2368, 128), (4196, 3112, 64), (1030, 522, 64),
+                                   (300, 200, 24)])
+def test_gemm_training_epilogues(dtype, M, N, K):
+    pf, dev = _mods()
+    md = _md(dtype)
+    if dtype == "f32" and M > 1100:
+        pytest.skip("the fp32 kernel has one code path; the small shapes cover it")
+    rng = np.random.default_rng(M * 7 + N + K)
+    X, W = _rand(rng, (M, K), dtype), _rand(rng, (N, K), dtype, 0.1)
+    bias, U = _rand(rng, (N,), dtype), _rand(rng, (M, N), dtype, 1.5)
+    dX, dW, dB, dU = (dev.storage_tensor(a, md) for a in (X, W, bias, U))
+    ref0 = X.astype(np.float64) @ W.astype(np.float64).T
+    tol = TOL[dtype] / 2
+    # forward of the first FFN matrix keeping the pre-activation: two outputs, rows behind both stay untouched
+    out = dev.empty_storage((M + 1, N), md)
+    pre = dev.empty_storage((M + 1, N), md)
+    out.zero_()
+    pre.zero_()
+    pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), out.data_ptr(), M, N, K, bias=dB.data_ptr(), gelu=1,
+                  preact_out=pre.data_ptr())
+    torch.cuda.synchronize()
+    o, p_ = dev.read_storage(out, md), dev.read_storage(pre, md)
+    assert rel_err(p_[:M], ref0 + bias) < tol and not p_[M].any()
+    assert rel_err(o[:M], ot.gelu(ref0 + bias)) < tol and not o[M].any()
+    # backward through the activation: (X W^T) * GELU'(U)
+    out.zero_()
+    pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), out.data_ptr(), M, N, K, dact_in=dU.data_ptr())
+    torch.cuda.synchronize()
+    o = dev.read_storage(out, md)
+    assert rel_err(o[:M], ref0 * ot.gelu_grad(U.astype(np.float64))) < tol and not o[M].any()
+    for bad in (dict(bias=dB.data_ptr()), dict(gelu=1), dict(resid=dU.data_ptr()), dict(preact_out=pre.data_ptr())):
+        with pytest.raises(pf.PipeFillError):
+            pf.pf_op_gemm(md.dtype, dX.data_ptr(), dW.data_ptr(), out.data_ptr(), M, N, K, dact_in=dU.data_ptr(), **bad)
+
+
 # Weight-gradient shapes: small result, K = all tokens; C holds an earlier gradient that must be kept.
 @pytest.mark.parametrize("M,N,K", [(1024, 1024, 8192), (3072, 1024, 8192), (1000, 520, 4096), (256, 256, 2048)])
 def test_gemm_accumulate_long_k(M, N, K):
