@@ -304,13 +304,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
       return;
     }
   }
-  // Staged epilogue (bf16 output, no per-element side inputs other than bias / residual): bias and GELU
-  // are applied in registers, the bf16 tile goes through LDS (free after the K loop; 16-byte slots
-  // XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the tile, the residual
-  // being added on the way out from equally coalesced loads.
-  constexpr bool STAGED = std::is_same<OutT, bf16_t>::value && !(EPI & (E_PRE | E_DACT | E_ACC));
+  // Staged epilogue (bf16 output): bias and GELU are applied in registers, the bf16 tile goes through LDS (free
+  // after the K loop; 16-byte slots XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the
+  // tile, the residual being added on the way out from equally coalesced loads.  The two training forms use the same
+  // route: the pre-activation is a second tile staged and stored before the activated one, and the saved tensor whose
+  // GELU' multiplies the result comes in the other way round, coalesced loads -> LDS -> the accumulator layout.
+  constexpr bool STAGED = std::is_same<OutT, bf16_t>::value && !(EPI & E_ACC);
   if constexpr (STAGED) {
-    const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid) & 15) == 0);
+    static_assert(!(EPI & E_DACT) || EPI == E_DACT, "GELU' multiplies the plain product only");
+    const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid | (uintptr_t)ep.preact_out |
+                                                 (uintptr_t)ep.dact_in) & 15) == 0);
     if (interior && aligned16) {
       constexpr int SLOTS = BN / 8, NT = 64 * NW, PER = BM * BN / 8 / NT;
       // 16-byte slot of a row, moved per row so that the lanes of a wave (32 rows, same column group) spread
@@ -320,6 +323,89 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
         else return (slot + row) % SLOTS;
       };
       uint2* st8 = (uint2*)smem;
+      if constexpr (EPI & E_DACT) {
+        // tile of the saved pre-activation: eight 16-byte pieces per thread at a time (more would not fit beside
+        // the accumulators), then every lane picks up the values of its own accumulator elements
+        constexpr int CH = PER < 8 ? PER : 8;
+#pragma unroll
+        for (int i0 = 0; i0 < PER; i0 += CH) {
+          uint4 t[CH];
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            if (i0 + i < PER) {
+              const int q = (i0 + i) * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+              t[i] = *(const uint4*)((const bf16_t*)ep.dact_in + (m0 + row) * N + n0 + slot * 8);
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            if (i0 + i < PER) {
+              const int q = (i0 + i) * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+              smem[row * SLOTS + swz(slot, row)] = t[i];
+            }
+          }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+        static_for<0, TN>([&](auto a) {
+          static_for<0, TM>([&](auto b) {
+            const int row = (wm * TM + b) * 32 + lr;
+            static_for<0, 4>([&](auto rg) {
+              const int slot = (wn * TN + a) * 4 + rg;
+              const uint2 u = st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk];
+              acc[a][b][rg * 4 + 0] *= gelu_grad_f(bf16_bits_to_f32(u.x & 0xffffu));
+              acc[a][b][rg * 4 + 1] *= gelu_grad_f(bf16_bits_to_f32(u.x >> 16));
+              acc[a][b][rg * 4 + 2] *= gelu_grad_f(bf16_bits_to_f32(u.y & 0xffffu));
+              acc[a][b][rg * 4 + 3] *= gelu_grad_f(bf16_bits_to_f32(u.y >> 16));
+            });
+          });
+        });
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();   // everyone has its values: the tile's place in LDS is free again
+      }
+      // accumulators (+ bias) (-> GELU) -> bf16 -> LDS in the swizzled row-major layout
+      auto stage_tile = [&](auto with_gelu) {
+        static_for<0, TN>([&](auto a) {
+          float bias4[4][4] = {};
+          if constexpr (EPI & E_BIAS) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg)
+              load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
+          }
+          static_for<0, TM>([&](auto b) {
+            const int row = (wm * TM + b) * 32 + lr;
+            static_for<0, 4>([&](auto rg) {
+              float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                            acc[a][b][rg * 4 + 3]};
+              if constexpr (EPI & E_BIAS) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] += bias4[rg][j];
+              }
+              if constexpr (decltype(with_gelu)::value) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
+              }
+              uint2 pk;
+              pk.x = pack_bf16x2(v[0], v[1]);
+              pk.y = pack_bf16x2(v[2], v[3]);
+              const int slot = (wn * TN + a) * 4 + rg;
+              st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk] = pk;
+            });
+          });
+        });
+      };
+      if constexpr (EPI & E_PRE) {   // the value before the activation leaves first, the same way
+        stage_tile(std::false_type{});
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          *(uint4*)((bf16_t*)ep.preact_out + (m0 + row) * N + n0 + slot * 8) = smem[row * SLOTS + swz(slot, row)];
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+      }
       // the residual tile is requested first, in the layout of the final stores, so that it arrives while the
       // accumulators go through bias / GELU / LDS
       constexpr int EARLY = PER < 8 ? PER : 8;   // more would not fit beside the accumulators
@@ -331,34 +417,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
           rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
         }
       }
-      static_for<0, TN>([&](auto a) {
-        float bias4[4][4] = {};
-        if constexpr (EPI & E_BIAS) {
-#pragma unroll
-          for (int rg = 0; rg < 4; ++rg)
-            load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
-        }
-        static_for<0, TM>([&](auto b) {
-          const int row = (wm * TM + b) * 32 + lr;
-          static_for<0, 4>([&](auto rg) {
-            float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                          acc[a][b][rg * 4 + 3]};
-            if constexpr (EPI & E_BIAS) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] += bias4[rg][j];
-            }
-            if constexpr (EPI & E_GELU) {
-#pragma unroll
-              for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
-            }
-            uint2 pk;
-            pk.x = pack_bf16x2(v[0], v[1]);
-            pk.y = pack_bf16x2(v[2], v[3]);
-            const int slot = (wn * TN + a) * 4 + rg;
-            st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk] = pk;
-          });
-        });
-      });
+      stage_tile(std::integral_constant<bool, (EPI & E_GELU) != 0>{});
       if constexpr (EPI & E_RESID) {   // the accumulators are dead now: the rest of the residual tile
 #pragma unroll
         for (int i = EARLY; i < PER; ++i) {

@@ -134,8 +134,18 @@ __device__ __forceinline__ float gelu_as<float>(float x) { return gelu_f(x); }
 template <>
 __device__ __forceinline__ float gelu_as<bf16_t>(float x) { return gelu_bf16_f(x); }
 
+// Phi(x) + x * phi(x) with Phi from the same rational approximation as erf_fast, written out so that the one
+// exp(-x^2 / 2) serves both terms: 1 - Phi(|x|) = p(t) * t * exp(-x^2 / 2) / 2 with t = 1 / (1 + 0.3275911 |x| / sqrt 2)
 __device__ __forceinline__ float gelu_grad_f(float x) {
-  return 0.5f * (1.0f + erf_fast(x * 0.70710678118654752f)) + x * 0.3989422804014327f * __expf(-0.5f * x * x);
+  const float ax = fabsf(x);
+  const float e = __builtin_amdgcn_exp2f(-0.72134752044448170f * x * x);   // exp(-x^2 / 2)
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.23164188843f, ax, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  const float tail = 0.5f * p * t * e;
+  return fmaf(x * 0.3989422804014327f, e, x < 0.0f ? tail : 1.0f - tail);
 }
 
 // Workgroup ids are dealt round-robin to the 8 XCDs (id % 8).  Returns the work unit of workgroup `pid` such
