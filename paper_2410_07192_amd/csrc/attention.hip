@@ -19,6 +19,8 @@ namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
+// first-class 16-byte value (the struct type would travel through a private-memory copy)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------------------
 template <int DH>
@@ -32,8 +34,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
   constexpr int VP = 68;             // pitch (elements) of a V^T row: 64 keys + 4 pad
   constexpr int KCH = 64 * CPR / 256;   // K chunks staged per thread
   constexpr int VUNITS = 16 * CPR;      // (4-key group, chunk) units of the V transpose, one per thread
-  __shared__ uint4 sK[64 * CPR];
-  __shared__ __align__(16) uint16_t sVt[DH * VP];
+  __shared__ uint4 sK2[2][64 * CPR];                        // two tiles: one is read while the next is written
+  __shared__ __align__(16) uint16_t sVt2[2][DH * VP];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
@@ -48,12 +50,15 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
   const int q_row = q_blk + wave * 32 + lr;                // this lane's query
 
+  // Rows are addressed by a 32-bit row number times the row stride, clamped to the last row of the sequence, so
+  // that no load sits in a branch (the compiler would otherwise wait for all of them at the next join): what a
+  // clamped row brings in is masked (scores) or zeroed before it reaches LDS (V).
+  const uint32_t rs32 = (uint32_t)rs;
   bf16x8 fq[KS];
+  {
+    const bf16_t* qp = base + (uint64_t)(uint32_t)(q_row < S ? q_row : S - 1) * rs32 + g * 8;
 #pragma unroll
-  for (int kk = 0; kk < KS; ++kk) {
-    uint4 t = make_uint4(0, 0, 0, 0);
-    if (q_row < S) t = *(const uint4*)(base + (int64_t)q_row * rs + kk * 16 + g * 8);
-    fq[kk] = as_bf16x8(t);
+    for (int kk = 0; kk < KS; ++kk) fq[kk] = as_bf16x8(*(const uint4*)(qp + kk * 16));
   }
 
   f32x16 accO[DT];
@@ -61,8 +66,6 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
   for (int i = 0; i < DT; ++i)
 #pragma unroll
     for (int r = 0; r < 16; ++r) accO[i][r] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-
   int n_tiles = (S + 63) / 64;
   if (causal) {
     const int last_q = (q_blk + 127 < S - 1) ? q_blk + 127 : S - 1;
@@ -70,33 +73,41 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
     if (need < n_tiles) n_tiles = need;
   }
 
-  // Tile staging goes global -> registers (issued before the previous tile's MFMAs, so the loads
-  // are in flight during them) -> LDS.  K keeps its row-major chunks (swizzled).  V is transposed
+  // Tile staging goes global -> registers (issued a whole tile ahead, so the loads are in flight during
+  // the previous tile's work) -> LDS (two buffers, one barrier per tile).  K keeps its row-major chunks (swizzled).  V is transposed
   // on the way: a thread takes one 8-wide d_head chunk of FOUR consecutive keys and writes, for each
   // of the 8 d_head rows, the 4 keys as one 8-byte piece; 16 lanes with consecutive key groups cover
   // 128 contiguous bytes of a V^T row, so the LDS writes are free of bank conflicts.
   const int v_kg = tid & 15, v_c = tid >> 4;
-  uint4 rk[KCH], rv[4];
+  u32x4 rk[KCH], rv[4];
   auto load_regs = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int q = tid + i * 256, r = q / CPR, c = q % CPR;
-      rk[i] = (k0 + r < S) ? *(const uint4*)(base + (int64_t)(k0 + r) * rs + d + c * 8) : make_uint4(0, 0, 0, 0);
+      const int row = (k0 + r < S) ? k0 + r : S - 1;
+      rk[i] = *(const u32x4*)(base + (uint64_t)(uint32_t)row * rs32 + d + c * 8);
     }
     if (tid < VUNITS) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int key = k0 + 4 * v_kg + j;
-        rv[j] = (key < S) ? *(const uint4*)(base + (int64_t)key * rs + 2 * d + v_c * 8) : make_uint4(0, 0, 0, 0);
+        rv[j] = *(const u32x4*)(base + (uint64_t)(uint32_t)(key < S ? key : S - 1) * rs32 + 2 * d + v_c * 8);
       }
     }
   };
-  auto write_lds = [&]() {
+  auto write_lds = [&](int buf, int k0) {
+    uint4* sK = sK2[buf];
+    uint16_t* sVt = sVt2[buf];
+    if (k0 + 64 > S && tid < VUNITS) {   // ragged last tile: keys past the end contribute 0 * 0, not 0 * V[S-1]
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (k0 + 4 * v_kg + j >= S) rv[j] = u32x4{0, 0, 0, 0};
+    }
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int q = tid + i * 256, r = q / CPR, c = q % CPR;
       const int sw = (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
-      sK[r * CPR + sw] = rk[i];
+      *(u32x4*)&sK[r * CPR + sw] = rk[i];
     }
     if (tid < VUNITS) {
       const uint32_t w0[4] = {rv[0].x, rv[0].y, rv[0].z, rv[0].w}, w1[4] = {rv[1].x, rv[1].y, rv[1].z, rv[1].w};
@@ -114,64 +125,79 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
     }
   };
 
+  // m_ref is the reference point of the running sum and of O (scaled scores, log2 units).  It follows the running
+  // maximum lazily: it moves only when some query of the wave exceeds it by more than 8, so p stays below 2^8 and
+  // most tiles skip the rescaling of O altogether; the result is the same up to rounding.
+  float m_ref = -INFINITY, l_run = 0.f;
   load_regs(0);
+  if (n_tiles > 0) {
+    write_lds(0, 0);
+    if (n_tiles > 1) load_regs(64);
+  }
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int k0 = kt * 64;
-    __syncthreads();   // previous tile fully consumed
-    write_lds();
+    // tile kt is in place for everyone, and everyone has left tile kt-1, whose buffer tile kt+1 takes over
     __syncthreads();
-    if (kt + 1 < n_tiles) load_regs(k0 + 64);
+    if (kt + 1 < n_tiles) {
+      write_lds((kt + 1) & 1, k0 + 64);
+      if (kt + 2 < n_tiles) load_regs(k0 + 128);
+    }
     // a wave whose 32 queries all precede this tile has nothing to add (causal)
     if (causal && k0 > q_blk + wave * 32 + 31) continue;
+    const uint4* sK = sK2[kt & 1];
+    const uint16_t* sVt = sVt2[kt & 1];
 
     // S^T tile: 64 keys x 32 queries per wave
     f32x16 accS[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) accS[ks][r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KS; ++kk) {
+    for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
         const int r = ks * 32 + lr, c = kk * 2 + g;
         const int sw = (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
         accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(sK[r * CPR + sw]), fq[kk], accS[ks], 0, 0, 0);
       }
-    }
-    // scale, mask, running max
+    // mask (only the tiles that touch the diagonal or the end of the sequence), maximum of the raw scores
     const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
-    float mx = -INFINITY;
+    if (need_mask) {
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+      for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float s = accS[ks][r] * scale_log2e;
-        if (need_mask) {
+        for (int r = 0; r < 16; ++r) {
           const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (key >= S || (causal && key > q_row)) s = -INFINITY;
+          if (key >= S || (causal && key > q_row)) accS[ks][r] = -INFINITY;
         }
-        accS[ks][r] = s;
-        mx = fmaxf(mx, s);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);            // m_run = -inf -> 0
+    }
+    float mx = fmaxf(accS[0][0], accS[1][0]);
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, accS[0][r]), accS[1][r]);   // one three-input max each
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2e;
+    if (__any(mx > m_ref + 8.0f)) {   // also the first tile (m_ref = -inf)
+      const float m_new = fmaxf(m_ref, mx);
+      const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);   // m_ref = -inf -> 0
+      l_run *= alpha;
+#pragma unroll
+      for (int i = 0; i < DT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) accO[i][r] *= alpha;
+      m_ref = m_new;
+    }
+    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
     float ps = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(accS[ks][r] - m_use);
+        const float p = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m));
         accS[ks][r] = p;
         ps += p;
       }
     ps += __shfl_xor(ps, 32, 64);
-    l_run = l_run * alpha + ps;
-    m_run = m_new;
-#pragma unroll
-    for (int i = 0; i < DT; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) accO[i][r] *= alpha;
+    l_run += ps;
 
     // O^T += V^T P^T.  K step i covers keys 16i..16i+15; in operand slot (g, t) sits key
     // 16i + 8*(t/4) + 4g + t%4, which is register 8*(i%2) + t of accS[i/2].
@@ -202,7 +228,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
                             accO[dt][rg * 4 + 3] * inv};
         store4(orow + dt * 32 + rg * 8 + g * 4, v);
       }
-    if (lse && g == 0) lse[((int64_t)b * h + hd) * S + q_row] = m_run * LN2 + __logf(l_run);
+    if (lse && g == 0) lse[((int64_t)b * h + hd) * S + q_row] = m_ref * LN2 + __logf(l_run);
   }
 }
 
