@@ -6,8 +6,8 @@
 // wave's Q rows the "B" operand, kept in registers), so that a lane holds 32 of the 64 scores of ONE
 // query: running max / sum need a single cross-lane exchange (lane ^ 32) and the rescale factor
 // is a per-lane scalar.  The probabilities, already in the "B" operand layout, then feed
-// O^T = V^T P^T; V is transposed into LDS ([d_head][key], padded pitch) when the tile is staged so
-// that the "A" operand reads are two 8-byte LDS loads.
+// O^T = V^T P^T.  K and V tiles go global -> LDS directly, row-major as they lie in memory; the V^T "A" operand
+// comes out of the row-major V tile through the transposing LDS load (ds_read_b64_tr_b16), two per fragment.
 //
 // Generic path (fp32, or any d_head in {8,16,32,64,128}): one thread per query, keys staged in LDS,
 // online softmax key by key.  Used for the small fp32 parity workload and odd head sizes.
@@ -19,23 +19,29 @@ namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
-// first-class 16-byte value (the struct type would travel through a private-memory copy)
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(3))) char* lds_char_ptr;
 
 // ------------------------------------------------------------------------------------------------
 template <int DH>
-__global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
+__global__ __launch_bounds__(256, DH == 64 ? 4 : 2) void attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                             float* __restrict__ lse, int32_t S, int32_t h,
                                                             int32_t causal, float scale_log2e, int32_t nq,
                                                             int32_t n_wg) {
-  constexpr int CPR = DH / 8;        // 16-byte chunks per K row
+  constexpr int CPR = DH / 8;        // 16-byte chunks per row
   constexpr int KS = DH / 16;        // MFMA K steps over d_head
   constexpr int DT = DH / 32;        // 32-row tiles of O^T
-  constexpr int VP = 68;             // pitch (elements) of a V^T row: 64 keys + 4 pad
-  constexpr int KCH = 64 * CPR / 256;   // K chunks staged per thread
-  constexpr int VUNITS = 16 * CPR;      // (4-key group, chunk) units of the V transpose, one per thread
-  __shared__ uint4 sK2[2][64 * CPR];                        // two tiles: one is read while the next is written
-  __shared__ __align__(16) uint16_t sVt2[2][DH * VP];
+  constexpr int ROWB = DH * 2;       // bytes per K or V row
+  constexpr int TILE = 64 * ROWB;    // bytes per tile of 64 keys
+  constexpr int NI = TILE / 1024;    // wave-wide copies (1 KB each) per tile
+  constexpr int RPI = 1024 / ROWB;   // rows per copy
+  constexpr int PER = 2 * NI / 4;    // copies per wave per (K, V) tile pair
+  // two buffers of (K tile | V tile), both row-major as in memory, 16-byte chunks swizzled within a row
+  __shared__ __align__(16) char smem[2 * 2 * TILE];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
@@ -51,8 +57,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
   const int q_row = q_blk + wave * 32 + lr;                // this lane's query
 
   // Rows are addressed by a 32-bit row number times the row stride, clamped to the last row of the sequence, so
-  // that no load sits in a branch (the compiler would otherwise wait for all of them at the next join): what a
-  // clamped row brings in is masked (scores) or zeroed before it reaches LDS (V).
+  // that no load sits in a branch: a clamped row repeats the last row of the sequence, which the tile holds anyway,
+  // and the scores of the keys past the end are masked, so their probabilities are 0.
   const uint32_t rs32 = (uint32_t)rs;
   bf16x8 fq[KS];
   {
@@ -73,79 +79,72 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
     if (need < n_tiles) n_tiles = need;
   }
 
-  // Tile staging goes global -> registers (issued a whole tile ahead, so the loads are in flight during
-  // the previous tile's work) -> LDS (two buffers, one barrier per tile).  K keeps its row-major chunks (swizzled).  V is transposed
-  // on the way: a thread takes one 8-wide d_head chunk of FOUR consecutive keys and writes, for each
-  // of the 8 d_head rows, the 4 keys as one 8-byte piece; 16 lanes with consecutive key groups cover
-  // 128 contiguous bytes of a V^T row, so the LDS writes are free of bank conflicts.
-  const int v_kg = tid & 15, v_c = tid >> 4;
-  u32x4 rk[KCH], rv[4];
-  auto load_regs = [&](int k0) {
+  // Swizzles (XOR on the 16-byte chunk index of a row).  K is read as the MFMA "A" operand, one 16-byte chunk per
+  // lane, 32 consecutive rows per half-wave: rows are spread over the banks by (row / 2) % 8 (d_head 64: two rows
+  // per 256 bytes) or row % 16.  V is read through the transposing LDS load, where 16 lanes fetch a 4-key x
+  // 32-byte block: the 32-byte pairs of the four rows must fall on different banks, so the pair index is flipped
+  // by (row / 2) % 2 (d_head 64: rows r and r+1 already sit in different halves of the banks) or row % 4.
+  auto swz_k = [](int r) { return CPR == 8 ? ((r >> 1) & 7) : (r & 15); };
+  auto swz_v = [](int r) { return CPR == 8 ? (((r >> 1) & 1) << 1) : ((r & 3) << 1); };
+
+  // Tile staging: global -> LDS directly, no registers in between.  One wave-wide copy moves 1 KB = RPI rows into
+  // consecutive LDS bytes (lane i -> byte 16 i); which chunk of the row a lane fetches undoes the swizzle.  Copy q
+  // of a tile belongs to wave q % 4; a wave's copy i (i < PER / 2: K, else V) covers rows from st_row + 4 i RPI,
+  // all congruent modulo the period of both swizzles, so one chunk offset per operand serves every copy.
+  static_assert((4 * RPI) % 16 == 0, "rows of one lane's copies must share their swizzle");
+  const int st_row = wave * RPI + lane / CPR;
+  const int st_col_k = d + (((lane % CPR) ^ swz_k(st_row)) << 3);
+  const int st_col_v = 2 * d + (((lane % CPR) ^ swz_v(st_row)) << 3);
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)smem);
+  auto stage = [&](int buf, int k0) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int q = tid + i * 256, r = q / CPR, c = q % CPR;
-      const int row = (k0 + r < S) ? k0 + r : S - 1;
-      rk[i] = *(const u32x4*)(base + (uint64_t)(uint32_t)row * rs32 + d + c * 8);
-    }
-    if (tid < VUNITS) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int key = k0 + 4 * v_kg + j;
-        rv[j] = *(const u32x4*)(base + (uint64_t)(uint32_t)(key < S ? key : S - 1) * rs32 + 2 * d + v_c * 8);
-      }
-    }
-  };
-  auto write_lds = [&](int buf, int k0) {
-    uint4* sK = sK2[buf];
-    uint16_t* sVt = sVt2[buf];
-    if (k0 + 64 > S && tid < VUNITS) {   // ragged last tile: keys past the end contribute 0 * 0, not 0 * V[S-1]
-#pragma unroll
-      for (int j = 0; j < 4; ++j)
-        if (k0 + 4 * v_kg + j >= S) rv[j] = u32x4{0, 0, 0, 0};
-    }
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int q = tid + i * 256, r = q / CPR, c = q % CPR;
-      const int sw = (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
-      *(u32x4*)&sK[r * CPR + sw] = rk[i];
-    }
-    if (tid < VUNITS) {
-      const uint32_t w0[4] = {rv[0].x, rv[0].y, rv[0].z, rv[0].w}, w1[4] = {rv[1].x, rv[1].y, rv[1].z, rv[1].w};
-      const uint32_t w2[4] = {rv[2].x, rv[2].y, rv[2].z, rv[2].w}, w3[4] = {rv[3].x, rv[3].y, rv[3].z, rv[3].w};
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        uint2 even, odd;   // d_head rows 2jj and 2jj+1 of the chunk, keys 4kg..4kg+3
-        even.x = (w0[jj] & 0xffffu) | (w1[jj] << 16);
-        even.y = (w2[jj] & 0xffffu) | (w3[jj] << 16);
-        odd.x = (w0[jj] >> 16) | (w1[jj] & 0xffff0000u);
-        odd.y = (w2[jj] >> 16) | (w3[jj] & 0xffff0000u);
-        *(uint2*)(sVt + (v_c * 8 + 2 * jj) * VP + 4 * v_kg) = even;
-        *(uint2*)(sVt + (v_c * 8 + 2 * jj + 1) * VP + 4 * v_kg) = odd;
-      }
+    for (int i = 0; i < PER; ++i) {
+      constexpr int HALF = PER / 2;
+      const bool is_v = i >= HALF;
+      const int q = wave + 4 * (i % HALF);   // copy index within the K or V tile
+      const uint32_t dst =
+          __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(buf * 2 * TILE + (is_v ? TILE : 0) + q * 1024));
+      int row = k0 + st_row + 4 * (i % HALF) * RPI;
+      row = row < S ? row : S - 1;
+      const bf16_t* p = base + (uint64_t)(uint32_t)row * rs32 + (is_v ? st_col_v : st_col_k);
+      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p) : "memory", "m0");
     }
   };
+
+  // V^T operand of O^T += V^T P^T for K step i (keys 16 i .. 16 i + 15) and d_head block dt: lane 16 G + p points
+  // at key 16 i + 8 r + 4 g + p / 4 (r = 0, 1 the two reads) and at the four d_head columns from
+  // 32 dt + 16 (G % 2) + 4 (p % 4); it receives column 32 dt + lane % 32 of the four keys, which is the order the
+  // probabilities have in the "B" operand registers.
+  int v_off[DT];
+  {
+    const int pl = lane & 15, mb = (lane >> 4) & 1, row = 4 * g + (pl >> 2);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      const int c = dt * 4 + mb * 2 + ((pl & 3) >> 1);
+      v_off[dt] = TILE + row * ROWB + ((c ^ swz_v(row)) << 4) + 8 * (pl & 1);   // swz_v(row + 8 r + 16 i) = swz_v(row)
+    }
+  }
 
   // m_ref is the reference point of the running sum and of O (scaled scores, log2 units).  It follows the running
   // maximum lazily: it moves only when some query of the wave exceeds it by more than 8, so p stays below 2^8 and
   // most tiles skip the rescaling of O altogether; the result is the same up to rounding.
   float m_ref = -INFINITY, l_run = 0.f;
-  load_regs(0);
-  if (n_tiles > 0) {
-    write_lds(0, 0);
-    if (n_tiles > 1) load_regs(64);
-  }
+  // the Q fragments are waited for here, once: left pending, the compiler would wait for them in every iteration
+  // with a count that also holds back the copies issued just before
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fq[kk]));
+  stage(0, 0);
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int k0 = kt * 64;
-    // tile kt is in place for everyone, and everyone has left tile kt-1, whose buffer tile kt+1 takes over
+    // tile kt has landed (every wave waits for its own copies, then the barrier), and everyone has left tile
+    // kt - 1, whose buffer tile kt + 1 takes over
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (kt + 1 < n_tiles) {
-      write_lds((kt + 1) & 1, k0 + 64);
-      if (kt + 2 < n_tiles) load_regs(k0 + 128);
-    }
+    if (kt + 1 < n_tiles) stage((kt + 1) & 1, k0 + 64);
     // a wave whose 32 queries all precede this tile has nothing to add (causal)
     if (causal && k0 > q_blk + wave * 32 + 31) continue;
-    const uint4* sK = sK2[kt & 1];
-    const uint16_t* sVt = sVt2[kt & 1];
+    const char* sKb = smem + (kt & 1) * 2 * TILE;
+    lds_char_ptr sVb = (lds_char_ptr)(lds_void_ptr)smem + (kt & 1) * 2 * TILE;
 
     // S^T tile: 64 keys x 32 queries per wave
     f32x16 accS[2];
@@ -158,8 +157,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks) {
         const int r = ks * 32 + lr, c = kk * 2 + g;
-        const int sw = (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
-        accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(sK[r * CPR + sw]), fq[kk], accS[ks], 0, 0, 0);
+        const uint4 fk = *(const uint4*)(sKb + r * ROWB + ((c ^ swz_k(r)) << 4));
+        accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fk), fq[kk], accS[ks], 0, 0, 0);
       }
     // mask (only the tiles that touch the diagonal or the end of the sequence), maximum of the raw scores
     const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
@@ -208,11 +207,13 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_fwd_bf16_kernel(co
       for (int t = 0; t < 8; ++t) fp[t] = (__bf16)accS[i >> 1][8 * (i & 1) + t];
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        const uint16_t* vr = sVt + (dt * 32 + lr) * VP + 16 * i + 4 * g;
-        const uint2 lo = *(const uint2*)vr;
-        const uint2 hi = *(const uint2*)(vr + 8);
-        const uint4 fv = make_uint4(lo.x, lo.y, hi.x, hi.y);
-        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fv), fp, accO[dt], 0, 0, 0);
+        lds_char_ptr vp = sVb + v_off[dt] + 16 * i * ROWB;
+        const v4s r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)vp);
+        const v4s r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(vp + 8 * ROWB));
+        v8s fv;
+        fv[0] = r0[0]; fv[1] = r0[1]; fv[2] = r0[2]; fv[3] = r0[3];
+        fv[4] = r1[0]; fv[5] = r1[1]; fv[6] = r1[2]; fv[7] = r1[3];
+        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fv), fp, accO[dt], 0, 0, 0);
       }
     }
   }
