@@ -7,11 +7,12 @@
 //    MFMA "B" operands) and walks the queries in tiles of 64 staged in LDS.  S = Q K^T and dP = dO V^T
 //    are computed with the query tile as the "A" operand, so a lane holds ONE key and 32 of the 64
 //    queries: exactly the "B" operand layout the second pair of products needs
-//    (dV^T += dO^T P, dK^T += Q^T dS, contraction over queries), with Q^T and dO^T read from
-//    transposed copies of the tile in LDS.
+//    (dV^T += dO^T P, dK^T += Q^T dS, contraction over queries), with Q^T and dO^T fragments read from
+//    the same row-major tiles through the transposing LDS load (ds_read_b64_tr_b16).
 //  * dQ pass: mirror image of the forward kernel: a workgroup owns 128 queries (Q and dO rows in
 //    registers), walks the keys in tiles of 64; S^T = K Q^T and dP^T = V dO^T put one query per lane,
-//    so lse and D are per-lane scalars, and dQ^T += K^T dS^T reads K^T from a transposed LDS copy.
+//    so lse and D are per-lane scalars, and dQ^T += K^T dS^T reads K^T through the transposing load.
+// Tiles go global -> LDS directly (no staging registers), a whole tile ahead, into the other of two buffers.
 // A small pre-pass computes D.
 #include "pf_kernels.h"
 #include "pf_device.h"
@@ -50,35 +51,65 @@ __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __rest
   Dsum[(bb * h + hd) * S + q] = s;
 }
 
-// stage a 64-row tile of one head: `rows` valid rows starting at src (row stride rs elements) into a
-// swizzled [row][dh] copy and, if dstT is given, a transposed [dh][row] copy with pitch 68
-template <int DH>
-__device__ __forceinline__ void stage_tile(const bf16_t* src, int64_t rs, int rows, uint4* dst, uint16_t* dstT, int tid) {
-  constexpr int CPR = DH / 8;
-#pragma unroll
-  for (int i = 0; i < 64 * CPR / 256; ++i) {
-    const int q = tid + i * 256, r = q / CPR, c = q % CPR;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (r < rows) v = *(const uint4*)(src + (int64_t)r * rs + c * 8);
-    dst[r * CPR + swz<CPR>(r, c)] = v;
-    if (dstT) {
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        dstT[(c * 8 + 2 * j) * 68 + r] = (uint16_t)(w[j] & 0xffffu);
-        dstT[(c * 8 + 2 * j + 1) * 68 + r] = (uint16_t)(w[j] >> 16);
-      }
-    }
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) v4s* lds_v4s_ptr;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef const __attribute__((address_space(3))) char* lds_char_ptr;
+
+// Tiles of 64 rows x d_head lie in LDS row-major, as in memory, with the 16-byte chunks of a row XOR-swizzled by
+// swz_rt(row).  A tile is read two ways: row-wise (one 16-byte chunk per lane, consecutive rows per lane: the MFMA
+// operand whose contraction runs over d_head) and through the transposing LDS load (16 lanes fetch a 4-row x
+// 32-byte block: the operand whose contraction runs over the rows).  The swizzle is a bijection of the 16 (d_head
+// 128) or 8 (d_head 64, two rows per 256 bytes) bank phases for the first, and moves the 32-byte pairs of four
+// consecutive rows apart for the second.  It depends on row % 16 only.
+template <int CPR>
+__device__ __forceinline__ int swz_rt(int r) {
+  if (CPR == 8) {
+    const int x = (r >> 1) & 7;
+    return ((x & 1) << 1) | ((x >> 1) & 1) | (x & 4);
   }
+  const int x = r & 15;
+  return (x & 8) | ((x & 3) << 1) | ((x >> 2) & 1);
 }
 
-__device__ __forceinline__ bf16x8 read_t_frag(const uint16_t* rowp) {
-  const uint2 lo = *(const uint2*)rowp;
-  const uint2 hi = *(const uint2*)(rowp + 8);
-  return as_bf16x8(make_uint4(lo.x, lo.y, hi.x, hi.y));
+// one wave-wide copy of 1 KB, global -> LDS directly: lane i's 16 bytes land at dst + 16 i (dst wave-uniform)
+__device__ __forceinline__ void copy_1k(uint32_t dst, const bf16_t* p) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p) : "memory", "m0");
+}
+
+// Byte offsets of a lane's transposing reads inside a tile, for the 32-column block dt and K step 0: lane 16 G + p
+// points at row 8 r + 4 g + p / 4 (r = 0, 1: the two reads; g = lane / 32) and at the four columns from
+// 32 dt + 16 (G % 2) + 4 (p % 4), and receives column 32 dt + lane % 32 of the four rows.  K step i adds 16 i rows
+// (the swizzle has period 16); the two reads are 8 rows apart, where the swizzle differs, so both offsets are kept.
+template <int DH>
+__device__ __forceinline__ void tr_offsets(int lane, int off[][2]) {
+  constexpr int CPR = DH / 8, ROWB = DH * 2;
+  const int pl = lane & 15, mb = (lane >> 4) & 1, g = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int row = 8 * r + 4 * g + (pl >> 2);
+      const int c = dt * 4 + mb * 2 + ((pl & 3) >> 1);
+      off[dt][r] = row * ROWB + ((c ^ swz_rt<CPR>(row)) << 4) + 8 * (pl & 1);
+    }
+}
+
+template <int ROWB>
+__device__ __forceinline__ bf16x8 read_tr_frag2(lds_char_ptr tile, const int off[2], int i) {
+  const v4s r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(tile + off[0] + 16 * i * ROWB));
+  const v4s r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(tile + off[1] + 16 * i * ROWB));
+  v8s f;
+  f[0] = r0[0]; f[1] = r0[1]; f[2] = r0[2]; f[3] = r0[3];
+  f[4] = r1[0]; f[5] = r1[1]; f[6] = r1[2]; f[7] = r1[3];
+  return __builtin_bit_cast(bf16x8, f);
 }
 
 // ------------------------------------------------------------------------------------------------
+// dK, dV: a workgroup owns 128 keys (a wave 32 of them, K and V fragments in registers) and walks the queries in
+// tiles of 64.  Per tile: Q and dO go global -> LDS directly, a whole tile ahead, into the other of two buffers;
+// lse and D of the tile travel through one register per thread.
 template <int DH>
 __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kernel(const bf16_t* __restrict__ qkv,
                                                                 const bf16_t* __restrict__ dout,
@@ -86,15 +117,10 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
                                                                 const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv,
                                                                 int32_t S, int32_t h, int32_t causal, float scale_log2e,
                                                                 float scale, int32_t nblk, int32_t n_wg) {
-  constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32, TP = 68;
-  // dynamic LDS (68 KB for d_head 128): Q | dO tiles, their transposes, lse and D of the tile
-  extern __shared__ uint4 dyn_smem[];
-  uint4* sQ = dyn_smem;
-  uint4* sdO = sQ + 64 * CPR;
-  uint16_t* sQt = (uint16_t*)(sdO + 64 * CPR);
-  uint16_t* sdOt = sQt + DH * TP;
-  float* sL = (float*)(sdOt + DH * TP);
-  float* sD = sL + 64;
+  constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32, ROWB = DH * 2, TILE = 64 * ROWB, NI = TILE / 1024,
+                RPI = 1024 / ROWB;
+  constexpr int BUF = 2 * TILE + 512;   // Q tile | dO tile | lse (log2 units) of the 64 queries | D
+  extern __shared__ __align__(16) char dyn_smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
@@ -104,21 +130,21 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
   const int k_blk = (unit % nblk) * 128;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;
+  const uint32_t rs32 = (uint32_t)rs, d32 = (uint32_t)d;
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
   const bf16_t* dobase = dout + (int64_t)b * S * d + hd * DH;
   const int key = k_blk + wave * 32 + lr;
 
+  // rows past the end are clamped, not branched around (a load in a branch makes the compiler wait for everything
+  // in flight at the join); what a clamped key accumulates is not stored
   bf16x8 fk[KS], fv[KS];
+  {
+    const bf16_t* p = base + (uint64_t)(uint32_t)(key < S ? key : S - 1) * rs32 + g * 8;
 #pragma unroll
-  for (int kk = 0; kk < KS; ++kk) {
-    uint4 a = make_uint4(0, 0, 0, 0), c = make_uint4(0, 0, 0, 0);
-    if (key < S) {
-      const bf16_t* p = base + (int64_t)key * rs + kk * 16 + g * 8;
-      a = *(const uint4*)(p + d);
-      c = *(const uint4*)(p + 2 * d);
+    for (int kk = 0; kk < KS; ++kk) {
+      fk[kk] = as_bf16x8(*(const uint4*)(p + d + kk * 16));
+      fv[kk] = as_bf16x8(*(const uint4*)(p + 2 * d + kk * 16));
     }
-    fk[kk] = as_bf16x8(a);
-    fv[kk] = as_bf16x8(c);
   }
   f32x16 accK[DT], accV[DT];
 #pragma unroll
@@ -126,20 +152,62 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
 #pragma unroll
     for (int r = 0; r < 16; ++r) accK[i][r] = accV[i][r] = 0.f;
 
+  const int st_row = wave * RPI + lane / CPR;
+  const int st_col = ((lane % CPR) ^ swz_rt<CPR>(st_row)) << 3;   // the same for all copies of a lane (rows 16 apart)
+  static_assert((4 * RPI) % 16 == 0, "rows of one lane's copies must share their swizzle");
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)dyn_smem);
+  auto stage = [&](int buf, int q0) {
+#pragma unroll
+    for (int i = 0; i < NI / 4; ++i) {
+      int row = q0 + st_row + 4 * i * RPI;
+      row = row < S ? row : S - 1;
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(buf * BUF + (wave + 4 * i) * 1024));
+      copy_1k(dst, base + (uint64_t)(uint32_t)row * rs32 + st_col);
+      copy_1k(dst + TILE, dobase + (uint64_t)(uint32_t)row * d32 + st_col);
+    }
+  };
+  // threads 0..63 carry lse, 64..127 carry D (the others repeat them and write nothing)
+  const float* ld_src = ((tid & 64) ? Dsum : lse) + ((int64_t)b * h + hd) * S;
+  auto load_ld = [&](int q0) {
+    const int q = q0 + (tid & 63);
+    return ld_src[q < S ? q : S - 1];
+  };
+  auto write_ld = [&](int buf, int q0, float v) {
+    if (tid < 128) {
+      const bool ok = q0 + (tid & 63) < S;
+      // a query past the end gets lse = +inf, so its probabilities are exp2(x - inf) = 0
+      const float w = (tid < 64) ? (ok ? v * LOG2E_B : INFINITY) : (ok ? v : 0.f);
+      *(float*)(dyn_smem + buf * BUF + 2 * TILE + tid * 4) = w;
+    }
+  };
+  int t_off[DT][2];
+  tr_offsets<DH>(lane, t_off);
+
   const int n_qt = (S + 63) / 64;
   const int qt0 = causal ? k_blk / 64 : 0;   // queries before the first key of the block see none of its keys
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fk[kk]), "v"(fv[kk]));   // waited for here, once
+  float ld = 0.f;
+  if (qt0 < n_qt) {
+    stage(0, qt0 * 64);
+    ld = load_ld(qt0 * 64);
+  }
   for (int qt = qt0; qt < n_qt; ++qt) {
-    const int q0 = qt * 64;
-    const int rows = (S - q0 < 64) ? S - q0 : 64;
+    const int cur = (qt - qt0) & 1, q0 = qt * 64;
+    // buffer cur was last read two iterations ago and the barrier of the previous iteration is behind us
+    write_ld(cur, q0, ld);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    stage_tile<DH>(base + (int64_t)q0 * rs, rs, rows, sQ, sQt, tid);
-    stage_tile<DH>(dobase + (int64_t)q0 * d, d, rows, sdO, sdOt, tid);
-    if (tid < 64) {
-      const bool ok = tid < rows;
-      sL[tid] = ok ? lse[((int64_t)b * h + hd) * S + q0 + tid] * LOG2E_B : INFINITY;   // exp2(x - inf) = 0
-      sD[tid] = ok ? Dsum[((int64_t)b * h + hd) * S + q0 + tid] : 0.f;
+    if (qt + 1 < n_qt) {
+      stage(cur ^ 1, q0 + 64);
+      ld = load_ld(q0 + 64);
     }
-    __syncthreads();
+    const char* sQ = dyn_smem + cur * BUF;
+    const char* sdO = sQ + TILE;
+    const float* sL = (const float*)(sQ + 2 * TILE);
+    const float* sD = sL + 64;
+    lds_char_ptr tQ = (lds_char_ptr)(lds_void_ptr)dyn_smem + cur * BUF;
+    lds_char_ptr tdO = tQ + TILE;
 
     f32x16 P[2], dS[2];
     const bool need_mask = causal && (q0 < k_blk + 128);
@@ -151,9 +219,9 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         const int r = qs * 32 + lr, c = kk * 2 + g;
-        const int o = r * CPR + swz<CPR>(r, c);
-        aS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(sQ[o]), fk[kk], aS, 0, 0, 0);
-        aP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(sdO[o]), fv[kk], aP, 0, 0, 0);
+        const int o = r * ROWB + ((c ^ swz_rt<CPR>(r)) << 4);
+        aS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(const uint4*)(sQ + o)), fk[kk], aS, 0, 0, 0);
+        aP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(const uint4*)(sdO + o)), fv[kk], aP, 0, 0, 0);
       }
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) {
@@ -163,7 +231,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
         const float Lv[4] = {L4.x, L4.y, L4.z, L4.w}, Dv[4] = {D4.x, D4.y, D4.z, D4.w};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          float p = __builtin_amdgcn_exp2f(aS[rg * 4 + j] * scale_log2e - Lv[j]);
+          float p = __builtin_amdgcn_exp2f(fmaf(aS[rg * 4 + j], scale_log2e, -Lv[j]));
           if (need_mask && key > q0 + qi + j) p = 0.f;
           P[qs][rg * 4 + j] = p;
           dS[qs][rg * 4 + j] = p * (aP[rg * 4 + j] - Dv[j]);
@@ -182,9 +250,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
       }
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        const int off = (dt * 32 + lr) * TP + 16 * i + 4 * g;
-        accV[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t_frag(sdOt + off), fp, accV[dt], 0, 0, 0);
-        accK[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t_frag(sQt + off), fds, accK[dt], 0, 0, 0);
+        accV[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr_frag2<ROWB>(tdO, t_off[dt], i), fp, accV[dt], 0, 0, 0);
+        accK[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr_frag2<ROWB>(tQ, t_off[dt], i), fds, accK[dt], 0, 0, 0);
       }
     }
   }
@@ -204,6 +271,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 2 : 1) void attn_bwd_dkv_bf16_kerne
 }
 
 // ------------------------------------------------------------------------------------------------
+// dQ: a workgroup owns 128 queries (Q and dO fragments, lse and D in registers) and walks the keys in tiles of
+// 64; K and V tiles go global -> LDS directly, a whole tile ahead, into the other of two buffers.
 template <int DH>
 __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv,
                                                                const bf16_t* __restrict__ dout,
@@ -211,10 +280,10 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel
                                                                const float* __restrict__ Dsum, bf16_t* __restrict__ dqkv,
                                                                int32_t S, int32_t h, int32_t causal, float scale_log2e,
                                                                float scale, int32_t nblk, int32_t n_wg) {
-  constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32, TP = 68;
-  __shared__ uint4 sK[64 * CPR];
-  __shared__ uint4 sV[64 * CPR];
-  __shared__ uint16_t sKt[DH * TP];
+  constexpr int CPR = DH / 8, KS = DH / 16, DT = DH / 32, ROWB = DH * 2, TILE = 64 * ROWB, NI = TILE / 1024,
+                RPI = 1024 / ROWB;
+  constexpr int BUF = 2 * TILE;   // K tile | V tile
+  extern __shared__ __align__(16) char dyn_smem[];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
@@ -224,23 +293,25 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel
   const int q_blk = (unit % nblk) * 128;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;
+  const uint32_t rs32 = (uint32_t)rs;
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
   const int q_row = q_blk + wave * 32 + lr;
   const bool live = q_row < S;
+  const int q_cl = live ? q_row : S - 1;
 
   bf16x8 fq[KS], fdo[KS];
+  {
+    const bf16_t* pq = base + (uint64_t)(uint32_t)q_cl * rs32 + g * 8;
+    const bf16_t* pd = dout + ((int64_t)b * S + q_cl) * d + hd * DH + g * 8;
 #pragma unroll
-  for (int kk = 0; kk < KS; ++kk) {
-    uint4 a = make_uint4(0, 0, 0, 0), c = make_uint4(0, 0, 0, 0);
-    if (live) {
-      a = *(const uint4*)(base + (int64_t)q_row * rs + kk * 16 + g * 8);
-      c = *(const uint4*)(dout + ((int64_t)b * S + q_row) * d + hd * DH + kk * 16 + g * 8);
+    for (int kk = 0; kk < KS; ++kk) {
+      fq[kk] = as_bf16x8(*(const uint4*)(pq + kk * 16));
+      fdo[kk] = as_bf16x8(*(const uint4*)(pd + kk * 16));
     }
-    fq[kk] = as_bf16x8(a);
-    fdo[kk] = as_bf16x8(c);
   }
-  const float Lq = live ? lse[((int64_t)b * h + hd) * S + q_row] * LOG2E_B : INFINITY;
-  const float Dq = live ? Dsum[((int64_t)b * h + hd) * S + q_row] : 0.f;
+  const float Lraw = lse[((int64_t)b * h + hd) * S + q_cl], Draw = Dsum[((int64_t)b * h + hd) * S + q_cl];
+  const float nLq = live ? -Lraw * LOG2E_B : -INFINITY;   // a query past the end: exp2(x - inf) = 0
+  const float Dq = live ? Draw : 0.f;
   f32x16 accQ[DT];
 #pragma unroll
   for (int i = 0; i < DT; ++i)
@@ -253,13 +324,36 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel
     const int need = last_q / 64 + 1;
     if (need < n_tiles) n_tiles = need;
   }
+  const int st_row = wave * RPI + lane / CPR;
+  const int st_col = ((lane % CPR) ^ swz_rt<CPR>(st_row)) << 3;
+  static_assert((4 * RPI) % 16 == 0, "rows of one lane's copies must share their swizzle");
+  const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)dyn_smem);
+  auto stage = [&](int buf, int k0) {
+#pragma unroll
+    for (int i = 0; i < NI / 4; ++i) {
+      int row = k0 + st_row + 4 * i * RPI;
+      row = row < S ? row : S - 1;
+      const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(buf * BUF + (wave + 4 * i) * 1024));
+      const bf16_t* p = base + (uint64_t)(uint32_t)row * rs32 + st_col;
+      copy_1k(dst, p + d);
+      copy_1k(dst + TILE, p + 2 * d);
+    }
+  };
+  int t_off[DT][2];
+  tr_offsets<DH>(lane, t_off);
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fq[kk]), "v"(fdo[kk]));   // waited for here, once
+  asm volatile("" ::"v"(nLq), "v"(Dq));
+
+  stage(0, 0);
   for (int kt = 0; kt < n_tiles; ++kt) {
-    const int k0 = kt * 64;
-    const int rows = (S - k0 < 64) ? S - k0 : 64;
+    const int k0 = kt * 64, cur = kt & 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    stage_tile<DH>(base + (int64_t)k0 * rs + d, rs, rows, sK, sKt, tid);
-    stage_tile<DH>(base + (int64_t)k0 * rs + 2 * d, rs, rows, sV, nullptr, tid);
-    __syncthreads();
+    if (kt + 1 < n_tiles) stage(cur ^ 1, k0 + 64);
+    const char* sK = dyn_smem + cur * BUF;
+    const char* sV = sK + TILE;
+    lds_char_ptr tK = (lds_char_ptr)(lds_void_ptr)dyn_smem + cur * BUF;
     const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
     f32x16 dS[2];
 #pragma unroll
@@ -270,13 +364,13 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel
 #pragma unroll
       for (int kk = 0; kk < KS; ++kk) {
         const int r = ks * 32 + lr, c = kk * 2 + g;
-        const int o = r * CPR + swz<CPR>(r, c);
-        aS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(sK[o]), fq[kk], aS, 0, 0, 0);
-        aP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(sV[o]), fdo[kk], aP, 0, 0, 0);
+        const int o = r * ROWB + ((c ^ swz_rt<CPR>(r)) << 4);
+        aS = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(const uint4*)(sK + o)), fq[kk], aS, 0, 0, 0);
+        aP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(const uint4*)(sV + o)), fdo[kk], aP, 0, 0, 0);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float p = __builtin_amdgcn_exp2f(aS[r] * scale_log2e - Lq);
+        float p = __builtin_amdgcn_exp2f(fmaf(aS[r], scale_log2e, nLq));
         if (need_mask) {
           const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
           if (key >= S || (causal && key > q_row)) p = 0.f;
@@ -290,10 +384,8 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel
 #pragma unroll
       for (int t = 0; t < 8; ++t) fds[t] = (__bf16)dS[i >> 1][8 * (i & 1) + t];
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const int off = (dt * 32 + lr) * TP + 16 * i + 4 * g;
-        accQ[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_t_frag(sKt + off), fds, accQ[dt], 0, 0, 0);
-      }
+      for (int dt = 0; dt < DT; ++dt)
+        accQ[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_tr_frag2<ROWB>(tK, t_off[dt], i), fds, accQ[dt], 0, 0, 0);
     }
   }
   if (live) {
@@ -319,18 +411,22 @@ hipError_t launch(const void* qkv, const void* o, const void* dout, const float*
   const int64_t nblk = (S + 127) / 128, n_wg = nblk * h * B;
   if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)n_wg), block(256);
-  constexpr size_t lds = 2 * 64 * (DH / 8) * 16 + 2 * DH * 68 * 2 + 2 * 64 * 4;
+  constexpr int TILE = 64 * DH * 2;
+  constexpr size_t lds_dkv = 2 * (2 * TILE + 512), lds_dq = 2 * 2 * TILE;   // two buffers each
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_bwd_dkv_bf16_kernel<DH>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dkv);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)attn_bwd_dq_bf16_kernel<DH>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds_dq);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<DH>, grid, block, lds, st, (const bf16_t*)qkv, (const bf16_t*)dout, lse,
+  hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<DH>, grid, block, lds_dkv, st, (const bf16_t*)qkv, (const bf16_t*)dout,
+                     lse, Dsum, (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale, (int32_t)nblk, (int32_t)n_wg);
+  hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<DH>, grid, block, lds_dq, st, (const bf16_t*)qkv, (const bf16_t*)dout, lse,
                      Dsum, (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale, (int32_t)nblk, (int32_t)n_wg);
-  hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<DH>, grid, block, 0, st, (const bf16_t*)qkv, (const bf16_t*)dout, lse, Dsum,
-                     (bf16_t*)dqkv, S, h, causal, scale * LOG2E_B, scale, (int32_t)nblk, (int32_t)n_wg);
   return hipGetLastError();
 }
 
