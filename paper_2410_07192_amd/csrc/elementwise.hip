@@ -26,14 +26,30 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
+  // every load of the wave is issued up front and stays raw until it is needed (x first, then gain and bias,
+  // which the statistics leave time to arrive); a group of 8 columns past the end reads column 0 and is not used
+  typedef typename Raw8<T>::type raw_t;
   const T* xr = x + row * d;
+  raw_t xraw[ITER], graw[ITER], braw[ITER];
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) {
+    const int c = (i * 64 + lane) * 8;
+    xraw[i] = *(const raw_t*)(xr + (c < d ? c : 0));
+  }
+#pragma unroll
+  for (int i = 0; i < ITER; ++i) {
+    const int c = (i * 64 + lane) * 8;
+    graw[i] = *(const raw_t*)(g + (c < d ? c : 0));
+    braw[i] = *(const raw_t*)(b + (c < d ? c : 0));
+  }
+  __builtin_amdgcn_sched_barrier(0);   // nothing that waits for the first load moves above the last one
   float v[ITER][8];
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     const int c = (i * 64 + lane) * 8;
+    unpack8(xraw[i], v[i]);
     if (c < d) {
-      load8(xr + c, v[i]);
 #pragma unroll
       for (int j = 0; j < 8; ++j) s += v[i][j];
     }
@@ -60,10 +76,10 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     const int c = (i * 64 + lane) * 8;
+    float gg[8], bb[8], o[8];
+    unpack8(graw[i], gg);
+    unpack8(braw[i], bb);
     if (c < d) {
-      float gg[8], bb[8], o[8];
-      load8(g + c, gg);
-      load8(b + c, bb);
 #pragma unroll
       for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * gg[j] + bb[j];
       store8(yr + c, o);

@@ -100,6 +100,23 @@ __device__ __forceinline__ void store8(bf16_t* p, const float v[8]) {
   *(uint4*)p = t;
 }
 
+// Eight consecutive elements as they come from memory (a first-class vector, so that a load can stay in
+// flight until the values are needed), and their conversion to float.
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> { typedef uint32_t type __attribute__((ext_vector_type(4))); };
+template <> struct Raw8<float> { typedef float type __attribute__((ext_vector_type(8))); };
+__device__ __forceinline__ void unpack8(const Raw8<bf16_t>::type& r, float v[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    v[2 * i] = bf16_bits_to_f32(r[i] & 0xffffu);
+    v[2 * i + 1] = bf16_bits_to_f32(r[i] >> 16);
+  }
+}
+__device__ __forceinline__ void unpack8(const Raw8<float>::type& r, float v[8]) {
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = r[i];
+}
+
 // erf by the rational approximation 7.1.26 of Abramowitz & Stegun (absolute error <= 1.5e-7, far
 // below the fp32 tolerance of the layer): one exp, one reciprocal and five FMAs instead of the
 // library routine, which would otherwise dominate the FFN epilogue.

@@ -137,29 +137,32 @@ __global__ __launch_bounds__(256) void colsum_bf16_vec_kernel(const bf16_t* __re
 // reduced (wave shuffle, then through LDS across the waves: one barrier per row, the LDS slots alternate).
 // Each workgroup writes one partial row to `partial` ([workgroups][2][d]) and a second kernel sums the rows
 // in a fixed order (deterministic) into dg / db.
-template <typename T, int NW, int ITER>
+template <typename T, int NW, int ITER, bool HAS_RESID>
 __global__ __launch_bounds__(64 * NW) void layernorm_bwd_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                                 const T* __restrict__ g, const float* __restrict__ mean,
                                                                 const float* __restrict__ rstd, const T* resid, T* dx,
                                                                 float* __restrict__ partial, int64_t rows, int32_t d) {
+  typedef typename Raw8<T>::type raw_t;
   __shared__ float red[2][NW][2];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
-  float pg[ITER][8], pb[ITER][8], gg[ITER][8], xn[ITER][8], dn[ITER][8];
+  float pg[ITER][8], pb[ITER][8], gg[ITER][8];
+  int cc[ITER];   // column of group i, or 0 for a group past the end (loaded like the others, never used)
 #pragma unroll
   for (int i = 0; i < ITER; ++i) {
     const int c = (i * 64 * NW + t) * 8;
+    cc[i] = c < d ? c : 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) pg[i][j] = pb[i][j] = gg[i][j] = xn[i][j] = dn[i][j] = 0.f;
-    if (c < d) load8(g + c, gg[i]);
+    for (int j = 0; j < 8; ++j) pg[i][j] = pb[i][j] = 0.f;
+    load8(g + cc[i], gg[i]);
   }
+  // the next row's x and dy stay raw in registers while this row is reduced: converting them on arrival would
+  // put the wait for the load right behind it
+  raw_t xr[ITER], dr[ITER];
   auto fetch = [&](int64_t r) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int c = (i * 64 * NW + t) * 8;
-      if (c < d) {
-        load8(x + r * d + c, xn[i]);
-        load8(dy + r * d + c, dn[i]);
-      }
+      xr[i] = *(const raw_t*)(x + r * d + cc[i]);
+      dr[i] = *(const raw_t*)(dy + r * d + cc[i]);
     }
   };
   int64_t row = blockIdx.x;
@@ -167,22 +170,21 @@ __global__ __launch_bounds__(64 * NW) void layernorm_bwd_kernel(const T* __restr
   int par = 0;
   for (; row < rows; row += gridDim.x) {
     const float mu = mean[row], rs = rstd[row];
-    float xh[ITER][8], dv[ITER][8], rr[ITER][8];
+    float xh[ITER][8], dv[ITER][8];
 #pragma unroll
-    for (int i = 0; i < ITER; ++i)
+    for (int i = 0; i < ITER; ++i) {
+      unpack8(xr[i], xh[i]);
+      unpack8(dr[i], dv[i]);
+    }
+    // requested in the order they are needed: the residual (at the end of this row), then the next row
+    raw_t rres[HAS_RESID ? ITER : 1];
+    if constexpr (HAS_RESID) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        xh[i][j] = xn[i][j];
-        dv[i][j] = dn[i][j];
-        rr[i][j] = 0.f;
-      }
-    if (row + gridDim.x < rows) fetch(row + gridDim.x);
-    if (resid) {
-#pragma unroll
-      for (int i = 0; i < ITER; ++i) {
-        const int c = (i * 64 * NW + t) * 8;
-        if (c < d) load8(resid + row * d + c, rr[i]);
-      }
+      for (int i = 0; i < ITER; ++i) rres[i] = *(const raw_t*)(resid + row * d + cc[i]);
+    }
+    {
+      const int64_t nxt = row + gridDim.x;
+      fetch(nxt < rows ? nxt : row);   // the last row is asked for once more rather than branched around
     }
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
@@ -221,10 +223,12 @@ __global__ __launch_bounds__(64 * NW) void layernorm_bwd_kernel(const T* __restr
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
       const int c = (i * 64 * NW + t) * 8;
+      float rr[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if constexpr (HAS_RESID) unpack8(rres[i], rr);
       if (c < d) {
         float o[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (dv[i][j] - s1 - xh[i][j] * s2) * rs + rr[i][j];
+        for (int j = 0; j < 8; ++j) o[j] = (dv[i][j] - s1 - xh[i][j] * s2) * rs + rr[j];
         store8(dx + row * d + c, o);
       }
     }
@@ -240,25 +244,27 @@ __global__ __launch_bounds__(64 * NW) void layernorm_bwd_kernel(const T* __restr
   }
 }
 
-// dg[c] / db[c] += sum over rows of partial[row][c]  (partial is [n_rows][2*d]).  64 columns per
-// workgroup, 16 row lanes per column, fixed summation order (deterministic).
+// dg[c] / db[c] += sum over rows of partial[row][c]  (partial is [n_rows][2*d]).  16 columns per workgroup
+// (64 bytes of a row per 16 lanes), 64 row lanes per column, fixed summation order (deterministic).
 __global__ __launch_bounds__(1024) void reduce_rows_add_kernel(const float* __restrict__ partial, float* __restrict__ dg,
                                                                float* __restrict__ db, int32_t n_rows, int32_t d) {
-  __shared__ float red[16][64];
-  const int cx = threadIdx.x & 63, ry = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cx;
+  __shared__ float red[64][17];
+  const int cx = threadIdx.x & 15, ry = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + cx;
+  const int cl = c < 2 * d ? c : 0;   // a column past the end reads column 0 and is dropped below
   float s = 0.f;
-  if (c < 2 * d)
-    for (int r = ry; r < n_rows; r += 16) s += partial[(int64_t)r * 2 * d + c];
+#pragma unroll 4
+  for (int r = ry; r < n_rows; r += 64) s += partial[(int64_t)r * 2 * d + cl];
   red[ry][cx] = s;
   __syncthreads();
   if (ry == 0 && c < 2 * d) {
     float t = 0.f;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) t += red[k][cx];
+    for (int k = 0; k < 64; ++k) t += red[k][cx];
     if (c < d) dg[c] += t;
     else db[c - d] += t;
   }
+}
 }
 
 // ---- attention backward, one thread per row ----------------------------------------------------------
@@ -626,9 +632,15 @@ static hipError_t launch_ln_bwd(const void* dy, const void* x, const void* g, co
   int64_t blocks = rows;
   if (blocks > LN_BWD_MAX_BLOCKS * 4) blocks = LN_BWD_MAX_BLOCKS * 4;   // rows of `partial`
   const dim3 grid((unsigned)blocks);
-#define PF_LNB(NW, I)                                                                                                   \
-  hipLaunchKernelGGL((layernorm_bwd_kernel<T, NW, I>), grid, dim3(64 * NW), 0, st, (const T*)dy, (const T*)x, (const T*)g, \
-                     mean, rstd, (const T*)resid, (T*)dx, partial, rows, d)
+#define PF_LNB(NW, I)                                                                                            \
+  do {                                                                                                           \
+    if (resid)                                                                                                   \
+      hipLaunchKernelGGL((layernorm_bwd_kernel<T, NW, I, true>), grid, dim3(64 * NW), 0, st, (const T*)dy,       \
+                         (const T*)x, (const T*)g, mean, rstd, (const T*)resid, (T*)dx, partial, rows, d);       \
+    else                                                                                                         \
+      hipLaunchKernelGGL((layernorm_bwd_kernel<T, NW, I, false>), grid, dim3(64 * NW), 0, st, (const T*)dy,      \
+                         (const T*)x, (const T*)g, mean, rstd, (const T*)resid, (T*)dx, partial, rows, d);       \
+  } while (0)
   if (d <= 512) PF_LNB(1, 1);
   else if (d <= 1024) PF_LNB(2, 1);
   else if (d <= 2048) PF_LNB(4, 1);
@@ -636,7 +648,7 @@ static hipError_t launch_ln_bwd(const void* dy, const void* x, const void* g, co
   else if (d <= 8192) PF_LNB(4, 4);
   else return hipErrorInvalidValue;
 #undef PF_LNB
-  hipLaunchKernelGGL(reduce_rows_add_kernel, dim3((unsigned)((2 * d + 63) / 64)), dim3(1024), 0, st, partial, dg, db,
+  hipLaunchKernelGGL(reduce_rows_add_kernel, dim3((unsigned)((2 * d + 15) / 16)), dim3(1024), 0, st, partial, dg, db,
                      (int32_t)blocks, d);
   return hipGetLastError();
 }

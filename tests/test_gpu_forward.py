@@ -211,7 +211,8 @@ def test_layernorm_with_a_range_to_warm(offset, nbytes):
 
 
 ATT_CASES = [("bf16", 2, 200, 3, 64), ("bf16", 1, 513, 2, 128), ("bf16", 3, 64, 2, 64), ("bf16", 2, 50, 2, 16),
-             ("f32", 2, 128, 4, 64), ("f32", 2, 77, 2, 8), ("f32", 1, 130, 1, 128), ("bf16", 1, 1, 1, 64)]
+             ("f32", 2, 128, 4, 64), ("f32", 2, 77, 2, 8), ("f32", 1, 130, 1, 128), ("bf16", 1, 1, 1, 64),
+             ("bf16", 2, 65, 1, 64), ("bf16", 1, 129, 1, 128)]
 
 
 @pytest.mark.parametrize("causal", [False, True])

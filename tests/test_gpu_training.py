@@ -339,8 +339,11 @@ def test_main_offload_argument_errors():
         m.close()
 
 
+# the MFMA kernels (bf16, d_head 64 / 128) walk tiles of 64 rows in blocks of 128: one row, one tile, one row more
+# than a tile, a ragged multiple of the block; the other cases run on the generic kernels
 ATT_BWD = [("bf16", 2, 200, 3, 64), ("bf16", 1, 321, 2, 128), ("bf16", 2, 64, 2, 64), ("bf16", 1, 130, 2, 16),
-           ("f32", 2, 100, 2, 32), ("f32", 1, 70, 1, 64)]
+           ("f32", 2, 100, 2, 32), ("f32", 1, 70, 1, 64), ("bf16", 1, 1, 1, 64), ("bf16", 1, 65, 1, 128),
+           ("bf16", 1, 129, 2, 64)]
 
 
 @pytest.mark.parametrize("causal", [False, True])
