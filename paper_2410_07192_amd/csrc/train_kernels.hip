@@ -253,18 +253,37 @@ __global__ __launch_bounds__(1024) void reduce_rows_add_kernel(const float* __re
   const int c = blockIdx.x * 16 + cx;
   const int cl = c < 2 * d ? c : 0;   // a column past the end reads column 0 and is dropped below
   float s = 0.f;
-#pragma unroll 4
-  for (int r = ry; r < n_rows; r += 64) s += partial[(int64_t)r * 2 * d + cl];
+  // eight rows per round, all requested before the first is added (a row past the end repeats the last one with
+  // weight 0): one memory round trip for the 512 rows the LayerNorm kernel writes at most
+  for (int r0 = ry; r0 < n_rows; r0 += 8 * 64) {
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int r = r0 + 64 * k;
+      v[k] = partial[(int64_t)(r < n_rows ? r : n_rows - 1) * 2 * d + cl];
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) s += (r0 + 64 * k < n_rows) ? v[k] : 0.f;
+  }
   red[ry][cx] = s;
   __syncthreads();
-  if (ry == 0 && c < 2 * d) {
-    float t = 0.f;
+  // fixed order: 16 lanes per column add four rows each, then lane 0 adds the sixteen
+  const int col = threadIdx.x >> 4, part = threadIdx.x & 15;   // threads 0..255: column col, rows 4 part .. 4 part + 3
+  float t = 0.f;
+  if (threadIdx.x < 256) t = (red[4 * part][col] + red[4 * part + 1][col]) + (red[4 * part + 2][col] + red[4 * part + 3][col]);
+  __syncthreads();
+  if (threadIdx.x < 256) red[part][col] = t;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    const int cc = blockIdx.x * 16 + threadIdx.x;
+    float u = 0.f;
 #pragma unroll
-    for (int k = 0; k < 64; ++k) t += red[k][cx];
-    if (c < d) dg[c] += t;
-    else db[c - d] += t;
+    for (int k = 0; k < 16; ++k) u += red[k][threadIdx.x];
+    if (cc < 2 * d) {
+      if (cc < d) dg[cc] += u;
+      else db[cc - d] += u;
+    }
   }
-}
 }
 
 // ---- attention backward, one thread per row ----------------------------------------------------------
