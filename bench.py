@@ -273,7 +273,13 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     windows = [dict(start=bubble_ns // 2, dur=bubble_ns, free=cap, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
     for mdl in models:
         mdl.ctx.pf_profile_chain(mdl.chain, 1, 3, fill.cuda_stream)
-    cfgs = [dict(F=mdl.chain, samples=mdl.cfg.g * shape.batch) for mdl in models]
+    # The same job follows itself (the Executor partitions the next batch from what is left of the bubble in which
+    # one completes), so the configurations are compared on a run of back-to-back batches that covers at least
+    # eight bubbles, not on one batch, whose last bubble a single plan would count as full.
+    usable = max(1, bubble_ns * args.fill_ppm // 1_000_000 - args.switch_ns)
+    runs = [max(1, -(-8 * usable // max(1, sum(n.dur_ns for n in mdl.chain)))) for mdl in models]
+    as_tuples = lambda chain: [(n.dur_ns, n.mem_bytes, n.op, n.layer, n.mb_first, n.mb_count) for n in chain]
+    cfgs = [dict(F=as_tuples(mdl.chain) * r, samples=mdl.cfg.g * shape.batch * r) for mdl, r in zip(models, runs)]
     best, rep, cyc, chk = pf.pf_select_config(windows, cfgs, args.fill_ppm, args.switch_ns, 0)
     if best < 0:
         raise RuntimeError(f"no configuration of the streamed job fits the {args.bubble_ms} ms / {args.cap_gib} GiB bubbles")
@@ -317,7 +323,7 @@ def run_cfg3(args, np, torch, pf, dev, synth):
                                f"{args.cap_gib:g} GiB cap",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
                    "microbatches_per_layer_visit": g,
-                   "candidates": {f"g={m_.cfg.g}": {"replicas": rep[i], "cycles": cyc[i],
+                   "candidates": {f"g={m_.cfg.g}": {"batches": rep[i] * runs[i], "bubbles": cyc[i],
                                                      "chain_ms": sum(n.dur_ns for n in m_.chain) * 1e-6}
                                   for i, m_ in enumerate(models)}},
         **fill_stats(agg), "main_slowdown_pct": None,

@@ -46,8 +46,9 @@ def main():
             run_point("fill_fraction", "fill_ppm", ppm, ["--workload", "cfg5", "--fill-ppm", str(ppm), "--steps", "2",
                                                           "--warmup", "1"])
     if "bubble" in which:    # streamed fill job (cfg3) in explicit bubbles of growing size
-        for ms in (5, 10, 20, 40, 80, 160):
-            run_point("bubble_size", "bubble_ms", ms, ["--workload", "cfg3", "--bubble-ms", str(ms), "--steps", "20"])
+        for ms in (5, 10, 20, 40, 80, 160):   # at least 20 bubbles and 3.2 s of them: a batch spans several small ones
+            run_point("bubble_size", "bubble_ms", ms, ["--workload", "cfg3", "--bubble-ms", str(ms), "--steps",
+                                                        str(max(20, 3200 // ms))])
     if "memory" in which:    # the same job with less and less free memory
         for gib in (1, 2, 3, 4, 6, 8):
             run_point("free_memory", "cap_gib", gib, ["--workload", "cfg3", "--cap-gib", str(gib), "--steps", "20"])
