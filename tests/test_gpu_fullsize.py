@@ -132,6 +132,37 @@ def test_weight_gradient_gemm_full_shapes(M, N, K):
     assert np.abs(cs.cpu().numpy() - cref).max() <= 5e-5 * float(A.double().abs().sum(dim=0).max())
 
 
+@pytest.mark.parametrize("B,S,h,dh", [(8, 1024, 16, 64), (16, 1024, 16, 128), (1, 2048, 64, 128)])
+def test_attention_full_shapes_sampled_heads(B, S, h, dh):
+    """Causal attention forward and backward at the shapes of the training fill job, of the streamed decoder and of
+    the d=8192 main stage: three (sequence, head) pairs, all their rows, against float64."""
+    pf, dev = _mods()
+    d = h * dh
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(S + h + dh)
+    qkv = torch.randn(B, S, 3 * d, device="cuda", generator=gen).to(torch.bfloat16)
+    dout = torch.randn(B, S, d, device="cuda", generator=gen).to(torch.bfloat16)
+    out = torch.empty(B, S, d, device="cuda", dtype=torch.bfloat16)
+    dqkv = torch.empty_like(qkv)
+    lse = torch.empty(B, h, S, device="cuda", dtype=torch.float32)
+    dsum = torch.empty_like(lse)
+    pf.pf_op_attention(pf.PF_DTYPE_BF16, qkv.data_ptr(), out.data_ptr(), B, S, h, dh, True, lse.data_ptr())
+    pf.pf_op_attention_bwd(pf.PF_DTYPE_BF16, qkv.data_ptr(), out.data_ptr(), dout.data_ptr(), lse.data_ptr(),
+                           dsum.data_ptr(), dqkv.data_ptr(), B, S, h, dh, True)
+    torch.cuda.synchronize()
+    for bi, hi in {(0, 0), (B // 2, h // 2 + 1), (B - 1, h - 1)}:
+        sl = lambda t, part: t[bi, :, part * d + hi * dh:part * d + (hi + 1) * dh].float().cpu().numpy().astype(np.float64)
+        q, k, v = (sl(qkv, i)[None, None] for i in range(3))
+        do = dout[bi, :, hi * dh:(hi + 1) * dh].float().cpu().numpy().astype(np.float64)[None, None]
+        A = ot.attention_probs(q, k, True)
+        assert rel_err(out[bi, :, hi * dh:(hi + 1) * dh].float().cpu().numpy(), (A @ v)[0, 0]) < 1e-2
+        dA = do @ v.transpose(0, 1, 3, 2)
+        ds = A * (dA - (dA * A).sum(-1, keepdims=True))
+        refs = (ds @ k / np.sqrt(dh), ds.transpose(0, 1, 3, 2) @ q / np.sqrt(dh), A.transpose(0, 1, 3, 2) @ do)
+        for i, ref in enumerate(refs):
+            assert rel_err(sl(dqkv, i), ref[0, 0]) < 2e-2, (bi, hi, "qkv"[i])
+
+
 def test_explicit_bubble_cycle_timeline():
     """Explicit windows (p = 0): chunks run only inside the given windows, plans are cyclic, results of
     completed replicas match the checker, and the configuration choice agrees with the checker."""
