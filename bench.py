@@ -37,6 +37,11 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+# The run keeps more than four streams alive (fill, main, the contexts' copy streams, the offload and deadline
+# streams); HIP's default of four hardware queues per process would make some of them share a queue, and a weight
+# copy then waits behind the kernels it is meant to overlap.  Read when the HIP runtime is loaded (before torch is imported).
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "4") or 4) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
 
 BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E peak

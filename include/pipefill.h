@@ -19,6 +19,12 @@
  *   - streams are hipStream_t values passed as void* (NULL = the null stream).  Calls that take
  *     a stream enqueue work and return; only pf_ctx_sync, pf_profile_chain and pf_timeline_run
  *     wait for the device.
+ *   - a context with streamed weights creates one copy stream, one with main-job offload one more,
+ *     and pf_timeline_run one for its deadline stamps, next to the caller's fill and main streams.
+ *     HIP gives a process four hardware queues unless GPU_MAX_HW_QUEUES says otherwise (read when
+ *     the HIP runtime is loaded); streams beyond that share a queue, and a weight copy that shares
+ *     the fill stream's queue waits behind the kernels it is meant to overlap (measured: a layer
+ *     visit 1.7 ms longer, the whole copy).  Run with GPU_MAX_HW_QUEUES=8 or more.
  *   - a missing or failing GPU is an error (PF_ERR_HIP); there is no CPU fallback.
  */
 #ifndef PIPEFILL_H

@@ -11,6 +11,13 @@ import os
 
 import numpy as np
 
+# A context with streamed weights, offload or the timeline loop creates streams of its own next to the caller's;
+# with HIP's default of four hardware queues per process some of them would share a queue and a copy would wait
+# behind the kernels it is meant to overlap.  Only effective if the HIP runtime is not loaded yet (import this
+# module, or set the variable, before torch).
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "4") or 4) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpipefill.so")
 

@@ -3,6 +3,9 @@ import sys
 
 import pytest
 
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "4") or 4) < 8:   # before torch is imported: see paper_2410_07192_amd/binding.py
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
