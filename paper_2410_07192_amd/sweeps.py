@@ -43,7 +43,7 @@ def main():
     which = set(args.which.split(","))
     if "fill" in which:      # real main-stage kernels (cfg5) with the streamed fill job inside its bubbles
         for ppm in (300_000, 500_000, 680_000, 800_000, 900_000, 980_000):
-            run_point("fill_fraction", "fill_ppm", ppm, ["--workload", "cfg5", "--fill-ppm", str(ppm), "--steps", "2",
+            run_point("fill_fraction", "fill_ppm", ppm, ["--workload", "cfg5", "--fill-ppm", str(ppm), "--steps", "4",
                                                           "--warmup", "1"])
     if "bubble" in which:    # streamed fill job (cfg3) in explicit bubbles of growing size
         for ms in (5, 10, 20, 40, 80, 160):   # at least 20 bubbles and 3.2 s of them: a batch spans several small ones
@@ -55,7 +55,7 @@ def main():
     if "offload" in which:   # cfg5 with 1 GiB free: the fill job only fits the windows that the offload enlarges
         for ms in (10, 25, 50, 100, 200, 400):
             run_point("main_offload", "sync_ms", ms, ["--workload", "cfg5", "--main-offload", "--cap-gib", "1", "--sync-ms",
-                                                       str(ms), "--steps", "2", "--warmup", "1"])
+                                                       str(ms), "--steps", "4", "--warmup", "1"])
 
 
 if __name__ == "__main__":
