@@ -22,11 +22,6 @@ namespace {
 
 constexpr float LOG2E_B = 1.4426950408889634f;
 
-template <int CPR>
-__device__ __forceinline__ int swz(int r, int c) {
-  return (CPR == 8) ? (c ^ ((r >> 1) & 7)) : (c ^ (r & 15));
-}
-
 // D[b][h][q] = sum_j dO[q][j] * O[q][j]
 template <int DH>
 __global__ __launch_bounds__(256) void attn_bwd_prep_kernel(const bf16_t* __restrict__ o, const bf16_t* __restrict__ dout,
