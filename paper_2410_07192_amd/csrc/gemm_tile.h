@@ -144,6 +144,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   constexpr int STAGE = (BM + BN) * 8;                          // uint4 per LDS stage
   static_assert(G % NW == 0 && GPW <= 32, "tile / wave mismatch");
   extern __shared__ uint4 smem[];
+  // GELU for bf16 results by table: h(x) = gelu(x) - max(x, 0) is bounded and vanishes at both ends; 1024 segments
+  // of 1/64 on [-8, 8), value and slope per segment, linear interpolation (error below 2.5e-5, a hundredth of a bf16
+  // ulp at 1).  Every workgroup builds its copy behind the two stages; the K loop's barriers publish it.
+  constexpr bool GELU_TAB = std::is_same<OutT, bf16_t>::value && (EPI & E_GELU) && !(EPI & E_ACC);
+  float2* gelu_tab = (float2*)(smem + 2 * STAGE);
+  if constexpr (GELU_TAB) {
+    for (int e = threadIdx.x; e < 1024; e += 64 * NW) {
+      const float x0 = -8.0f + (float)e * (1.0f / 64.0f), x1 = x0 + 1.0f / 64.0f;
+      const float h0 = gelu_f(x0) - fmaxf(x0, 0.f), h1 = gelu_f(x1) - fmaxf(x1, 0.f);
+      gelu_tab[e] = make_float2(h0, h1 - h0);
+    }
+  }
 
   const int64_t tile = xcd_contiguous(blockIdx.x, (int64_t)tiles_m * tiles_n);
   const int64_t per_group = (int64_t)group_m * tiles_n;
@@ -383,7 +395,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
               }
               if constexpr (decltype(with_gelu)::value) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
+                for (int j = 0; j < 4; ++j) {
+                  const float u = __builtin_amdgcn_fmed3f(fmaf(v[j], 64.0f, 512.0f), 0.0f, 1023.996f);
+                  const float2 e = gelu_tab[(int)u];
+                  v[j] = fmaxf(v[j], 0.f) + fmaf(e.y, __builtin_amdgcn_fractf(u), e.x);
+                }
               }
               uint2 pk;
               pk.x = pack_bf16x2(v[0], v[1]);
@@ -486,7 +502,7 @@ template <typename OutT, typename Kern>
 hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, const void* X, const void* W, void* C,
                         int64_t M, int64_t N, int64_t K, const EpiDev& ep, int32_t splits, hipStream_t stream) {
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  const size_t lds = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
+  const size_t lds = (size_t)2 * (BM + BN) * 8 * sizeof(uint4) + 8192;   // two stages + the GELU table
   if (!*attr_set) {   // raise the dynamic-LDS limit once per instantiation
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
