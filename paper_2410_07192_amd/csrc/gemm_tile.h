@@ -156,6 +156,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
       gelu_tab[e] = make_float2(h0, h1 - h0);
     }
   }
+  // the same for GELU' (between -0.13 and 1.13, 0 and 1 beyond the ends), where the saved pre-activation is bf16
+  constexpr bool GRAD_TAB = std::is_same<OutT, bf16_t>::value && EPI == E_DACT;
+  if constexpr (GRAD_TAB) {
+    for (int e = threadIdx.x; e < 1024; e += 64 * NW) {
+      const float x0 = -8.0f + (float)e * (1.0f / 64.0f);
+      const float d0 = gelu_grad_f(x0), d1 = gelu_grad_f(x0 + 1.0f / 64.0f);
+      gelu_tab[e] = make_float2(d0, d1 - d0);
+    }
+  }
+  auto gelu_grad_tab = [&](float x) {
+    const float u = __builtin_amdgcn_fmed3f(fmaf(x, 64.0f, 512.0f), 0.0f, 1023.996f);
+    const float2 e = gelu_tab[(int)u];
+    return fmaf(e.y, __builtin_amdgcn_fractf(u), e.x);
+  };
 
   const int64_t tile = xcd_contiguous(blockIdx.x, (int64_t)tiles_m * tiles_n);
   const int64_t per_group = (int64_t)group_m * tiles_n;
@@ -365,10 +379,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
             static_for<0, 4>([&](auto rg) {
               const int slot = (wn * TN + a) * 4 + rg;
               const uint2 u = st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk];
-              acc[a][b][rg * 4 + 0] *= gelu_grad_f(bf16_bits_to_f32(u.x & 0xffffu));
-              acc[a][b][rg * 4 + 1] *= gelu_grad_f(bf16_bits_to_f32(u.x >> 16));
-              acc[a][b][rg * 4 + 2] *= gelu_grad_f(bf16_bits_to_f32(u.y & 0xffffu));
-              acc[a][b][rg * 4 + 3] *= gelu_grad_f(bf16_bits_to_f32(u.y >> 16));
+              acc[a][b][rg * 4 + 0] *= gelu_grad_tab(bf16_bits_to_f32(u.x & 0xffffu));
+              acc[a][b][rg * 4 + 1] *= gelu_grad_tab(bf16_bits_to_f32(u.x >> 16));
+              acc[a][b][rg * 4 + 2] *= gelu_grad_tab(bf16_bits_to_f32(u.y & 0xffffu));
+              acc[a][b][rg * 4 + 3] *= gelu_grad_tab(bf16_bits_to_f32(u.y >> 16));
             });
           });
         });
