@@ -346,3 +346,11 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert out.returncode != 0 and "ONE GPU" in out.stderr and out.stdout.strip() == ""
+
+
+def test_binding_asks_for_more_hardware_queues():
+    """Streams beyond HIP's default of four hardware queues share a queue and a weight copy then waits behind the
+    kernels it should overlap: the binding (and conftest, before torch is imported) raise the count to eight."""
+    import os
+    from paper_2410_07192_amd import binding  # noqa: F401
+    assert int(os.environ["GPU_MAX_HW_QUEUES"]) >= 8
