@@ -271,6 +271,20 @@ def make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4), n_slots=3):
     return shape, models
 
 
+def choose_streamed_config(pf, windows, chains, samples, bubble_ns, fill_ppm, switch_ns):
+    """Configuration (microbatches per layer visit) of the streamed job for a cycle of equal bubbles.  The same job
+    follows itself (the Executor partitions the next batch from what is left of the bubble in which one completes),
+    so the configurations are compared on a run of back-to-back batches that covers at least eight bubbles, not on
+    one batch, whose last bubble a single plan would count as full.  Returns (best index or -1, batches per run,
+    bubbles per run, batches in a run) with one entry per configuration."""
+    usable = max(1, bubble_ns * fill_ppm // 1_000_000 - switch_ns)
+    as_tuples = lambda chain: [(n.dur_ns, n.mem_bytes, n.op, n.layer, n.mb_first, n.mb_count) for n in chain]
+    runs = [max(1, -(-8 * usable // max(1, sum(n.dur_ns for n in ch)))) for ch in chains]
+    cfgs = [dict(F=as_tuples(ch) * r, samples=sm * r) for ch, sm, r in zip(chains, samples, runs)]
+    best, rep, cyc, _ = pf.pf_select_config(windows, cfgs, fill_ppm, switch_ns, 0)
+    return best, rep, cyc, runs
+
+
 def run_cfg3(args, np, torch, pf, dev, synth):
     shape, models = make_cfg3_models(torch, pf, dev, synth)
     fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
@@ -278,14 +292,9 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     windows = [dict(start=bubble_ns // 2, dur=bubble_ns, free=cap, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
     for mdl in models:
         mdl.ctx.pf_profile_chain(mdl.chain, 1, 3, fill.cuda_stream)
-    # The same job follows itself (the Executor partitions the next batch from what is left of the bubble in which
-    # one completes), so the configurations are compared on a run of back-to-back batches that covers at least
-    # eight bubbles, not on one batch, whose last bubble a single plan would count as full.
-    usable = max(1, bubble_ns * args.fill_ppm // 1_000_000 - args.switch_ns)
-    runs = [max(1, -(-8 * usable // max(1, sum(n.dur_ns for n in mdl.chain)))) for mdl in models]
-    as_tuples = lambda chain: [(n.dur_ns, n.mem_bytes, n.op, n.layer, n.mb_first, n.mb_count) for n in chain]
-    cfgs = [dict(F=as_tuples(mdl.chain) * r, samples=mdl.cfg.g * shape.batch * r) for mdl, r in zip(models, runs)]
-    best, rep, cyc, chk = pf.pf_select_config(windows, cfgs, args.fill_ppm, args.switch_ns, 0)
+    best, rep, cyc, runs = choose_streamed_config(pf, windows, [mdl.chain for mdl in models],
+                                                  [mdl.cfg.g * shape.batch for mdl in models], bubble_ns,
+                                                  args.fill_ppm, args.switch_ns)
     if best < 0:
         raise RuntimeError(f"no configuration of the streamed job fits the {args.bubble_ms} ms / {args.cap_gib} GiB bubbles")
     mdl = models[best]

@@ -354,3 +354,26 @@ def test_binding_asks_for_more_hardware_queues():
     import os
     from paper_2410_07192_amd import binding  # noqa: F401
     assert int(os.environ["GPU_MAX_HW_QUEUES"]) >= 8
+
+
+def test_streamed_configuration_is_chosen_on_a_run_of_batches():
+    """One batch of four microbatches in three 80 ms bubbles beats one single-microbatch batch per bubble when the
+    rest of that bubble counts as lost (Algorithm 1 on a single batch), although it is the slowest per token; on a
+    run of back-to-back batches, which is what the Executor executes, the fastest configuration wins."""
+    import collections
+    import bench
+    from paper_2410_07192_amd import binding as pf
+    Node = collections.namedtuple("Node", "dur_ns mem_bytes op layer mb_first mb_count")
+    def chain(layer_ns, g):
+        return [Node(layer_ns, 1 << 30, pf.PF_OP_LAYER_FWD, l, 0, g) for l in range(24)]
+    chains = [chain(1_750_000, 1), chain(3_370_000, 2), chain(8_800_000, 4)]       # 42, 81 and 211 ms per batch
+    samples = [16, 32, 64]
+    bubble = 80_000_000
+    windows = [dict(start=bubble // 2, dur=bubble, free=8 << 30, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
+    single = pf.pf_select_config(windows, [dict(F=[tuple(n) for n in c], samples=s) for c, s in zip(chains, samples)],
+                                 900_000, 100_000, 0)
+    assert single[0] == 2                                     # what a single-batch comparison picks
+    best, rep, cyc, runs = bench.choose_streamed_config(pf, windows, chains, samples, bubble, 900_000, 100_000)
+    assert best == 1                                          # 32 samples per 81 ms
+    rate = [s * r * k / c for s, r, k, c in zip(samples, runs, rep, cyc)]
+    assert rate[1] > rate[0] > rate[2]
