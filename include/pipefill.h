@@ -293,8 +293,12 @@ int32_t pf_ctx_set_io(pf_ctx* ctx, const void* in, int32_t n_in, void* out, int3
 /* Host->HBM prefetch of one layer blob (Sec. 4.5: parameters offloaded to CPU memory).  Enqueues
  * on copy_stream: wait until the last kernels that read `slot` have finished, copy layer
  * `layer` from pinned host memory into the slot, record the slot's ready event.  A later
- * LAYER_FWD of that layer on the fill stream waits for the event.  PF_ERR_STATE if the
- * configuration is not streamed. */
+ * LAYER_FWD of that layer on the fill stream waits for the event.  copy_stream NULL = the
+ * context's own copy stream (the one its automatic prefetch uses); with any other stream the copy
+ * also waits for an earlier copy into the same slot that was enqueued elsewhere.  The chunk
+ * runner finds the layer in the slot and does not copy it again; it goes on prefetching the
+ * layers that follow into the slots after `slot`.  PF_ERR_STATE if the configuration is not
+ * streamed, PF_ERR_ARG if layer or slot is out of range. */
 int32_t pf_load_layer_async(pf_ctx* ctx, int32_t layer, int32_t slot, void* copy_stream);
 
 /* Run one chunk's forward-type nodes (EMBED, LAYER_FWD, FINAL_LN, HEAD_LOSS) on fill_stream
@@ -320,7 +324,12 @@ int32_t pf_fill_chunk(pf_ctx* ctx, const pf_chunk* chunk, const pf_node* F, int3
 
 /* Measure dur_ns of every node of F (host, in/out) on this device: each node is run `reps`
  * times after `warmup` runs on `stream` and the median HIP-event time is stored (the
- * per-node profiles the Executor is handed, Sec. 4.3).  Synchronises the device. */
+ * per-node profiles the Executor is handed, Sec. 4.3).  Synchronises the device.
+ * The nodes really run, on input slot 0 of the ring: call it between jobs, with no replica in
+ * flight (carried hidden states, checkpoints and output slot 0 are overwritten).  On a training context the optimizer nodes run
+ * the Adam kernel with a zero step (parameters, moment estimates, step count, accumulated loss and
+ * gradient accumulators are the same after the call as before); PF_ERR_STATE if microbatches are
+ * accumulated towards an optimizer step when it is called. */
 int32_t pf_profile_chain(pf_ctx* ctx, pf_node* F, int32_t nF, int32_t warmup, int32_t reps,
                          void* stream);
 
@@ -331,6 +340,10 @@ int32_t pf_profile_chain(pf_ctx* ctx, pf_node* F, int32_t nF, int32_t warmup, in
  * for FWD; upstream gradient for BWD).  PF_INSTR_OPT: Adam update of all the stage's parameters
  * from the gradients accumulated over `index` microbatches (index >= 1; io is ignored and may be
  * NULL), working copies recast, accumulators cleared.  Enqueues on main_stream and returns.
+ * Microbatch `index` uses checkpoint slot index mod g of the context (g of its pf_exec_config), from
+ * its forward to its backward: the context needs g >= the number of microbatches the schedule keeps
+ * in flight on the stage (1F1B: min(p - stage, m)).  PF_ERR_STATE if a forward lands on a slot whose
+ * backward has not run, or a backward on a slot without a forward.
  * PF_INSTR_BUBBLE is handled by pf_timeline_run and is rejected here with PF_ERR_ARG. */
 int32_t pf_main_stage_step(pf_ctx* ctx, int32_t instr, int32_t index, const void* io,
                            void* main_stream);
@@ -389,7 +402,8 @@ int32_t pf_ctx_set_replan(pf_ctx* ctx, int32_t enable, int64_t fill_ppm, int64_t
  * (Sec. 4.2 signalling, Sec. 4.3 "Bubble synchronization and memory capping").
  * windows/nW: the stage's idle windows in time order (from pf_schedule_1f1b).  The stage's busy
  * periods between windows are real kernels when main_ctx != NULL (FWD/BWD of `main_io`,
- * issued in 1F1B order for p, m, stage) and timed waits of tf_ns / tb_ns otherwise.  At each fillable window the
+ * issued in 1F1B order for p, m, stage; PF_ERR_ARG if main_ctx has fewer checkpoint slots, g, than the
+ * min(p - stage, m) microbatches in flight) and timed waits of tf_ns / tb_ns otherwise.  At each fillable window the
  * next planned chunk plan[*cursor] whose bubble index equals the window is launched on
  * fill_stream with the window's free_bytes as cap, and the window is held open on the host for
  * its dur_ns.  fill_ctx may be NULL (no filling: the baseline for slowdown).  *cursor (host,

@@ -534,6 +534,7 @@ def pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial,
     _check(lib.pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream))
 
 
+
 def pf_op_gemm_tn(dtype, A, B, Cp, M, N, K, colsum_acc=None, stream=None):
     _check(lib.pf_op_gemm_tn(dtype, A, B, Cp, colsum_acc, M, N, K, stream))
 

@@ -61,11 +61,12 @@ hipError_t colsum_add(int32_t dtype, const void* x, float* acc, int64_t rows, in
 hipError_t transpose2d_colsum(int32_t dtype, const void* in, void* out, float* acc, int64_t R, int64_t C,
                               hipStream_t stream);
 // LayerNorm backward: dx = LN'(dy) (+ resid), dg += sum dy*xhat, db += sum dy.  dx may alias resid or dy.
-// partial: fp32 scratch of LN_BWD_MAX_BLOCKS * 4 * 2 * d elements.
+// partial: fp32 scratch of max_blocks * 2 * d elements (one partial dg | db row per workgroup; at most
+// LN_BWD_MAX_BLOCKS * 4 workgroups).
 constexpr int64_t LN_BWD_MAX_BLOCKS = 128;
 hipError_t layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
                          const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
-                         int64_t rows, int32_t d, hipStream_t stream);
+                         int64_t rows, int32_t d, hipStream_t stream, int64_t max_blocks = LN_BWD_MAX_BLOCKS * 4);
 // Attention backward from the saved log-sum-exp.  dqkv: [B*S][3*d] like qkv; Dsum: fp32 [B][h][S] scratch.
 hipError_t attention_bwd(int32_t dtype, const void* qkv, const void* o, const void* dout, const float* lse,
                          float* Dsum, void* dqkv, int32_t B, int32_t S, int32_t h, int32_t dh, int32_t causal,
@@ -80,8 +81,9 @@ hipError_t ce_loss_inplace(int32_t dtype, void* logits, const int32_t* ids, floa
 hipError_t embed_bwd(int32_t dtype, const void* dx, const int32_t* ids, float* dtok, float* dpos, int64_t tokens,
                      int32_t S, int32_t d, int32_t V, hipStream_t stream);
 // Adam with bias correction on fp32 arrays; g holds the sum over `accum` microbatches and is cleared.
+// dry: the same kernel with a zero step and unit decay factors, so theta, m and v keep their values (for profiling).
 hipError_t adam_update(float* theta, float* m, float* v, float* g, int64_t n, float lr, float b1, float b2, float eps,
-                       int64_t step, int32_t accum, hipStream_t stream);
+                       int64_t step, int32_t accum, hipStream_t stream, bool dry = false);
 // fp32 [R][C] -> dst [R][C] in `dtype` and, if dst_t is not null, dst_t [C][R]
 hipError_t cast_from_f32(int32_t dtype, const float* src, void* dst, void* dst_t, int64_t R, int64_t C,
                          hipStream_t stream);

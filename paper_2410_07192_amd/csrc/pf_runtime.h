@@ -46,6 +46,8 @@ struct TrainState {
   int64_t mb_accum = 0;                 // microbatches accumulated since the last optimizer step
   int64_t steps = 0;                    // optimizer steps taken
   int64_t loss_count = 0;               // HEAD_LOSS evaluations since the loss was last read
+  bool dry = false;                     // profiling: optimizer steps leave parameters, moments and the step count alone
+  std::vector<char> slot_live;          // emulated main stage: checkpoint slot holds a forward whose backward has not run
 };
 
 int64_t train_arena_bytes(const pf_model_desc& md, const pf_exec_config& cfg, const Layout& lay);
@@ -68,6 +70,10 @@ int32_t train_opt_state_copy(pf_ctx* c, int64_t off, int64_t len, char* host, bo
 int32_t train_opt_state_fill(pf_ctx* c, int64_t off, int64_t len, int32_t byte, hipStream_t st);
 // optimizer update of an emulated main stage after `microbatches` accumulated backward passes
 int32_t train_main_opt(pf_ctx* c, int32_t microbatches, hipStream_t st);
+// Brackets pf_profile_chain on a training context: begin refuses a context with microbatches accumulated, saves the
+// scalar state and switches optimizer steps to dry mode; end clears what the profiled nodes accumulated and restores it.
+int32_t train_profile_begin(pf_ctx* c, hipStream_t st);
+int32_t train_profile_end(pf_ctx* c, hipStream_t st);
 // Weights that a LayerNorm reads ahead for the GEMMs after it: worth it while they are small beside the
 // LayerNorm's own traffic and the cache they are meant to sit in; larger ranges are not warmed (returns 0).
 inline int64_t warm_bytes(int64_t n) { return n <= ((int64_t)12 << 20) ? n : 0; }
@@ -98,6 +104,7 @@ struct pf_ctx {
   std::vector<int32_t> slot_layer;
   std::vector<hipEvent_t> slot_ready, slot_free;
   std::vector<char> slot_free_valid;
+  std::vector<hipStream_t> slot_stream;   // stream the slot's last copy was enqueued on
   int32_t next_slot = 0;
   hipStream_t copy_stream = nullptr;
   // job io rings

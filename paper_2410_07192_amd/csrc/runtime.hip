@@ -180,6 +180,7 @@ int32_t pf_ctx_create(const pf_model_desc* model, const pf_exec_config* cfg, con
   if (e == hipSuccess && cfg->streamed) {
     c->slot_layer.assign(cfg->n_slots, -1);
     c->slot_free_valid.assign(cfg->n_slots, 0);
+    c->slot_stream.assign(cfg->n_slots, nullptr);
     c->slot_ready.resize(cfg->n_slots);
     c->slot_free.resize(cfg->n_slots);
     for (int32_t i = 0; i < cfg->n_slots && e == hipSuccess; ++i) {
@@ -231,10 +232,13 @@ int32_t pf_ctx_set_io(pf_ctx* c, const void* in, int32_t n_in, void* out, int32_
 // ---- weight streaming ---------------------------------------------------------------------------
 static int32_t load_into(pf_ctx* c, int32_t layer, int32_t slot, hipStream_t cs) {
   if (c->slot_free_valid[slot]) PF_HIP(hipStreamWaitEvent(cs, c->slot_free[slot], 0));
+  // an earlier copy into this slot that was enqueued on another stream must have landed first
+  if (c->slot_layer[slot] >= 0 && c->slot_stream[slot] != cs) PF_HIP(hipStreamWaitEvent(cs, c->slot_ready[slot], 0));
   PF_HIP(hipMemcpyAsync(c->slots + (int64_t)slot * c->lay.blob, c->layers[layer], (size_t)c->lay.blob,
                         hipMemcpyHostToDevice, cs));
   PF_HIP(hipEventRecord(c->slot_ready[slot], cs));
   c->slot_layer[slot] = layer;
+  c->slot_stream[slot] = cs;
   return PF_OK;
 }
 
@@ -516,10 +520,15 @@ int32_t pf_fill_chunk(pf_ctx* c, const pf_chunk* ch, const pf_node* F, int32_t n
 int32_t pf_profile_chain(pf_ctx* c, pf_node* F, int32_t nF, int32_t warmup, int32_t reps, void* stream) {
   if (!c || !F || nF <= 0 || warmup < 0 || reps <= 0) return pf::fail(PF_ERR_ARG, "pf_profile_chain: bad argument");
   hipStream_t st = (hipStream_t)stream;
+  if (c->tr) {
+    int32_t brc = pf::train_profile_begin(c, st);
+    if (brc != PF_OK) return brc;
+  }
   std::vector<hipEvent_t> ev(nF + 1, nullptr);
-  for (auto& e : ev) PF_HIP(hipEventCreate(&e));
-  std::vector<std::vector<float>> ms(nF);
   int32_t rc = PF_OK;
+  for (auto& e : ev)
+    if (rc == PF_OK && hipEventCreate(&e) != hipSuccess) rc = pf::fail(PF_ERR_HIP, "pf_profile_chain: hipEventCreate failed");
+  std::vector<std::vector<float>> ms(nF);
   const int64_t saved_base = c->replica_base;
   for (int32_t it = 0; it < warmup + reps && rc == PF_OK; ++it) {
     // the whole chain runs in order so that streamed configurations are measured with their
@@ -541,7 +550,11 @@ int32_t pf_profile_chain(pf_ctx* c, pf_node* F, int32_t nF, int32_t warmup, int3
       }
   }
   c->replica_base = saved_base;
-  for (auto& e : ev) (void)hipEventDestroy(e);
+  for (auto& e : ev) if (e) (void)hipEventDestroy(e);
+  if (c->tr) {
+    const int32_t erc = pf::train_profile_end(c, st);
+    if (rc == PF_OK) rc = erc;
+  }
   if (rc != PF_OK) return rc;
   for (int32_t i = 0; i < nF; ++i) {
     std::sort(ms[i].begin(), ms[i].end());
@@ -671,6 +684,9 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
       fwd_before = true;
     }
   }
+  if (mc && mc->cfg.g < std::min(p - stage, m))
+    return pf::fail(PF_ERR_ARG, "pf_timeline_run: stage %d of %d keeps %d microbatches in flight, the main context has "
+                    "checkpoint slots for %d", stage, p, std::min(p - stage, m), mc->cfg.g);
   const bool opt_phase = mc && mc->off.opt_phase;
   const bool offload = opt_phase && !mc->off.slices.empty();
   if (offload && (int32_t)mc->off.slices.size() != m)

@@ -144,6 +144,7 @@ int32_t train_create(pf_ctx* c, const pf_weights* w, char* base, hipStream_t st)
   std::memcpy(t.emb32_off, z.emb32_off, sizeof z.emb32_off);
   t.wt_bytes = z.wt;
   t.emb32 = z.emb32;
+  t.slot_live.assign((size_t)g, 0);
   char* p = base;
   auto take = [&](int64_t n) { char* r = p; p += n; return r; };
   for (int64_t l = 0; l < L; ++l) {
@@ -363,16 +364,17 @@ int32_t train_fwd_node(pf_ctx* c, const pf_node& n, int64_t replica, hipStream_t
 static int32_t optimizer_step(pf_ctx* c, hipStream_t st) {
   TrainState& t = *c->tr;
   const pf_adam& a = c->adam;
-  t.steps += 1;
+  const int64_t step = t.steps + 1;
+  if (!t.dry) t.steps = step;
   const int32_t accum = (int32_t)t.mb_accum;
   for (int64_t l = 0; l < c->md.n_layers; ++l) {
-    PF_HIP(adam_update(t.master[l], t.m[l], t.v[l], t.grad[l], t.blob32 / 4, a.lr, a.beta1, a.beta2, a.eps, t.steps,
-                       accum, st));
+    PF_HIP(adam_update(t.master[l], t.m[l], t.v[l], t.grad[l], t.blob32 / 4, a.lr, a.beta1, a.beta2, a.eps, step,
+                       accum, st, t.dry));
     int32_t rc = recast_layer(c, (int32_t)l, st);
     if (rc != PF_OK) return rc;
   }
   if (t.Vp) {
-    PF_HIP(adam_update(t.embM, t.embm, t.embv, t.embg, t.emb32 / 4, a.lr, a.beta1, a.beta2, a.eps, t.steps, accum, st));
+    PF_HIP(adam_update(t.embM, t.embm, t.embv, t.embg, t.emb32 / 4, a.lr, a.beta1, a.beta2, a.eps, step, accum, st, t.dry));
     int32_t rc = recast_emb(c, st);
     if (rc != PF_OK) return rc;
   }
@@ -417,6 +419,14 @@ int32_t train_main_step(pf_ctx* c, int32_t instr, int32_t index, const void* io,
   const int64_t act = c->lay.act, L = c->md.n_layers;
   const int32_t slot = index % c->cfg.g;
   char* ck0 = t.ckpt + (int64_t)slot * (L + 1) * act;
+  // A checkpoint slot serves one microbatch from its forward to its backward: a forward that lands on a slot still
+  // in use would overwrite checkpoints a later backward reads (the context has fewer slots than microbatches in flight).
+  if (instr == PF_INSTR_FWD && t.slot_live[slot])
+    return fail(PF_ERR_STATE, "pf_main_stage_step: forward %d needs checkpoint slot %d, whose backward has not run "
+                "(the context keeps g = %d microbatches in flight)", index, slot, c->cfg.g);
+  if (instr == PF_INSTR_BWD && !t.slot_live[slot])
+    return fail(PF_ERR_STATE, "pf_main_stage_step: backward %d has no forward in checkpoint slot %d", index, slot);
+  t.slot_live[slot] = instr == PF_INSTR_FWD;
   if (instr == PF_INSTR_FWD) {
     PF_HIP(hipMemcpyAsync(ck0, io, (size_t)act, hipMemcpyDeviceToDevice, st));
     for (int64_t l = 0; l < L; ++l) {
@@ -473,6 +483,38 @@ int32_t train_opt_state_fill(pf_ctx* c, int64_t off, int64_t len, int32_t byte, 
 int32_t train_main_opt(pf_ctx* c, int32_t microbatches, hipStream_t st) {
   c->tr->mb_accum = microbatches;
   return optimizer_step(c, st);
+}
+
+namespace {
+struct ProfileSave { int64_t steps, loss_count; float loss; };
+thread_local ProfileSave g_profile_save;
+}  // namespace
+
+int32_t train_profile_begin(pf_ctx* c, hipStream_t st) {
+  TrainState& t = *c->tr;
+  if (t.mb_accum != 0)
+    return fail(PF_ERR_STATE, "pf_profile_chain: %lld microbatches are accumulated; profile a training context between "
+                "optimizer steps", (long long)t.mb_accum);
+  PF_HIP(hipStreamSynchronize(st));
+  g_profile_save.steps = t.steps;
+  g_profile_save.loss_count = t.loss_count;
+  PF_HIP(hipMemcpy(&g_profile_save.loss, t.loss, sizeof(float), hipMemcpyDeviceToHost));
+  t.dry = true;
+  return PF_OK;
+}
+
+int32_t train_profile_end(pf_ctx* c, hipStream_t st) {
+  TrainState& t = *c->tr;
+  int32_t rc = PF_OK;
+  if (t.mb_accum != 0) rc = optimizer_step(c, st);   // dry: clears the gradients the profiled nodes left behind
+  t.dry = false;
+  t.mb_accum = 0;
+  t.steps = g_profile_save.steps;
+  t.loss_count = g_profile_save.loss_count;
+  if (rc != PF_OK) return rc;
+  PF_HIP(hipStreamSynchronize(st));
+  PF_HIP(hipMemcpy(t.loss, &g_profile_save.loss, sizeof(float), hipMemcpyHostToDevice));
+  return PF_OK;
 }
 
 int32_t train_read_params(pf_ctx* c, int32_t what, int32_t layer, void* dst, int64_t dst_bytes, hipStream_t st) {

@@ -6,6 +6,9 @@
 // version): 16-byte accesses where the layout allows, fp32 arithmetic, fp32 atomics for the
 // reductions over tokens (bias, LayerNorm scale/shift and embedding gradients), which makes those
 // sums order-dependent in the last bits.
+#include <mutex>
+
+#include "pf_internal.h"
 #include "pf_kernels.h"
 #include "pf_device.h"
 
@@ -647,9 +650,9 @@ hipError_t transpose2d_colsum(int32_t dtype, const void* in, void* out, float* a
 template <typename T>
 static hipError_t launch_ln_bwd(const void* dy, const void* x, const void* g, const float* mean, const float* rstd,
                                 const void* resid, void* dx, float* dg, float* db, float* partial, int64_t rows,
-                                int32_t d, hipStream_t st) {
+                                int32_t d, hipStream_t st, int64_t max_blocks) {
   int64_t blocks = rows;
-  if (blocks > LN_BWD_MAX_BLOCKS * 4) blocks = LN_BWD_MAX_BLOCKS * 4;   // rows of `partial`
+  if (blocks > max_blocks) blocks = max_blocks;   // rows of `partial`
   const dim3 grid((unsigned)blocks);
 #define PF_LNB(NW, I)                                                                                            \
   do {                                                                                                           \
@@ -674,11 +677,12 @@ static hipError_t launch_ln_bwd(const void* dy, const void* x, const void* g, co
 
 hipError_t layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
                          const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
-                         int64_t rows, int32_t d, hipStream_t st) {
-  if (rows <= 0 || d <= 0 || d % 8 != 0 || d > 8192 || !partial) return hipErrorInvalidValue;
+                         int64_t rows, int32_t d, hipStream_t st, int64_t max_blocks) {
+  if (rows <= 0 || d <= 0 || d % 8 != 0 || d > 8192 || !partial || max_blocks < 1 || max_blocks > LN_BWD_MAX_BLOCKS * 4)
+    return hipErrorInvalidValue;
   if (dtype == PF_DTYPE_BF16_)
-    return launch_ln_bwd<bf16_t>(dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, st);
-  return launch_ln_bwd<float>(dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, st);
+    return launch_ln_bwd<bf16_t>(dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, st, max_blocks);
+  return launch_ln_bwd<float>(dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, st, max_blocks);
 }
 
 template <typename T>
@@ -741,9 +745,13 @@ hipError_t embed_bwd(int32_t dtype, const void* dx, const int32_t* ids, float* d
 }
 
 hipError_t adam_update(float* theta, float* m, float* v, float* g, int64_t n, float lr, float b1, float b2, float eps,
-                       int64_t step, int32_t accum, hipStream_t st) {
+                       int64_t step, int32_t accum, hipStream_t st, bool dry) {
   if (n <= 0 || step < 1 || accum < 1) return hipErrorInvalidValue;
   const float bc1 = 1.f - powf(b1, (float)step), bc2 = 1.f - powf(b2, (float)step);
+  if (dry) {   // same loads, stores and arithmetic, but m, v and theta keep their values (finite gradients assumed): only g is cleared
+    lr = 0.f;
+    b1 = b2 = 1.f;
+  }
   hipLaunchKernelGGL(adam_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, theta, m, v, g, n, lr, b1, b2,
                      eps, bc1, bc2, 1.f / (float)accum);
   return hipGetLastError();
@@ -776,3 +784,4 @@ hipError_t widen_to_f32(int32_t dtype, const void* src, float* dst, int64_t n, h
 }
 
 }  // namespace pf
+

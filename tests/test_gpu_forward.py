@@ -364,6 +364,48 @@ def test_streamed_weights_and_microbatch_groups():
         assert rel_err(resident[i], _oracle_model(shape, params, ids[i])) < TOL["bf16"]
 
 
+@pytest.mark.parametrize("own_stream", [False, True], ids=["ctx-stream", "caller-stream"])
+def test_explicit_layer_loads_match_resident(own_stream):
+    """Layers brought in by explicit pf_load_layer_async calls (the context's copy stream, or a stream of the
+    caller's) before and between chunks: the streamed chunks find them in their slots and give the resident
+    configuration's result bit for bit, also when a caller-stream copy follows an automatic prefetch into the
+    same slot."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(5, 128, 2, 256, 96, 2, 400, True, "bf16")
+    params = synth.make_model_params(shape, seed=10)
+    g = 2
+    ids = np.stack([synth.make_token_ids(shape, seed=20 + i) for i in range(g)])
+    resident = _run_model(shape, params, ids, g=g)
+    n_slots = 3
+    m = dev.DeviceModel(shape, params, g=g, streamed=True, n_slots=n_slots)
+    try:
+        d_in = dev.to_device(ids.astype(np.int32))
+        d_out = dev.empty_storage((g, shape.batch, shape.seq_len, shape.d_model), m.md)
+        m.set_io(d_in, 1, d_out, 1)
+        st, cs = torch.cuda.Stream(), torch.cuda.Stream()
+        copy = cs.cuda_stream if own_stream else None
+        # before the first bubble: layers 0 and 1 wait in slots 0 and 1
+        m.ctx.pf_load_layer_async(0, 0, copy)
+        m.ctx.pf_load_layer_async(1, 1, copy)
+        m.ctx.pf_fill_chunk_fwd(m.chunk(0, 3), m.chain, stream=st.cuda_stream)      # embed, layers 0 and 1
+        # no synchronisation: the chunk's own prefetches (layers 2, 3) are in flight on the context's stream when
+        # the caller replaces what slot 0 will hold next; the copy must queue behind them and behind the kernels
+        m.ctx.pf_load_layer_async(4, 0, copy)
+        m.ctx.pf_fill_chunk_fwd(m.chunk(3, 5), m.chain, stream=st.cuda_stream)      # layers 2 and 3
+        m.ctx.pf_ctx_sync()
+        m.ctx.pf_fill_chunk_fwd(m.chunk(5, len(m.chain)), m.chain, stream=st.cuda_stream)   # layer 4, final LN
+        m.ctx.pf_ctx_sync()
+        assert np.array_equal(dev.read_storage(d_out, m.md), resident)
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_load_layer_async(5, 0, copy)
+        assert e.value.code == pf.PF_ERR_ARG
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_load_layer_async(0, n_slots, copy)
+        assert e.value.code == pf.PF_ERR_ARG
+    finally:
+        m.close()
+
+
 def test_chunk_error_paths_on_device():
     pf, dev = _mods()
     shape = SMALL[3]
@@ -419,7 +461,8 @@ def test_timeline_small():
             stats = pf.pf_timeline_run(m.ctx, None, None, p, mm, stage, tf, tb, windows, plan, n_plan, m.chain,
                                        cursor, st.cuda_stream, main.cuda_stream)
             assert stats["idle_ns"] == (p - 1) * (tf + tb)
-            assert stats["iter_ns"] == (mm + p - 1) * (tf + tb) - stage * tf + 0 * it or stats["iter_ns"] > 0
+            # a placeholder stage advances a scheduled clock: its forwards and backwards plus its idle windows
+            assert stats["iter_ns"] == (mm + p - 1) * (tf + tb)
             assert 0 < stats["fill_busy_ns"]
             total_rep += stats["replicas_done"]
         assert total_rep >= 1

@@ -145,6 +145,78 @@ def test_training_chunked_through_timeline():
         m.close()
 
 
+def test_profiling_leaves_training_state_alone():
+    """pf_profile_chain runs every node of a training chain, optimizer nodes included, and still leaves parameters,
+    moment estimates, gradient accumulators, step count and accumulated loss as they were; with microbatches
+    accumulated it refuses to run."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(2, 128, 2, 256, 64, 2, 300, True, "bf16")
+    params = synth.make_model_params(shape, seed=3, std=0.05)
+    m = dev.DeviceModel(shape, params, training=True, adam=pf.pf_adam(1e-2, 0.9, 0.999, 1e-8, 2))
+    try:
+        ids = np.stack([synth.make_token_ids(shape, seed=70 + i)[None] for i in range(2)])
+        m.set_io(dev.to_device(ids.astype(np.int32)), 2, None, 0)
+        st = torch.cuda.Stream()
+        nF = len(m.chain)
+        # one real optimizer step first (two microbatches), so the moments and the step count are not zero
+        for r in range(2):
+            m.ctx.pf_fill_chunk(pf.pf_chunk(0, 0, r * nF, (r + 1) * nF, 0, 0), m.chain, stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        before = [[read_layer(m, what, l) for l in range(shape.n_layers)] + [read_emb(m, what)] for what in range(4)]
+        m.ctx.pf_profile_chain(m.chain, 1, 3, st.cuda_stream)   # 4 passes: two dry optimizer steps
+        assert all(n.dur_ns > 0 for n in m.chain)
+        after = [[read_layer(m, what, l) for l in range(shape.n_layers)] + [read_emb(m, what)] for what in range(4)]
+        for what in range(4):
+            for a, b in zip(before[what], after[what]):
+                for k in a:
+                    assert np.array_equal(a[k], b[k]), (what, k)
+        loss, steps = m.ctx.pf_ctx_train_state()
+        assert steps == 1
+        assert abs(loss - np.log(shape.vocab)) < 1.0     # the mean over the two real microbatches, not over six
+        # one more microbatch is now accumulated towards a step of two: profiling must refuse
+        m.ctx.pf_fill_chunk(pf.pf_chunk(0, 0, 2 * nF, 3 * nF, 0, 0), m.chain, stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_profile_chain(m.chain, 0, 1, st.cuda_stream)
+        assert e.value.code == pf.PF_ERR_STATE
+    finally:
+        m.close()
+
+
+def test_main_stage_needs_a_checkpoint_slot_per_microbatch_in_flight():
+    """A main context with fewer checkpoint slots (g) than the schedule keeps microbatches in flight would have
+    forward j+g overwrite the checkpoints of microbatch j: refused, not computed wrongly."""
+    import ctypes as C
+    pf, dev = _mods()
+    shape = synth.ModelShape(1, 128, 2, 256, 64, 1, 0, True, "bf16")
+    params = synth.make_model_params(shape, seed=41, std=0.08)
+    m = dev.DeviceModel(shape, params, g=1, training=True)
+    try:
+        x = dev.storage_tensor(synth.make_hidden(shape, seed=60), m.md)
+        st, fs = torch.cuda.Stream(), torch.cuda.Stream()
+        m.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, 0, x.data_ptr(), st.cuda_stream)
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, 1, x.data_ptr(), st.cuda_stream)   # slot 0 is still in use
+        assert e.value.code == pf.PF_ERR_STATE
+        m.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, 0, x.data_ptr(), st.cuda_stream)
+        with pytest.raises(pf.PipeFillError) as e:
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, 0, x.data_ptr(), st.cuda_stream)   # no forward to go back through
+        assert e.value.code == pf.PF_ERR_STATE
+        m.ctx.pf_ctx_sync()
+        p, mm, stage = 3, 4, 1                       # stage 1 of 3 keeps min(p - stage, m) = 2 microbatches in flight
+        windows = pf.pf_schedule_1f1b(p, mm, stage, 1_000_000, 2_000_000, 1 << 30, True, 0)
+        with pytest.raises(pf.PipeFillError) as e:
+            pf.pf_timeline_run(None, m.ctx, x.data_ptr(), p, mm, stage, 1_000_000, 2_000_000, windows, None, 0, None,
+                               C.c_int32(0), fs.cuda_stream, st.cuda_stream)
+        assert e.value.code == pf.PF_ERR_ARG
+        stats = pf.pf_timeline_run(None, m.ctx, x.data_ptr(), p, mm, 2, 1_000_000, 2_000_000,
+                                   pf.pf_schedule_1f1b(p, mm, 2, 1_000_000, 2_000_000, 1 << 30, True, 0), None, 0, None,
+                                   C.c_int32(0), fs.cuda_stream, st.cuda_stream)        # last stage: one in flight
+        assert stats["main_busy_ns"] > 0
+    finally:
+        m.close()
+
+
 @pytest.mark.parametrize("dtype,tol", [("f32", 1e-4), ("bf16", 2e-2)])
 def test_main_stage_forward_backward(dtype, tol):
     """Emulated main-job stage: forward of two microbatches, then their backwards (1F1B order keeps
