@@ -478,6 +478,18 @@ int32_t pf_op_attention_bwd(int32_t dtype, const void* qkv, const void* out, con
 int32_t pf_op_layernorm_bwd(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
                             const float* rstd, const void* resid, void* dx, float* dg, float* db, float* partial,
                             int64_t rows, int32_t d, void* stream);
+/* pf_op_layernorm_bwd for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without `partial`, same results.
+ * The partial dg / db rows go to a device array of 8 MiB that the library holds on every GPU it runs on until the
+ * process ends; its address on the current device is looked up on the first call there.  The call allocates
+ * nothing.  d a multiple of 8, at most 8192 (PF_ERR_ARG beyond that); any number of rows (the array bounds the
+ * number of workgroups, 128 at d = 8192, 512 up to d = 2048, not the input).  dx is identical to
+ * pf_op_layernorm_bwd's; dg and db can differ in the last bits when rows exceeds the number of workgroups (fewer,
+ * longer partial sums).  All calls on one GPU share the array: calls that overlap there (different streams or
+ * threads) race; calls on one stream are safe. */
+int32_t pf_op_layernorm_bwd_static(int32_t dtype, const void* dy, const void* x, const void* g, const float* mean,
+                                   const float* rstd, const void* resid, void* dx, float* dg, float* db,
+                                   int64_t rows, int32_t d, void* stream);
 /* out[c][r] = in[r][c] for in [rows][cols], out [cols][rows] (distinct buffers); rows <= 64 * 65535.
  * colsum_acc (device fp32 [cols], may be NULL): colsum_acc[c] += sum over r of in[r][c] (fp32 atomics:
  * the order of the additions, and with it the last bits, can differ between calls). */

@@ -35,6 +35,7 @@ EXPORTS = [
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
     "pf_ctx_set_replan", "pf_main_opt_state_bytes", "pf_ctx_set_main_offload", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
     "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd", "pf_op_layernorm_bwd", "pf_op_transpose", "pf_op_gemm_tn",
+    "pf_op_layernorm_bwd_static",
 ]
 PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
 
@@ -148,6 +149,7 @@ def _load():
     lib.pf_op_attention.argtypes = [I32, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_attention_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, I32, I32, I32, I32, I32, VP]
     lib.pf_op_layernorm_bwd.argtypes = [I32, VP, VP, VP, VP, VP, VP, VP, VP, VP, VP, I64, I32, VP]
+    lib.pf_op_layernorm_bwd_static.argtypes = [I32, VP, VP, VP, VP, VP, VP, VP, VP, VP, I64, I32, VP]
     lib.pf_op_transpose.argtypes = [I32, VP, VP, I64, I64, VP, VP]
     lib.pf_op_gemm_tn.argtypes = [I32, VP, VP, VP, VP, I64, I64, I64, VP]
     lib.pf_op_embed.argtypes = [I32, VP, VP, VP, VP, I64, I32, I32, I32, VP]
@@ -533,6 +535,9 @@ def unpack_embedding_f32(md, raw):
 def pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream=None):
     _check(lib.pf_op_layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, partial, rows, d, stream))
 
+
+def pf_op_layernorm_bwd_static(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, rows, d, stream=None):
+    _check(lib.pf_op_layernorm_bwd_static(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, rows, d, stream))
 
 
 def pf_op_gemm_tn(dtype, A, B, Cp, M, N, K, colsum_acc=None, stream=None):

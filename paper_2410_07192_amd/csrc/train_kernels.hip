@@ -785,3 +785,47 @@ hipError_t widen_to_f32(int32_t dtype, const void* src, float* dst, int64_t n, h
 
 }  // namespace pf
 
+// ---- LayerNorm backward without a workspace argument ---------------------------------------------------------
+// The partial dg / db rows of layernorm_bwd_kernel live in a device array of the library's own instead of a buffer
+// of the caller's.  The array's name is a host-side stand-in in host code: its device address is looked up once per
+// device and only that pointer is handed to kernels.
+namespace {
+constexpr int64_t kStaticScratchBytes = (int64_t)8 << 20;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / 4];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+}  // namespace
+
+extern "C" int32_t pf_op_layernorm_bwd_static(int32_t dtype, const void* dy, const void* x, const void* g,
+                                              const float* mean, const float* rstd, const void* resid, void* dx,
+                                              float* dg, float* db, int64_t rows, int32_t d, void* stream) {
+  if ((dtype != PF_DTYPE_F32 && dtype != PF_DTYPE_BF16) || !dy || !x || !g || !mean || !rstd || !dx || !dg || !db ||
+      rows <= 0 || d <= 0 || d % 8 != 0)
+    return pf::fail(PF_ERR_ARG, "pf_op_layernorm_bwd_static: bad argument");
+  if (d > 8192)
+    return pf::fail(PF_ERR_ARG, "pf_op_layernorm_bwd_static: d = %d exceeds the maximum of 8192 columns", d);
+  // one partial row is 2 * d floats; the array holds at least 128 of them at the widest d
+  int64_t max_blocks = kStaticScratchBytes / (2 * (int64_t)d * 4);
+  if (max_blocks > pf::LN_BWD_MAX_BLOCKS * 4) max_blocks = pf::LN_BWD_MAX_BLOCKS * 4;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return pf::fail(PF_ERR_HIP, "pf_op_layernorm_bwd_static: hipGetDevice: %s", hipGetErrorString(e));
+  if (dev < 0 || dev >= kMaxDevices) return pf::fail(PF_ERR_ARG, "pf_op_layernorm_bwd_static: device index %d not supported", dev);
+  float* ptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {   // first call on this device, which is the current one: its copy of the array
+      void* p = nullptr;
+      e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !p)
+        return pf::fail(PF_ERR_HIP, "pf_op_layernorm_bwd_static: hipGetSymbolAddress: %s", hipGetErrorString(e));
+      g_scratch_ptr[dev] = (float*)p;
+    }
+    ptr = g_scratch_ptr[dev];
+  }
+  // every partial row the second kernel reads is written by the first in the same call: nothing to clear
+  e = pf::layernorm_bwd(dtype, dy, x, g, mean, rstd, resid, dx, dg, db, ptr, rows, d, (hipStream_t)stream, max_blocks);
+  if (e != hipSuccess) return pf::fail(PF_ERR_HIP, "pf_op_layernorm_bwd_static: %s", hipGetErrorString(e));
+  return PF_OK;
+}
