@@ -223,74 +223,56 @@ def layer_param_count(d, f):
     return 4 * d * d + 2 * d * f + (3 * d + d + f + d) + 4 * d
 
 
-def _al256(x):
-    return -(-x // 256) * 256
-
-
-def layer_blob_bytes(d, f, esize):
-    """Packed layer: the 12 parameter arrays, each padded to a multiple of 256 bytes."""
-    sizes = (d, d, 3 * d * d, 3 * d, d * d, d, d, d, f * d, f, d * f, d)
-    return sum(_al256(n * esize) for n in sizes)
-
-
-def chain_nodes(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, n_slots, training):
-    """Node list (op, layer, mb_first, mb_count, mem_bytes) of one replica = g microbatches.
-
-    mem_bytes of a node is its peak HBM footprint including everything the job keeps resident
-    between bubbles (Sec. 4.3 tests mem(F[0]) <= M[i] per node): the weights that stay in HBM
-    (all layers, or the slots of a streamed configuration), embeddings and final LayerNorm, the
-    g hidden-state tensors carried from bubble to bubble, and for a layer visit the workspace of
-    one microbatch (LayerNorm output, fused QKV, attention output, FFN intermediate).  Every
-    buffer is padded to a multiple of 256 bytes.
-    """
-    tokens = batch * seq
-    act = _al256(tokens * d * esize)
-    blob = layer_blob_bytes(d, f, esize)
-    emb = ((vocab * d + seq * d) * esize if vocab > 0 else 0) + 2 * d * esize
-    slots = n_slots * blob if streamed else 0
-    carried = g * act
-    ws_fwd = 5 * act + _al256(tokens * f * esize)
-    resident = emb + (0 if streamed else n_layers * blob)
-    persistent = resident + slots + carried
+def chain_nodes(n_layers, vocab, g, training):
+    """Node list (op, layer, mb_first, mb_count) of one replica = g microbatches: the job's graph
+    flattened into a chain (Sec. 4.3).  Inference: [embedding] + one node per layer + final
+    LayerNorm.  Training adds the head with its loss, one recompute-and-backward node per layer
+    (last layer first) and the optimizer node.  Durations and memory are profiled inputs of the
+    Executor (Sec. 4.3), so they are not part of this list."""
     nodes = []
-    if not training:
-        if vocab > 0:
-            nodes.append((OP_EMBED, -1, 0, g, persistent))
-        for l in range(n_layers):
-            nodes.append((OP_LAYER_FWD, l, 0, g, persistent + ws_fwd))
-        nodes.append((OP_FINAL_LN, -1, 0, g, persistent))
-        return nodes
-    # Training: the job copies every parameter into its own memory and keeps, for its whole life,
-    # fp32 master weights, Adam moments and gradient accumulators, working and transposed copies in
-    # the storage type, one checkpoint per layer input and microbatch, and the workspaces of the
-    # recomputing backward; every node therefore reports the same footprint.
-    L = n_layers
-    sizes = (d, d, 3 * d * d, 3 * d, d * d, d, d, d, f * d, f, d * f, d)
-    blob32 = sum(_al256(n * 4) for n in sizes)
-    wt = sum(_al256(n * esize) for n in (3 * d * d, d * d, f * d, d * f))
-    mid = _al256(tokens * f * esize)
-    vp = -(-vocab // 64) * 64
-    total = ws_fwd
-    total += L * (blob + wt + 4 * blob32)
-    emb32 = _al256(vp * d * 4) + _al256(seq * d * 4) + 2 * _al256(d * 4)
-    total += 2 * _al256(vp * d * esize) + _al256(seq * d * esize) + 2 * _al256(d * esize) + 4 * emb32
-    total += g * (L + 1) * act + g * act + g * act                 # checkpoints, running gradient, head input
-    lse = _al256(batch * n_heads * seq * 4)
-    stat = _al256(tokens * 4)
-    total += 2 * act + mid + 2 * lse + 6 * stat                    # recompute outputs and statistics
-    t_a = _al256(max(tokens * f, 3 * tokens * d) * esize)
-    total += mid + 3 * act + 2 * act + t_a + mid                   # backward tensors and the two transposes
-    total += _al256(128 * 4 * 2 * d * 4)                           # LayerNorm-backward partial sums
-    total += 2 * _al256(tokens * vp * esize) + 256                 # logits, their transpose, loss cell
-    nodes.append((OP_EMBED, -1, 0, g, total))
-    for l in range(L):
-        nodes.append((OP_LAYER_FWD, l, 0, g, total))
-    nodes.append((OP_FINAL_LN, -1, 0, g, total))
-    nodes.append((OP_HEAD_LOSS, -1, 0, g, total))
-    for l in reversed(range(L)):
-        nodes.append((OP_LAYER_BWD, l, 0, g, total))
-    nodes.append((OP_OPT, -1, 0, g, total))
+    if vocab > 0 or training:
+        nodes.append((OP_EMBED, -1, 0, g))
+    for l in range(n_layers):
+        nodes.append((OP_LAYER_FWD, l, 0, g))
+    nodes.append((OP_FINAL_LN, -1, 0, g))
+    if training:
+        nodes.append((OP_HEAD_LOSS, -1, 0, g))
+        for l in reversed(range(n_layers)):
+            nodes.append((OP_LAYER_BWD, l, 0, g))
+        nodes.append((OP_OPT, -1, 0, g))
     return nodes
+
+
+def footprint_bounds(n_layers, d, n_heads, f, seq, batch, vocab, esize, g, streamed, n_slots, training):
+    """(lower, upper) bounds in bytes on the HBM a layer-visit node of the job may report, from
+    counts of parameters and activations only (Sec. 4.3: a node's memory requirement is a
+    profiled input, tested against the bubble's free memory; Sec. 3.2 item 3: model, optimizer
+    state and activations are what occupies it).  No buffer list of any implementation enters.
+
+    lower: what the method itself keeps in HBM -- the parameters that stay on the device (all
+    layers, or n_slots layers when streamed; embeddings) in the storage type, the g hidden-state
+    tensors carried between bubbles, and for training fp32 master weights, two Adam moments and a
+    gradient accumulator per parameter plus one checkpoint per layer input and microbatch.
+    upper: lower plus a generous allowance for working memory -- every intermediate tensor of one
+    layer visit of one microbatch (LayerNorm output, Q, K, V, attention output, projection output,
+    FFN intermediate) once for inference and four times for training (forward, saved for backward,
+    gradient, transposed operand), a second storage-type copy of the parameters (transposed
+    weights), two logits-sized tensors for the head, and 3 % + 48 MiB of padding and small
+    per-token statistics."""
+    T = batch * seq
+    n_layer = layer_param_count(d, f)
+    n_emb = (vocab * d + seq * d if vocab > 0 else 0) + 2 * d
+    on_device_layers = n_slots if streamed else n_layers
+    act = T * d * esize
+    inter = T * (6 * d + f) * esize
+    if not training:
+        lower = (on_device_layers * n_layer + n_emb) * esize + g * act
+        upper = lower + inter
+    else:
+        n_all = n_layers * n_layer + n_emb
+        lower = n_all * (esize + 16) + g * (n_layers + 1) * act
+        upper = lower + n_all * esize + 4 * inter + 3 * g * act + 2 * T * (vocab + 64) * esize
+    return lower, upper + upper * 3 // 100 + (48 << 20)
 
 
 # ---------------------------------------------------------------------------------------------

@@ -183,6 +183,9 @@ def test_select_config_matches_checker():
 
 
 def test_blob_layout_and_chain_against_checker():
+    """pf_build_chain: node order and microbatch fields equal the checker's chain; the memory a node reports is what
+    the context really occupies (its arena, from pf_ctx_arena_bytes, plus the weights that stay in HBM outside it)
+    and lies between bounds the checker derives from parameter and activation counts alone."""
     for name in ("cfg1", "cfg2", "cfg3"):
         s = synth.WORKLOADS[name]
         md = pf.model_desc(s)
@@ -191,25 +194,36 @@ def test_blob_layout_and_chain_against_checker():
         assert off[0] == 0 and all(o % 256 == 0 for o in off) and size % 256 == 0
         assert size >= op.layer_param_count(s.d_model, s.d_ff) * e
         assert size < op.layer_param_count(s.d_model, s.d_ff) * e + 12 * 256
+        emb = ((s.vocab + s.seq_len) * s.d_model if s.vocab > 0 else 0) * e + 2 * s.d_model * e
         for g, streamed, slots in ((1, 0, 0), (2, 1, 3), (4, 1, 2)):
             cfg = pf.pf_exec_config(g, streamed, slots, 0)
             chain = pf.pf_build_chain(md, cfg)
-            want = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, e,
-                                  g, bool(streamed), slots, False)
-            got = [(n.op, n.layer, n.mb_first, n.mb_count, n.mem_bytes) for n in chain]
-            assert got == want
-            assert pf.pf_ctx_arena_bytes(md, cfg) > 0
+            want = op.chain_nodes(s.n_layers, s.vocab, g, False)
+            assert [(n.op, n.layer, n.mb_first, n.mb_count) for n in chain] == want
+            arena = pf.pf_ctx_arena_bytes(md, cfg)
+            outside = emb + (0 if streamed else s.n_layers * size)      # resident blobs and embeddings are the caller's
+            lo, hi = op.footprint_bounds(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, e,
+                                         g, bool(streamed), slots, False)
+            for n in chain:
+                if n.op == op.OP_LAYER_FWD:
+                    assert n.mem_bytes == outside + arena             # a layer visit needs the whole arena
+                    assert lo <= n.mem_bytes <= hi
+                else:
+                    assert lo <= n.mem_bytes <= outside + arena       # the other nodes leave the layer workspace out
     s = synth.WORKLOADS["cfg4"]
     md = pf.model_desc(s)
     for g in (1, 2):
         cfg = pf.pf_exec_config(g, 0, 0, 1)
         chain = pf.pf_build_chain(md, cfg)
-        want = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2, g, False, 0, True)
-        got = [(n.op, n.layer, n.mb_first, n.mb_count, n.mem_bytes) for n in chain]
-        assert got == want and len(got) == 2 * s.n_layers + 4
-        assert [n[1] for n in got if n[0] == op.OP_LAYER_BWD] == list(range(s.n_layers - 1, -1, -1))
-        assert pf.pf_ctx_arena_bytes(md, cfg) == want[0][4]
-        assert want[0][4] < 16 * synth.GIB          # the training fill job fits its 16 GiB bubble memory
+        want = op.chain_nodes(s.n_layers, s.vocab, g, True)
+        assert [(n.op, n.layer, n.mb_first, n.mb_count) for n in chain] == want and len(want) == 2 * s.n_layers + 4
+        # a training context copies every parameter into its arena: the arena is the whole footprint, all the time
+        arena = pf.pf_ctx_arena_bytes(md, cfg)
+        lo, hi = op.footprint_bounds(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2, g, False,
+                                     0, True)
+        assert all(n.mem_bytes == arena for n in chain)
+        assert lo <= arena <= hi
+        assert arena < 16 * synth.GIB          # the training fill job fits its 16 GiB bubble memory
 
 
 def test_context_calls_fail_loudly_without_a_device_or_with_bad_arguments():

@@ -14,14 +14,15 @@ HERE = os.path.dirname(__file__)
 
 
 # ---------------------------------------------------------------- independent 1F1B simulation
-def simulate_1f1b(p, m, tf, tb):
+def simulate_1f1b(p, m, tf, tb, gpipe=False):
     """Event-driven simulation from the dependency rules alone (no closed forms):
     stage s runs min(p-s-1, m) warm-up forwards, then forward/backward pairs, then the
-    remaining backwards; F(s,j) needs F(s-1,j), B(s,j) needs B(s+1,j) (last stage: its own F).
+    remaining backwards (gpipe: all m forwards, then all m backwards); F(s,j) needs F(s-1,j),
+    B(s,j) needs B(s+1,j) (last stage: its own F).
     Returns per stage the list of (start, end) busy intervals of one iteration."""
     order = []
     for s in range(p):
-        w = min(p - s - 1, m)
+        w = m if gpipe else min(p - s - 1, m)
         seq = [("F", j) for j in range(w)]
         f, b = w, 0
         while f < m:
@@ -80,6 +81,22 @@ def test_windows_match_dependency_simulation(tf, tb):
                 want = idle_from_busy(busy[s], s * tf, T + s * tf)
                 got = [(w["start"], w["dur"]) for w in op.windows_1f1b(p, m, s, tf, tb, 1)]
                 assert got == want, (p, m, s)
+
+
+@pytest.mark.parametrize("tf,tb", [(2, 4), (3, 5), (7, 7), (5, 3)])
+def test_gpipe_windows_match_dependency_simulation(tf, tb):
+    """Start times and lengths of the GPipe windows (Sec. 4.5) against the same simulation run in GPipe order."""
+    for p in range(1, 9):
+        for m in range(1, 12):
+            busy = simulate_1f1b(p, m, tf, tb, gpipe=True)
+            T = op.iteration_time(p, m, tf, tb)
+            assert max(e for s in range(p) for _, e in busy[s]) == T       # same iteration length as 1F1B
+            for s in range(p):
+                want = idle_from_busy(busy[s], s * tf, T + s * tf)
+                got = [(w["start"], w["dur"]) for w in op.windows_gpipe(p, m, s, tf, tb, 1)]
+                assert got == want, (p, m, s)
+                kinds = [w["kind"] for w in op.windows_gpipe(p, m, s, tf, tb, 1)]
+                assert kinds == ([op.KIND_FWD_BWD] if s < p - 1 else []) + ([op.KIND_FILL_DRAIN] if s > 0 else [])
 
 
 def test_idle_total_and_paper_lengths():
@@ -288,11 +305,44 @@ def test_choose_configuration_against_fractions():
 
 
 def test_chain_nodes_shape():
+    """The flattened graph (Sec. 4.3) of the workloads, against counts that follow from the model sizes alone, and
+    the parameter counts against the published sizes of the architectures the workloads stand for."""
     s = synth.WORKLOADS["cfg2"]
-    nodes = op.chain_nodes(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2,
-                           g=1, streamed=False, n_slots=0, training=False)
-    assert len(nodes) == 14 and [n[0] for n in nodes] == [0] + [1] * 12 + [2]
-    assert op.layer_param_count(768, 3072) == 7087872       # one BERT-base-shaped layer
+    nodes = op.chain_nodes(s.n_layers, s.vocab, g=1, training=False)
+    assert len(nodes) == 14 and [n[0] for n in nodes] == [op.OP_EMBED] + [op.OP_LAYER_FWD] * 12 + [op.OP_FINAL_LN]
+    assert [n[1] for n in nodes] == [-1] + list(range(12)) + [-1]
+    assert len(op.chain_nodes(24, 50257, 2, False)) == 26 and all(n[3] == 2 for n in op.chain_nodes(24, 50257, 2, False))
+    assert len(op.chain_nodes(1, 0, 1, False)) == 2            # hidden states in: no embedding node
+    tr = op.chain_nodes(12, 50257, 1, True)
+    assert len(tr) == 2 * 12 + 4
+    assert [n[0] for n in tr] == ([op.OP_EMBED] + [op.OP_LAYER_FWD] * 12 + [op.OP_FINAL_LN, op.OP_HEAD_LOSS]
+                                  + [op.OP_LAYER_BWD] * 12 + [op.OP_OPT])
+    assert [n[1] for n in tr if n[0] == op.OP_LAYER_BWD] == list(range(11, -1, -1))     # last layer first
+    # one BERT-base-shaped layer: the 12 encoder layers of that model hold 85 054 464 parameters
+    assert op.layer_param_count(768, 3072) == 7087872 and 12 * 7087872 == 85054464
+    # the 24-layer d=2048 decoder with a 50257-token vocabulary and 1024 positions: "1.3B"
+    total = 24 * op.layer_param_count(2048, 8192) + (50257 + 1024) * 2048 + 2 * 2048
+    assert 1.30e9 < total < 1.33e9
+
+
+def test_footprint_bounds_follow_the_counts():
+    """The memory bounds are sums of parameter and activation counts: known totals for the workloads."""
+    s = synth.WORKLOADS["cfg2"]
+    lo, hi = op.footprint_bounds(s.n_layers, s.d_model, s.n_heads, s.d_ff, s.seq_len, s.batch, s.vocab, 2, 1, False, 0, False)
+    n_params = 85054464 + (30522 + 512) * 768 + 2 * 768           # encoder layers + embeddings + final LayerNorm
+    assert lo == 2 * n_params + 16384 * 768 * 2                    # bf16 parameters + one carried [tokens][d] tensor
+    inter = 16384 * (6 * 768 + 3072) * 2                           # every intermediate tensor of one layer visit
+    assert lo + inter < hi < (lo + inter) * 1.04 + (49 << 20)
+    # streaming keeps n_slots layers instead of all of them; each extra carried microbatch adds one tensor
+    lo3, _ = op.footprint_bounds(24, 2048, 16, 8192, 1024, 16, 50257, 2, 2, True, 3, False)
+    lo3b, _ = op.footprint_bounds(24, 2048, 16, 8192, 1024, 16, 50257, 2, 3, True, 2, False)
+    layer = op.layer_param_count(2048, 8192) * 2
+    assert lo3 - lo3b == layer - 16384 * 2048 * 2
+    # training: 2 + 16 bytes per parameter (working copy; master, two moments, accumulator) + checkpoints
+    lo4, hi4 = op.footprint_bounds(12, 1024, 16, 4096, 1024, 8, 50257, 2, 1, False, 0, True)
+    n4 = 12 * op.layer_param_count(1024, 4096) + (50257 + 1024) * 1024 + 2 * 1024
+    assert lo4 == 18 * n4 + 13 * 8192 * 1024 * 2
+    assert hi4 < 16 * synth.GIB                                    # the training fill job fits its 16 GiB
 
 
 def test_job_arriving_in_the_middle_of_a_bubble():

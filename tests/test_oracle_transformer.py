@@ -193,3 +193,33 @@ def test_adam_first_step_closed_form_and_decay():
     for t in range(1, 6):
         th, m, v = ot.adam_step(th, m, v, g, t, lr=1e-2)
     assert np.allclose(th, 1 - 5e-2 * g / (np.abs(g) + 1e-8), atol=1e-12)
+
+
+def test_lm_loss_hand_worked_next_token_alignment():
+    """Tied head, V = 3, S = 3, two sequences, logits chosen as logarithms of small integers so every softmax is a
+    ratio of integers (R7: position t predicts token t+1, the last position has no target, mean over B(S-1)).
+    Position 0 of sequence 0 holds p = (1/8, 2/8, 5/8) and must be scored on ids[0,1] = 0; a loss aligned with
+    ids[0,0] = 2, or one that counts the last position, gives a different number."""
+    E = np.eye(3)                                   # tied embedding = identity: logits are the hidden states
+    L = np.log
+    h = np.array([[[L(1), L(2), L(5)], [L(3), L(1), L(4)], [L(7), L(1), L(1)]],
+                  [[L(2), L(1), L(1)], [L(1), L(1), L(2)], [L(1), L(9), L(1)]]])
+    ids = np.array([[2, 0, 1], [1, 1, 2]])
+    loss, dlogits = ot.lm_loss(h, E, ids)
+    # targets: seq 0 -> (0, 1) with p = 1/8, 1/8; seq 1 -> (1, 2) with p = 1/4, 1/2
+    assert abs(loss - (L(8) + L(8) + L(4) + L(2)) / 4) < 1e-15
+    want = np.array([[[1 / 8 - 1, 2 / 8, 5 / 8], [3 / 8, 1 / 8 - 1, 4 / 8], [0, 0, 0]],
+                     [[1 / 2, 1 / 4 - 1, 1 / 4], [1 / 4, 1 / 4, 1 / 2 - 1], [0, 0, 0]]]) / 4
+    assert np.allclose(dlogits, want, atol=1e-15)
+
+
+def test_embed_hand_worked():
+    """x[b,t] = E[ids[b,t]] + P[t] (R5) on numbers that name their own row: token v -> (10v, 10v+1), position t ->
+    (100t, 200t); the position table is longer than the sequence."""
+    tok = np.array([[0., 1.], [10., 11.], [20., 21.], [30., 31.]])
+    pos = np.array([[0., 0.], [100., 200.], [200., 400.], [300., 600.]])
+    ids = np.array([[2, 0, 3], [1, 1, 0]])
+    x = ot.embed(ids, dict(tok_emb=tok, pos_emb=pos))
+    want = np.array([[[20., 21.], [100., 201.], [230., 431.]],
+                     [[10., 11.], [110., 211.], [200., 401.]]])
+    assert np.array_equal(x, want)
