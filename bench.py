@@ -10,7 +10,15 @@ while the main stage is emulated on the timeline.  The headline value is
                                / summed duration of the windows offered
 
 Workloads (--workload):
-  cfg2 (default)  12-layer bf16 encoder inference fill job, weights resident, 1F1B p=8 m=16
+  cfg5 (default)  real main-job stage (3 layers d=8192, fwd+bwd on its own stream) under emulated
+                  1F1B p=16 m=32 with measured t_f/t_b, the cfg3 job (24-layer d=2048 decoder, weights
+                  streamed from pinned host memory) filling its bubbles: the largest configuration that
+                  fits one GPU and the only one on which the main-stage slowdown is defined.  A step is
+                  one main-job iteration with filling; the same iterations without filling are run
+                  outside the timed region for the slowdown.  --main-offload adds the main job's
+                  optimizer phase (gradient synchronisation of --sync-ms, Adam update) and offloads
+                  optimizer state to pinned host memory around it; the windows gain the offloaded bytes.
+  cfg2            12-layer bf16 encoder inference fill job, weights resident, 1F1B p=8 m=16
                   t_f=15 ms t_b=30 ms, 24 GiB free; the steps are shared evenly by the 8 stages.
                   --schedule gpipe fills the two contiguous windows of a GPipe main job instead.
   cfg3            24-layer d=2048 causal decoder inference, weights streamed from pinned host memory,
@@ -18,11 +26,6 @@ Workloads (--workload):
                   visit chosen by the planner.
   cfg4            12-layer d=1024 causal decoder TRAINING fill job (fwd + recompute/bwd + Adam,
                   accumulation across bubbles), 1F1B p=16 m=32, 16 GiB free.
-  cfg5            real main-job stage (3 layers d=8192, fwd+bwd on its own stream) under emulated
-                  1F1B p=16 m=32 with measured t_f/t_b, the cfg3 job filling its bubbles; reports
-                  the main-stage slowdown.  --main-offload adds the main job's optimizer phase
-                  (gradient synchronisation of --sync-ms, Adam update) and offloads optimizer state
-                  to pinned host memory around it; the windows gain the offloaded bytes.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -75,6 +78,44 @@ def cpu_baseline(shape, params, ids, n_seq):
     return {"value": sample.size / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n_seq} of {shape.batch} sequences (seq {shape.seq_len}) through all "
                       f"{shape.n_layers} layers in float64, {dt:.1f} s"}
+
+
+def _oracle_threads():
+    try:
+        from threadpoolctl import threadpool_info
+        return int(max([p.get("num_threads", 1) for p in threadpool_info()] or [1]))
+    except Exception:
+        return int(os.cpu_count() or 1)
+
+
+def cpu_baseline_layer(shape, synth, n_seq, n_lay=3):
+    """The CPU checker on a bounded slice of a large inference job: n_seq sequences through n_lay layers (a layer's
+    cost is the same for every layer and linear in the number of sequences), scaled to the whole stack."""
+    from oracle import transformer as ot
+    P = ot.cast_params({"layers": [synth.make_layer_params(shape, 0, seed=300)]})["layers"][0]
+    x = synth.make_hidden(shape, seed=301, batch=n_seq).astype("float64")
+    t0 = time.perf_counter()
+    for _ in range(n_lay):
+        x = ot.layer_forward(x, P, shape.n_heads, shape.causal, shape.eps)
+    dt = time.perf_counter() - t0
+    return {"value": n_seq * shape.seq_len / (dt / n_lay * shape.n_layers), "unit": "tokens/s", "cores": _oracle_threads(),
+            "kind": "oracle",
+            "sample": f"{n_seq} of {shape.batch} sequences (seq {shape.seq_len}) through {n_lay} of the {shape.n_layers} "
+                      f"layers in float64, {dt:.1f} s, scaled to {shape.n_layers} layers (embedding and final LayerNorm "
+                      f"left out: under 0.1 % of the work)"}
+
+
+def cpu_baseline_train(shape, params, ids, n_seq):
+    """The CPU checker's training microbatch (forward, loss, backward of every parameter) on n_seq sequences."""
+    from oracle import transformer as ot
+    P = ot.cast_params(params)
+    sample = ids[:n_seq]
+    t0 = time.perf_counter()
+    ot.model_loss_and_grads(sample, P, shape.n_heads, shape.causal, shape.eps)
+    dt = time.perf_counter() - t0
+    return {"value": sample.size / dt, "unit": "tokens/s", "cores": _oracle_threads(), "kind": "oracle",
+            "sample": f"{n_seq} of {shape.batch} sequences (seq {shape.seq_len}): forward, loss and all gradients through "
+                      f"all {shape.n_layers} layers in float64 (no recompute, no Adam), {dt:.1f} s"}
 
 
 def stage_stepper(pf, model, stages, args, p, m, tf, tb, fill, main_s):
@@ -134,19 +175,27 @@ def kernel_rates(ctx, pf, shape):
     return out
 
 
-# HBM-side traffic of one FFN1 launch of the default workload (M=16384, N=3072, K=768), from two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a plain
-# 256 MiB copy (FETCH_SIZE x2.0, WRITE_SIZE x1.0): 108.3 MiB fetched + 96.0 MiB written.  Algorithmic:
-# 28.5 MiB read (X, W, bias) + 96 MiB written.  A profiler run is needed to refresh it.
-FFN1_CFG2_TRAFFIC_BYTES = int((108.3 + 96.0) * (1 << 20))
+def measured_traffic(key):
+    """HBM bytes per launch of a roofline kernel as the profiler measured them: the committed summary of two
+    rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by what the same counter reads for a plain copy of
+    known size) carries one line `traffic_bytes_per_launch[<key>]: <bytes>` per kernel.  None when no summary
+    holds the key (a profiler run is needed to produce one; this program cannot read the counters itself)."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic*.md"))):
+        with open(path) as fh:
+            m = re.search(r"traffic_bytes_per_launch\[%s\]:\s*(\d+)" % re.escape(key), fh.read())
+        if m:
+            return int(m.group(1))
+    return None
 
 
-def ffn1_roofline(kernels, shape, tile="2,4,4,2", traffic=None):
+def ffn1_roofline(kernels, shape, key):
     dom = kernels["gemm_ffn1"]
     return {"bound": "mfma", "achieved": dom["achieved"], "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": dom["frac"], "traffic": traffic,
-            "kernel": "gemm_bf16_nt_kernel<%s,bf16_t,bias+GELU> (FFN1: M=%d N=%d K=%d)" %
-                      (tile, shape.tokens, shape.d_ff, shape.d_model),
+            "frac": dom["frac"], "traffic": measured_traffic(key),
+            "kernel": "gemm_bf16_nt_kernel<bf16_t,bias+GELU> (FFN1: M=%d N=%d K=%d)" %
+                      (shape.tokens, shape.d_ff, shape.d_model),
             "launches": dom["launches"], "avg_us": dom["avg_us"]}
 
 
@@ -162,10 +211,16 @@ def base_line(args, metric_value, wall, extra):
     return out
 
 
-def fill_stats(agg):
+def fill_stats(agg, copy_wait_ns=0):
+    """pct_bubble_filled counts the time the fill stream had kernels to run: the span from a window's first chunk
+    start to its last chunk end (HIP events), less the time the stream sat waiting inside it for a streamed layer's
+    host-to-HBM copy (copy_wait_ns, bracketed by events of its own)."""
     off = max(1, agg["offered_ns"])
-    return {"pct_bubble_filled": 100.0 * agg["fill_busy_ns"] / off,
-            "pct_idle_filled": 100.0 * agg["fill_busy_ns"] / max(1, agg["idle_ns"]),
+    busy = agg["fill_busy_ns"] - copy_wait_ns
+    return {"pct_bubble_filled": 100.0 * busy / off,
+            "pct_idle_filled": 100.0 * busy / max(1, agg["idle_ns"]),
+            "pct_bubble_spanned": 100.0 * agg["fill_busy_ns"] / off,
+            "copy_wait_pct_of_offered": 100.0 * copy_wait_ns / off,
             "overrun_pct_of_offered": 100.0 * agg["overrun_ns"] / off,
             "replicas_done": agg["replicas_done"], "chunks_run": agg["chunks_run"]}
 
@@ -242,9 +297,9 @@ def run_cfg2(args, np, torch, pf, dev, synth):
         # the same job with the GPU to itself (profiled chain, back to back): what a bubble-second is worth against it
         "exclusive_tokens_per_s": shape.tokens / (chain_ns * 1e-9),
         "fill_vs_exclusive": (tokens / (agg["offered_ns"] * 1e-9)) / (shape.tokens / (chain_ns * 1e-9)),
-        "roofline": ffn1_roofline(kernels, shape, traffic=FFN1_CFG2_TRAFFIC_BYTES), "kernels": kernels})
+        "roofline": ffn1_roofline(kernels, shape, "cfg2_ffn1"), "kernels": kernels})
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs)
+        out["cpu_baseline"] = cpu_baseline(shape, params, ids[0], args.cpu_seqs or 24)
     model.close()
     return out
 
@@ -271,18 +326,42 @@ def make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4), n_slots=3):
     return shape, models
 
 
-def choose_streamed_config(pf, windows, chains, samples, bubble_ns, fill_ppm, switch_ns):
-    """Configuration (microbatches per layer visit) of the streamed job for a cycle of equal bubbles.  The same job
-    follows itself (the Executor partitions the next batch from what is left of the bubble in which one completes),
-    so the configurations are compared on a run of back-to-back batches that covers at least eight bubbles, not on
-    one batch, whose last bubble a single plan would count as full.  Returns (best index or -1, batches per run,
-    bubbles per run, batches in a run) with one entry per configuration."""
-    usable = max(1, bubble_ns * fill_ppm // 1_000_000 - switch_ns)
-    as_tuples = lambda chain: [(n.dur_ns, n.mem_bytes, n.op, n.layer, n.mb_first, n.mb_count) for n in chain]
-    runs = [max(1, -(-8 * usable // max(1, sum(n.dur_ns for n in ch)))) for ch in chains]
-    cfgs = [dict(F=as_tuples(ch) * r, samples=sm * r) for ch, sm, r in zip(chains, samples, runs)]
-    best, rep, cyc, _ = pf.pf_select_config(windows, cfgs, fill_ppm, switch_ns, 0)
-    return best, rep, cyc, runs
+def choose_streamed_config(pf, windows, models, shape, fill_ppm, switch_ns):
+    """Configuration (microbatches per layer visit) of the streamed job: the library compares the candidates on a
+    run of back-to-back batches that covers eight bubble cycles (the same job follows itself).  Returns (best index
+    or -1, per candidate: batches in the run, cycles the run takes)."""
+    cfgs = [dict(F=[(n.dur_ns, n.mem_bytes, n.op, n.layer, n.mb_first, n.mb_count) for n in m_.chain],
+                 samples=m_.cfg.g * shape.batch) for m_ in models]
+    best, runs, cyc, _ = pf.pf_select_config_stream(windows, cfgs, fill_ppm, switch_ns, 0, 8)
+    return best, runs, cyc
+
+
+def timed_fill_run(ctx, pf, torch, run_step, steps, verbose=False):
+    """The timed region: `steps` calls of run_step() with only the roofline kernel (FFN1) and the copy waits
+    bracketed by events.  Returns (aggregated statistics, list of per-step statistics, wall seconds, FFN1 rates
+    source = the context's totals, copy wait ns)."""
+    ctx.pf_ctx_kernel_timing((1 << pf.PF_K_GEMM_FFN1) | (1 << pf.PF_K_COPY_WAIT))
+    torch.cuda.synchronize()
+    agg = dict.fromkeys(AGG_KEYS, 0)
+    per_step = []
+    t0 = time.perf_counter()
+    for i in range(steps):
+        s = run_step()
+        per_step.append(s)
+        for k_ in agg:
+            agg[k_] += s[k_]
+        ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)      # folds this step's event pairs into the totals
+        if verbose:
+            print(f"step {i}: " + " ".join(f"{k_}={s[k_]}" for k_ in AGG_KEYS), file=sys.stderr)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    _, wait_ns = ctx.pf_ctx_kernel_stats(pf.PF_K_COPY_WAIT)
+    return agg, per_step, wall, wait_ns
+
+
+def candidates_report(models, runs, cyc):
+    return {f"g={m_.cfg.g}": {"batches_in_run": runs[i], "cycles_of_run": cyc[i],
+                              "chain_ms": sum(n.dur_ns for n in m_.chain) * 1e-6} for i, m_ in enumerate(models)}
 
 
 def run_cfg3(args, np, torch, pf, dev, synth):
@@ -292,9 +371,7 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     windows = [dict(start=bubble_ns // 2, dur=bubble_ns, free=cap, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
     for mdl in models:
         mdl.ctx.pf_profile_chain(mdl.chain, 1, 3, fill.cuda_stream)
-    best, rep, cyc, runs = choose_streamed_config(pf, windows, [mdl.chain for mdl in models],
-                                                  [mdl.cfg.g * shape.batch for mdl in models], bubble_ns,
-                                                  args.fill_ppm, args.switch_ns)
+    best, runs, cyc = choose_streamed_config(pf, windows, models, shape, args.fill_ppm, args.switch_ns)
     if best < 0:
         raise RuntimeError(f"no configuration of the streamed job fits the {args.bubble_ms} ms / {args.cap_gib} GiB bubbles")
     mdl = models[best]
@@ -308,17 +385,7 @@ def run_cfg3(args, np, torch, pf, dev, synth):
 
     for _ in range(args.warmup):
         run_step()
-    mdl.ctx.pf_ctx_kernel_timing(1 << pf.PF_K_GEMM_FFN1)
-    torch.cuda.synchronize()
-    agg = dict.fromkeys(AGG_KEYS, 0)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        s = run_step()
-        for k_ in agg:
-            agg[k_] += s[k_]
-        mdl.ctx.pf_ctx_kernel_stats(pf.PF_K_GEMM_FFN1)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    agg, _, wall, wait_ns = timed_fill_run(mdl.ctx, pf, torch, run_step, args.steps)
     g = mdl.cfg.g
     tokens = agg["replicas_done"] * g * shape.tokens
     dominant = kernel_rates(mdl.ctx, pf, shape)
@@ -336,17 +403,16 @@ def run_cfg3(args, np, torch, pf, dev, synth):
                                f"explicit {args.bubble_ms:g} ms bubbles separated by {args.bubble_ms / 2:g} ms, "
                                f"{args.cap_gib:g} GiB cap",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
-                   "microbatches_per_layer_visit": g,
-                   "candidates": {f"g={m_.cfg.g}": {"batches": rep[i] * runs[i], "bubbles": cyc[i],
-                                                     "chain_ms": sum(n.dur_ns for n in m_.chain) * 1e-6}
-                                  for i, m_ in enumerate(models)}},
-        **fill_stats(agg), "main_slowdown_pct": None,
+                   "microbatches_per_layer_visit": g, "candidates": candidates_report(models, runs, cyc)},
+        **fill_stats(agg, wait_ns), "main_slowdown_pct": None,
         "fill_tflops_in_bubbles": agg["replicas_done"] * g * shape.n_layers * layer_fwd_flops(shape) /
         (agg["offered_ns"] * 1e-9) * 1e-12,
         "host_to_hbm_gbs_in_bubbles": layer_visits * blob_bytes / (agg["offered_ns"] * 1e-9) * 1e-9,
-        "roofline": ffn1_roofline(kernels, shape), "kernels": kernels})
+        "roofline": ffn1_roofline(kernels, shape, "cfg3_ffn1"), "kernels": kernels})
     for m_ in models:
         m_.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_layer(shape, synth, args.cpu_seqs or 16)
     return out
 
 
@@ -364,7 +430,6 @@ def run_cfg4(args, np, torch, pf, dev, synth):
     model.set_io(d_in, n_ring, None, 0)
     fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
     model.ctx.pf_profile_chain(model.chain, 1, 3, fill.cuda_stream)
-    model.ctx.pf_ctx_train_state()
     chain_ns = sum(n.dur_ns for n in model.chain)
     stages = []
     for s in range(p):
@@ -378,17 +443,11 @@ def run_cfg4(args, np, torch, pf, dev, synth):
         run_step(0)
     run_step.reset()
     _, steps0 = model.ctx.pf_ctx_train_state()
-    torch.cuda.synchronize()
-    agg = dict.fromkeys(AGG_KEYS, 0)
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        s = run_step(i)
-        for k_ in agg:
-            agg[k_] += s[k_]
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    it = iter(range(args.steps))
+    agg, _, wall, _ = timed_fill_run(model.ctx, pf, torch, lambda: run_step(next(it)), args.steps)
     loss, steps1 = model.ctx.pf_ctx_train_state()
     tokens = agg["replicas_done"] * shape.tokens
+    kernels = kernel_rates(model.ctx, pf, shape)       # the forward visits' FFN1 (M=8192 N=4096 K=1024), timed in situ
     # forward + recompute + backward (2x forward) = 4x the layer forward, plus the head's three T x V x d GEMMs
     step_flops = 4 * shape.n_layers * layer_fwd_flops(shape) + 3 * gemm_flops(shape.tokens, shape.vocab, shape.d_model)
     L = shape.n_layers
@@ -405,8 +464,10 @@ def run_cfg4(args, np, torch, pf, dev, synth):
         "arena_gib": model.arena_bytes / GIB,
         "node_ms": {"layer_fwd": model.chain[1].dur_ns * 1e-6, "head_loss": model.chain[L + 2].dur_ns * 1e-6,
                     "layer_bwd": model.chain[L + 3].dur_ns * 1e-6, "opt": model.chain[len(model.chain) - 1].dur_ns * 1e-6},
-        "roofline": None})
+        "roofline": ffn1_roofline(kernels, shape, "cfg4_ffn1")})
     model.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_train(shape, params, ids[0, 0], args.cpu_seqs or 1)
     return out
 
 
@@ -445,11 +506,12 @@ def run_cfg5(args, np, torch, pf, dev, synth):
     tf_ms, tb_ms = time_main(3)
     tf, tb = int(tf_ms * 1e6), int(tb_ms * 1e6)
 
-    shape3, models = make_cfg3_models(torch, pf, dev, synth, gs=(2,))
-    fm = models[0]
-    fm.ctx.pf_profile_chain(fm.chain, 1, 3, fill.cuda_stream)
+    shape3, models = make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4))
+    for mdl in models:
+        mdl.ctx.pf_profile_chain(mdl.chain, 1, 3, fill.cuda_stream)
     cap = int(args.cap_gib * GIB)
-    windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, cap, True, 2 * max(n.dur_ns for n in fm.chain))
+    min_gap = 2 * max(n.dur_ns for mdl in models for n in mdl.chain if mdl.cfg.g == 1)
+    windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, cap, True, min_gap)
     offload = None
     if args.main_offload:
         # measured copy rates (1 GiB, pinned host memory), planned at 85 % of them
@@ -475,6 +537,10 @@ def run_cfg5(args, np, torch, pf, dev, synth):
         offload = dict(state=state, slices=slices, extra=extra, host=host, sync_ns=sync_ns, rates=rates)
         for w, e in zip(windows, extra):
             w["free"] += e
+    best, runs, cyc = choose_streamed_config(pf, windows, models, shape3, args.fill_ppm, args.switch_ns)
+    if best < 0:
+        raise RuntimeError(f"no configuration of the fill job fits the stage's bubbles with {args.cap_gib} GiB free")
+    fm = models[best]
     plan, n_plan, k = pf.pf_plan_bubbles(windows, fm.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
     cursor = C.c_int32(0)
     fm.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
@@ -491,37 +557,43 @@ def run_cfg5(args, np, torch, pf, dev, synth):
     set_offload(True)
     for _ in range(args.warmup):
         run_iter(True)
-    set_offload(False)       # baseline: same iteration (with its optimizer phase), nothing offloaded, nothing filled
-    base = [run_iter(False) for _ in range(args.steps)]
+    # the same iterations with nothing offloaded and nothing filled, outside the timed region: half of them before
+    # the filled iterations and half after, so that a drift of the device's clock does not read as a slowdown
+    n_base = max(2, min(args.steps, 8))
+    set_offload(False)
+    base = [run_iter(False) for _ in range((n_base + 1) // 2)]
     set_offload(True)
-    off_only = [run_iter(False) for _ in range(args.steps)] if offload else []
-    torch.cuda.synchronize()
-    agg = dict.fromkeys(AGG_KEYS, 0)
-    t0 = time.perf_counter()
-    filled = []
-    for _ in range(args.steps):
-        s = run_iter(True)
-        filled.append(s)
-        for k_ in agg:
-            agg[k_] += s[k_]
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    off_only = [run_iter(False) for _ in range(min(args.steps, 3))] if offload else []
+    agg, filled, wall, wait_ns = timed_fill_run(fm.ctx, pf, torch, lambda: run_iter(True), args.steps)
+    dominant = kernel_rates(fm.ctx, pf, shape3)
+    set_offload(False)
+    base += [run_iter(False) for _ in range(n_base // 2)]
+    set_offload(True)
+    fm.ctx.pf_ctx_kernel_timing(0x7f)
+    run_iter(True)                                        # one more filled iteration with every kernel class bracketed
+    kernels = kernel_rates(fm.ctx, pf, shape3)
+    kernels["gemm_ffn1"] = dominant["gemm_ffn1"]
     t_base = sum(s["iter_ns"] for s in base) / len(base)
     t_fill = sum(s["iter_ns"] for s in filled) / len(filled)
     mb_base = sum(s["main_busy_ns"] for s in base) / len(base)
     mb_fill = sum(s["main_busy_ns"] for s in filled) / len(filled)
     g = fm.cfg.g
     tokens = agg["replicas_done"] * g * shape3.tokens
+    blob_bytes = pf.pf_layer_blob_layout(fm.md)[0]
+    layer_visits = sum(1 for n in fm.chain if n.op == pf.PF_OP_LAYER_FWD) * agg["replicas_done"]
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": f"cfg5: main-job stage of 3 layers d=8192 h=64 ff=32768 seq=2048 microbatch=1 bf16 fwd+bwd "
                                f"(recomputing backward) on its own stream, emulated 1F1B p={p} m={m} stage {stage} with "
-                               f"measured t_f={tf_ms:.1f} ms t_b={tb_ms:.1f} ms; fill = cfg3 job (streamed weights, g=2), "
-                               f"{args.cap_gib:g} GiB free" + (
+                               f"measured t_f={tf_ms:.1f} ms t_b={tb_ms:.1f} ms; fill = cfg3 job (24-layer d=2048 causal "
+                               f"decoder inference, seq 1024, batch 16, weights streamed from pinned host memory, "
+                               f"{g} microbatches per layer visit), {args.cap_gib:g} GiB free" + (
                                    f"; main job ends the iteration with a {args.sync_ms:g} ms gradient synchronisation and an "
                                    f"Adam update, and offloads {sum(offload['slices']) / GIB:.2f} of its "
                                    f"{offload['state'] / GIB:.2f} GiB of optimizer state" if offload else ""),
-                   "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns},
-        **fill_stats(agg),
+                   "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
+                   "candidates": candidates_report(models, runs, cyc),
+                   "iterations_without_fill": len(base)},
+        **fill_stats(agg, wait_ns),
         **({"main_offload": {
             "d2h_gb_per_s": offload["rates"][0] * 1e-9, "h2d_gb_per_s": offload["rates"][1] * 1e-9,
             "slice_mib": offload["slices"][0] / (1 << 20), "slices_used": sum(1 for c in offload["slices"] if c),
@@ -535,9 +607,13 @@ def run_cfg5(args, np, torch, pf, dev, synth):
         "main_stage_tflops": (4 * shape5.n_layers * layer_fwd_flops(shape5) * m) / (mb_base * 1e-9) * 1e-12,
         "fill_tflops_in_bubbles": agg["replicas_done"] * g * shape3.n_layers * layer_fwd_flops(shape3) /
         (agg["offered_ns"] * 1e-9) * 1e-12,
-        "roofline": None})
-    fm.close()
+        "host_to_hbm_gbs_in_bubbles": layer_visits * blob_bytes / (agg["offered_ns"] * 1e-9) * 1e-9,
+        "roofline": ffn1_roofline(kernels, shape3, "cfg3_ffn1"), "kernels": kernels})
+    for m_ in models:
+        m_.close()
     main.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_layer(shape3, synth, args.cpu_seqs or 16)
     return out
 
 
@@ -546,7 +622,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
     ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
     ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles (cfg2)")
@@ -554,7 +630,8 @@ def main():
                     help="cfg2: main-job schedule whose idle windows are filled (Sec. 4.5; GPipe has two contiguous windows per stage)")
     ap.add_argument("--stage", type=int, default=7, help="pipeline stage emulated by cfg5")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=24)
+    ap.add_argument("--cpu-seqs", type=int, default=0,
+                    help="sequences of the CPU baseline's sample (0: 24 for cfg2, 16 for cfg3/cfg5, 1 for cfg4)")
     ap.add_argument("--verbose", action="store_true", help="per-step statistics on stderr (cfg2)")
     ap.add_argument("--bubble-ms", type=float, default=40.0, help="cfg3: duration of the explicit bubbles")
     ap.add_argument("--cap-gib", type=float, default=8.0, help="cfg3, cfg5: free memory inside the bubbles")
@@ -570,7 +647,7 @@ def main():
         print("bench.py: this build runs on ONE GPU; the fill path has no cross-GPU step "
               "(one independent Executor per device). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
-    defaults = {"cfg2": (16, 2), "cfg3": (50, 3), "cfg4": (16, 1), "cfg5": (3, 1)}
+    defaults = {"cfg2": (16, 2), "cfg3": (50, 3), "cfg4": (16, 1), "cfg5": (6, 1)}
     if args.steps is None:
         args.steps = defaults[args.workload][0]
     if args.warmup is None:

@@ -55,9 +55,11 @@ enum { PF_OP_EMBED = 0, PF_OP_LAYER_FWD = 1, PF_OP_FINAL_LN = 2, PF_OP_HEAD_LOSS
 
 enum { PF_DTYPE_F32 = 0, PF_DTYPE_BF16 = 1 };
 
-/* kernel classes of a layer visit, for pf_ctx_kernel_timing / pf_ctx_kernel_stats */
+/* kernel classes of a layer visit, for pf_ctx_kernel_timing / pf_ctx_kernel_stats.  PF_K_COPY_WAIT is no
+ * kernel: it brackets the point where the fill stream waits for a streamed layer's host-to-HBM copy, so its
+ * total is the time the fill stream sat idle inside its chunks because weights had not arrived. */
 enum { PF_K_GEMM_QKV = 0, PF_K_GEMM_OUT = 1, PF_K_GEMM_FFN1 = 2, PF_K_GEMM_FFN2 = 3, PF_K_ATTENTION = 4,
-       PF_K_LAYERNORM = 5, PF_K_EMBED = 6, PF_KERNEL_CLASSES = 16 };
+       PF_K_LAYERNORM = 5, PF_K_EMBED = 6, PF_K_COPY_WAIT = 7, PF_KERNEL_CLASSES = 16 };
 
 /* instructions of the emulated main-job stage (Sec. 4.2: forward / backward of a microbatch,
  * and the pipeline bubble instruction) */
@@ -257,6 +259,21 @@ int32_t pf_select_config(const pf_bubble* B, int32_t nB, const pf_node* const* c
                          int32_t* best, int32_t* replicas_out, int32_t* cycles_out,
                          int32_t* chunks_out);
 
+/* Configuration choice for a stream of jobs of one kind (Sec. 4.3: when a fill job completes the Executor takes the
+ * next one, which starts in what is left of the same bubble).  A plan of ONE job counts the rest of the bubble in
+ * which the job ends as used up, which favours configurations whose single job happens to end near a bubble's
+ * end.  Here configuration c is compared on a run of r_c = max(1, ceil(horizon_cycles * U / dur(F_c))) jobs back
+ * to back, U = summed usable duration of the fillable bubbles of one cycle (fill fraction and switch time applied
+ * as in pf_plan_bubbles): the run's chain is F_c repeated r_c times and processes samples[c] * r_c samples; the
+ * runs are then compared exactly as in pf_select_config (same tie-breaks, infeasible ones skipped).
+ * runs_out / cycles_out / chunks_out (host, n_cfg entries each, may be NULL): r_c, and the cycles and chunks the
+ * run's plan takes (0 for infeasible configurations).  horizon_cycles >= 1. */
+int32_t pf_select_config_stream(const pf_bubble* B, int32_t nB, const pf_node* const* chains,
+                                const int32_t* n_nodes, const int64_t* samples, int32_t n_cfg,
+                                int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
+                                int32_t horizon_cycles, int32_t* best, int32_t* runs_out, int32_t* cycles_out,
+                                int32_t* chunks_out);
+
 /* ---- job description -> chain of nodes (Sec. 4.3: the job's graph is flattened into a chain) ---- */
 /* Writes the node list of one replica (g microbatches): [EMBED] L x LAYER_FWD FINAL_LN, and for
  * training HEAD_LOSS, L x LAYER_BWD (last layer first), OPT.  mem_bytes is the node's peak HBM
@@ -432,7 +449,7 @@ int32_t pf_ctx_read_params(pf_ctx* ctx, int32_t what, int32_t layer, void* dst, 
                            void* stream);
 
 /* Sampling for pf_ctx_kernel_timing: only every n-th launch of an enabled class is bracketed by events
- * (n >= 1, default 1).  An event pair costs about 10 us of stream time around the launch it brackets, so a
+ * (n >= 1, default 1; PF_K_COPY_WAIT is never sampled).  An event pair costs about 10 us of stream time around the launch it brackets, so a
  * caller that times a kernel inside a throughput measurement samples it. */
 int32_t pf_ctx_kernel_timing_every(pf_ctx* ctx, int32_t n);
 

@@ -211,6 +211,25 @@ def choose_configuration(bubbles, configs, fill_ppm=1_000_000, first_bubble=0, s
     return best, plans
 
 
+def choose_configuration_stream(bubbles, configs, horizon_cycles, fill_ppm=1_000_000, first_bubble=0, switch_ns=0):
+    """Configuration choice when jobs of one kind follow each other (Sec. 4.3: the Executor takes the
+    next fill job when one completes, in the middle of a bubble).  Reading: a plan of one job counts
+    the rest of its last bubble as used, so configuration c is judged on a run of
+    r_c = max(1, ceil(horizon_cycles * U / dur(F_c))) jobs back to back, U = the summed usable duration
+    of one bubble cycle; the run is one long chain (F_c repeated r_c times, samples * r_c) and the runs
+    are compared like single jobs in choose_configuration.
+    Returns (best_index, runs, plans) with plans as in choose_configuration."""
+    U = sum(e for e, b in zip(effective_durations(bubbles, fill_ppm, switch_ns), bubbles) if b["fillable"])
+    runs, long_cfgs = [], []
+    for cfg in configs:
+        dur = sum(n[0] for n in cfg["F"])
+        r = max(1, -(-(horizon_cycles * U) // dur)) if dur > 0 else 1
+        runs.append(r)
+        long_cfgs.append(dict(F=list(cfg["F"]) * r, samples=cfg["samples"] * r))
+    best, plans = choose_configuration(bubbles, long_cfgs, fill_ppm, first_bubble, switch_ns)
+    return best, runs, plans
+
+
 # --------------------------------------------------------------------------------------
 # chain of graph nodes for a transformer fill job (Sec. 4.3: "linearizes the computational
 # graph and its profiles, turning it into a sequence of nodes with sequential dependency")

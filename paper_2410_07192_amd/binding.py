@@ -35,9 +35,9 @@ EXPORTS = [
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
     "pf_ctx_set_replan", "pf_main_opt_state_bytes", "pf_ctx_set_main_offload", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
     "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd", "pf_op_layernorm_bwd", "pf_op_transpose", "pf_op_gemm_tn",
-    "pf_op_layernorm_bwd_static",
+    "pf_op_layernorm_bwd_static", "pf_select_config_stream",
 ]
-PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED = range(7)
+PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED, PF_K_COPY_WAIT = range(8)
 
 
 class PipeFillError(RuntimeError):
@@ -119,6 +119,8 @@ def _load():
     lib.pf_offload_plan.argtypes = [I32, I32, I32, I64, I64, I64, I64, I64, P(I64), P(I64), I32, P(I32)]
     lib.pf_plan_bubbles_from.argtypes = [P(pf_bubble), I32, P(pf_node), I32, I64, I64, I32, I64, P(pf_chunk), I32, P(I32),
                                          P(I32)]
+    lib.pf_select_config_stream.argtypes = [P(pf_bubble), I32, P(P(pf_node)), P(I32), P(I64), I32, I64, I64, I32, I32,
+                                            P(I32), P(I32), P(I32), P(I32)]
     lib.pf_select_config.argtypes = [P(pf_bubble), I32, P(P(pf_node)), P(I32), P(I64), I32, I64, I64, I32,
                                      P(I32), P(I32), P(I32), P(I32)]
     lib.pf_build_chain.argtypes = [P(pf_model_desc), P(pf_exec_config), P(pf_node), I32, P(I32)]
@@ -306,6 +308,26 @@ def pf_select_config(bubbles, configs, fill_ppm=1_000_000, switch_ns=0, first_bu
         return -1, list(rep), list(cyc), list(chk)
     _check(rc)
     return best.value, list(rep), list(cyc), list(chk)
+
+
+def pf_select_config_stream(bubbles, configs, fill_ppm=1_000_000, switch_ns=0, first_bubble=0, horizon_cycles=8):
+    """configs: list of dicts (F, samples).  Returns (best, runs[], cycles[], chunks[])."""
+    B = bubbles_to_c(bubbles)
+    n = len(configs)
+    keep = [nodes_to_c(c["F"]) for c in configs]
+    chains = (C.POINTER(pf_node) * n)(*[C.cast(a, C.POINTER(pf_node)) for a in keep])
+    nn = (C.c_int32 * n)(*[len(c["F"]) for c in configs])
+    samples = (C.c_int64 * n)(*[c["samples"] for c in configs])
+    best = C.c_int32(-1)
+    runs = (C.c_int32 * n)()
+    cyc = (C.c_int32 * n)()
+    chk = (C.c_int32 * n)()
+    rc = lib.pf_select_config_stream(B, len(bubbles), chains, nn, samples, n, fill_ppm, switch_ns, first_bubble,
+                                     horizon_cycles, C.byref(best), runs, cyc, chk)
+    if rc == PF_ERR_INFEASIBLE:
+        return -1, list(runs), list(cyc), list(chk)
+    _check(rc)
+    return best.value, list(runs), list(cyc), list(chk)
 
 
 # ------------------------------------------------------------------------------------------ model

@@ -378,4 +378,45 @@ int32_t pf_select_config(const pf_bubble* B, int32_t nB, const pf_node* const* c
   return PF_OK;
 }
 
+int32_t pf_select_config_stream(const pf_bubble* B, int32_t nB, const pf_node* const* chains, const int32_t* n_nodes,
+                                const int64_t* samples, int32_t n_cfg, int64_t fill_ppm, int64_t switch_ns,
+                                int32_t first_bubble, int32_t horizon_cycles, int32_t* best, int32_t* runs_out,
+                                int32_t* cycles_out, int32_t* chunks_out) {
+  if (bad_bubbles(B, nB) || !chains || !n_nodes || !samples || n_cfg <= 0 || !best || fill_ppm < 0 ||
+      fill_ppm > 1000000 || switch_ns < 0 || horizon_cycles < 1)
+    return pf::fail(PF_ERR_ARG, "pf_select_config_stream: bad argument");
+  // usable time of one cycle, as Algorithm 1 sees it
+  __int128 usable = 0;
+  for (int32_t i = 0; i < nB; ++i) {
+    if (!B[i].fillable) continue;
+    const int64_t e = (int64_t)((__int128)B[i].dur_ns * fill_ppm / 1000000) - switch_ns;
+    if (e > 0) usable += e;
+  }
+  std::vector<std::vector<pf_node>> runs((size_t)n_cfg);
+  std::vector<const pf_node*> ptrs((size_t)n_cfg);
+  std::vector<int32_t> lens((size_t)n_cfg);
+  std::vector<int64_t> smp((size_t)n_cfg);
+  for (int32_t c = 0; c < n_cfg; ++c) {
+    if (bad_nodes(chains[c], n_nodes[c]) || samples[c] < 0)
+      return pf::fail(PF_ERR_ARG, "pf_select_config_stream: bad chain %d", c);
+    __int128 dur = 0;
+    for (int32_t j = 0; j < n_nodes[c]; ++j) dur += chains[c][j].dur_ns;
+    __int128 r = 1;
+    if (dur > 0) {
+      r = (usable * horizon_cycles + dur - 1) / dur;
+      if (r < 1) r = 1;
+    }
+    if (r * n_nodes[c] > ((__int128)1 << 24))
+      return pf::fail(PF_ERR_ARG, "pf_select_config_stream: the run of chain %d would have more than 2^24 nodes", c);
+    runs[c].reserve((size_t)(r * n_nodes[c]));
+    for (int64_t k = 0; k < (int64_t)r; ++k) runs[c].insert(runs[c].end(), chains[c], chains[c] + n_nodes[c]);
+    ptrs[c] = runs[c].data();
+    lens[c] = (int32_t)runs[c].size();
+    smp[c] = samples[c] * (int64_t)r;
+    if (runs_out) runs_out[c] = (int32_t)r;
+  }
+  return pf_select_config(B, nB, ptrs.data(), lens.data(), smp.data(), n_cfg, fill_ppm, switch_ns, first_bubble, best,
+                          nullptr, cycles_out, chunks_out);
+}
+
 }  // extern "C"

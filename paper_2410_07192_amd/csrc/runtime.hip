@@ -252,6 +252,25 @@ int32_t pf_load_layer_async(pf_ctx* c, int32_t layer, int32_t slot, void* copy_s
   return rc;
 }
 
+// ---- optional event timing of kernel classes ---------------------------------------------------------
+struct TimedScope {
+  pf_ctx* c;
+  hipStream_t st;
+  hipEvent_t end = nullptr;
+  TimedScope(pf_ctx* ctx, int32_t cls, hipStream_t s) : c(ctx), st(s) {
+    if (!((c->timing_mask >> cls) & 1u) || c->timing_used >= c->timing_pool.size()) return;
+    if (cls != PF_K_COPY_WAIT && c->timing_every > 1 && (c->cls_seen[cls]++ % c->timing_every) != 0) return;   // sampled launches only (waits are summed: all of them count)
+    pf_ctx::TimedPair& p = c->timing_pool[c->timing_used];
+    if (hipEventRecord(p.a, st) != hipSuccess) return;
+    p.cls = cls;
+    end = p.b;
+    ++c->timing_used;
+  }
+  ~TimedScope() {
+    if (end) (void)hipEventRecord(end, st);
+  }
+};
+
 static int32_t find_slot(const pf_ctx* c, int32_t layer) {
   for (int32_t i = 0; i < (int32_t)c->slot_layer.size(); ++i)
     if (c->slot_layer[i] == layer) return i;
@@ -278,29 +297,13 @@ static int32_t acquire_layer(pf_ctx* c, int32_t layer, hipStream_t fs, int32_t* 
     int32_t rc = load_into(c, nl, ps, c->copy_stream);
     if (rc != PF_OK) return rc;
   }
-  PF_HIP(hipStreamWaitEvent(fs, c->slot_ready[s], 0));
+  {
+    TimedScope t(c, PF_K_COPY_WAIT, fs);   // when enabled: how long the fill stream has nothing to run until the copy lands
+    PF_HIP(hipStreamWaitEvent(fs, c->slot_ready[s], 0));
+  }
   *slot_out = s;
   return PF_OK;
 }
-
-// ---- optional event timing of kernel classes ---------------------------------------------------------
-struct TimedScope {
-  pf_ctx* c;
-  hipStream_t st;
-  hipEvent_t end = nullptr;
-  TimedScope(pf_ctx* ctx, int32_t cls, hipStream_t s) : c(ctx), st(s) {
-    if (!((c->timing_mask >> cls) & 1u) || c->timing_used >= c->timing_pool.size()) return;
-    if (c->timing_every > 1 && (c->cls_seen[cls]++ % c->timing_every) != 0) return;   // sampled launches only
-    pf_ctx::TimedPair& p = c->timing_pool[c->timing_used];
-    if (hipEventRecord(p.a, st) != hipSuccess) return;
-    p.cls = cls;
-    end = p.b;
-    ++c->timing_used;
-  }
-  ~TimedScope() {
-    if (end) (void)hipEventRecord(end, st);
-  }
-};
 
 static int32_t drain_timing(pf_ctx* c) {
   PF_HIP(hipDeviceSynchronize());

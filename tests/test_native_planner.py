@@ -370,24 +370,36 @@ def test_binding_asks_for_more_hardware_queues():
     assert int(os.environ["GPU_MAX_HW_QUEUES"]) >= 8
 
 
-def test_streamed_configuration_is_chosen_on_a_run_of_batches():
-    """One batch of four microbatches in three 80 ms bubbles beats one single-microbatch batch per bubble when the
-    rest of that bubble counts as lost (Algorithm 1 on a single batch), although it is the slowest per token; on a
-    run of back-to-back batches, which is what the Executor executes, the fastest configuration wins."""
-    import collections
-    import bench
-    from paper_2410_07192_amd import binding as pf
-    Node = collections.namedtuple("Node", "dur_ns mem_bytes op layer mb_first mb_count")
-    def chain(layer_ns, g):
-        return [Node(layer_ns, 1 << 30, pf.PF_OP_LAYER_FWD, l, 0, g) for l in range(24)]
-    chains = [chain(1_750_000, 1), chain(3_370_000, 2), chain(8_800_000, 4)]       # 42, 81 and 211 ms per batch
-    samples = [16, 32, 64]
+def test_stream_selection_bit_exact_and_the_worked_case():
+    """pf_select_config_stream against the checker on random instances, and the case that motivated it: one batch
+    of four microbatches in three 80 ms bubbles beats one single-microbatch batch per bubble when the rest of that
+    bubble counts as lost (Algorithm 1 on a single batch), although it is the slowest per token; on a run of
+    back-to-back batches, which is what the Executor executes, the fastest configuration wins."""
+    rng = np.random.default_rng(35)
+    for trial in range(200):
+        bubbles, _ = _random_cycle(rng, 9500 + trial)
+        configs = []
+        for c in range(int(rng.integers(1, 5))):
+            _, _, F = synth.make_planner_instance(30000 + 10 * trial + c, int(rng.integers(1, 12)), 1,
+                                                  int(rng.integers(5, 1500)), 50)
+            configs.append(dict(F=F, samples=int(rng.integers(1, 64))))
+        ppm = int(rng.choice([1_000_000, 680_000]))
+        h = int(rng.integers(1, 6))
+        best, runs, plans = op.choose_configuration_stream(bubbles, configs, h, ppm, 0, 0)
+        gbest, gruns, cyc, chk = pf.pf_select_config_stream(bubbles, configs, ppm, 0, 0, h)
+        assert gbest == best and gruns == runs
+        for c, pl in enumerate(plans):
+            assert (cyc[c], chk[c]) == ((0, 0) if pl is None else (pl[2], len(pl[0])))
+    layer = lambda ns, g: [(ns, 1 << 30, pf.PF_OP_LAYER_FWD, l, 0, g) for l in range(24)]
+    configs = [dict(F=layer(1_750_000, 1), samples=16), dict(F=layer(3_370_000, 2), samples=32),
+               dict(F=layer(8_800_000, 4), samples=64)]                      # 42, 81 and 211 ms per batch
     bubble = 80_000_000
     windows = [dict(start=bubble // 2, dur=bubble, free=8 << 30, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
-    single = pf.pf_select_config(windows, [dict(F=[tuple(n) for n in c], samples=s) for c, s in zip(chains, samples)],
-                                 900_000, 100_000, 0)
-    assert single[0] == 2                                     # what a single-batch comparison picks
-    best, rep, cyc, runs = bench.choose_streamed_config(pf, windows, chains, samples, bubble, 900_000, 100_000)
-    assert best == 1                                          # 32 samples per 81 ms
-    rate = [s * r * k / c for s, r, k, c in zip(samples, runs, rep, cyc)]
+    assert pf.pf_select_config(windows, configs, 900_000, 100_000, 0)[0] == 2   # what a single-batch comparison picks
+    best, runs, cyc, _ = pf.pf_select_config_stream(windows, configs, 900_000, 100_000, 0, 8)
+    assert best == 1                                                          # 32 samples per 81 ms
+    rate = [c["samples"] * r / k for c, r, k in zip(configs, runs, cyc)]
     assert rate[1] > rate[0] > rate[2]
+    with pytest.raises(pf.PipeFillError) as e:
+        pf.pf_select_config_stream(windows, configs, 900_000, 100_000, 0, 0)
+    assert e.value.code == pf.PF_ERR_ARG

@@ -304,6 +304,40 @@ def test_choose_configuration_against_fractions():
             assert best == min(scored)[2]
 
 
+def test_stream_choice_converges_to_the_long_run_rate():
+    """Sec. 4.3 (a completed job is followed by the next one in the same bubble): judged on a long enough run of
+    back-to-back jobs, the chosen configuration is the one whose unbounded stream completes most samples per cycle.
+    The long-run rate is measured here by brute force -- walk the bubbles one by one and pack nodes with the
+    rule of Algorithm 1 until many cycles have passed -- without calling the partitioning function."""
+    def long_run_rate(B_eff, F, samples, cycles=400):
+        done, pos = 0, 0
+        for _ in range(cycles):
+            for limit in B_eff:
+                used = 0
+                while used + F[pos][0] < limit:
+                    used += F[pos][0]
+                    pos += 1
+                    if pos == len(F):
+                        pos, done = 0, done + samples
+        return Fraction(done, cycles)
+    rng = np.random.default_rng(12)
+    disagreements = 0
+    for trial in range(40):
+        nb = int(rng.integers(1, 4))
+        bubbles = mk_bubbles([int(rng.integers(400, 900)) for _ in range(nb)], [10] * nb)
+        configs = []
+        for c in range(3):
+            n = int(rng.integers(3, 9))
+            configs.append(dict(F=[(int(rng.integers(20, 120)), 1) for _ in range(n)], samples=int(rng.integers(1, 9))))
+        B_eff = [b["dur"] for b in bubbles]
+        rates = [long_run_rate(B_eff, c["F"], c["samples"]) for c in configs]
+        best, runs, _ = op.choose_configuration_stream(bubbles, configs, 200)
+        assert rates[best] >= max(rates) * Fraction(99, 100), (trial, rates, best)     # within the horizon's granularity
+        single, _ = op.choose_configuration(bubbles, configs)
+        disagreements += rates[single] < max(rates) * Fraction(95, 100)
+    assert disagreements >= 3        # the single-job comparison does pick a clearly slower configuration at times
+
+
 def test_chain_nodes_shape():
     """The flattened graph (Sec. 4.3) of the workloads, against counts that follow from the model sizes alone, and
     the parameter counts against the published sizes of the architectures the workloads stand for."""
