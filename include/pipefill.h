@@ -365,6 +365,13 @@ int32_t pf_profile_chain(pf_ctx* ctx, pf_node* F, int32_t nF, int32_t warmup, in
 int32_t pf_main_stage_step(pf_ctx* ctx, int32_t instr, int32_t index, const void* io,
                            void* main_stream);
 
+/* What the stage hands to its neighbours (Sec. 4.2: the engine's send instructions follow the compute ones): copies
+ * to dst (device, [batch][seq][d], model dtype) what = 0: the output of the forward of microbatch `index` (valid
+ * from its forward until the slot's next forward), what = 1: the gradient with respect to the stage's input left
+ * by the backward of microbatch `index` (valid until the slot's next backward).  Enqueues on stream.
+ * PF_ERR_CAPACITY if dst_bytes is too small, PF_ERR_STATE if ctx is not a main-stage context. */
+int32_t pf_main_stage_read(pf_ctx* ctx, int32_t what, int32_t index, void* dst, int64_t dst_bytes, void* stream);
+
 /* Result of one emulated main-job iteration. */
 typedef struct pf_timeline_stats {
   int64_t iter_ns;          /* wall time of the iteration                                        */

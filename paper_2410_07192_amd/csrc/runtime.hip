@@ -602,6 +602,17 @@ int32_t pf_main_stage_step(pf_ctx* c, int32_t instr, int32_t index, const void* 
   return pf::train_main_step(c, instr, index, io, (hipStream_t)main_stream);
 }
 
+int32_t pf_main_stage_read(pf_ctx* c, int32_t what, int32_t index, void* dst, int64_t dst_bytes, void* stream) {
+  if (!c || !dst || index < 0 || (what != 0 && what != 1)) return pf::fail(PF_ERR_ARG, "pf_main_stage_read: bad argument");
+  if (!c->tr || c->md.vocab != 0)
+    return pf::fail(PF_ERR_STATE, "pf_main_stage_read: needs a training context without vocabulary");
+  if (dst_bytes < c->lay.act) return pf::fail(PF_ERR_CAPACITY, "pf_main_stage_read: %lld bytes needed", (long long)c->lay.act);
+  const int64_t slot = index % c->cfg.g, L = c->md.n_layers;
+  const char* src = what == 0 ? c->tr->ckpt + (slot * (L + 1) + L) * c->lay.act : c->tr->G + slot * c->lay.act;
+  PF_HIP(hipMemcpyAsync(dst, src, (size_t)c->lay.act, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+  return PF_OK;
+}
+
 int32_t pf_main_opt_state_bytes(pf_ctx* c, int64_t* bytes) {
   if (!c || !bytes) return pf::fail(PF_ERR_ARG, "pf_main_opt_state_bytes: bad argument");
   if (!c->tr || c->md.vocab != 0)

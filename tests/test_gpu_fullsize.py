@@ -338,3 +338,113 @@ def test_bench_line_contract():
     # the default workload is the one the whole metric is defined on: real main-stage kernels, so a slowdown exists
     assert d["config"]["workload"].startswith("cfg5") and d["main_slowdown_pct"] is not None
     assert abs(d["main_slowdown_pct"]) < 10.0 and d["pct_bubble_spanned"] >= d["pct_bubble_filled"]
+
+
+_BLOB_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_g", "ln2_b", "w_1", "b_1", "w_2", "b_2")
+
+
+def _blob_to_params(pf, md, blob):
+    """Device blob in the library's layout (bf16, matrices [out][in]) -> float64 arrays in the checker's layout
+    ([in][out] matrices).  Byte plumbing only."""
+    _, off = pf.pf_layer_blob_layout(md)
+    d, f = md.d_model, md.d_ff
+    shapes = {"ln1_g": (d,), "ln1_b": (d,), "w_qkv": (3 * d, d), "b_qkv": (3 * d,), "w_o": (d, d), "b_o": (d,),
+              "ln2_g": (d,), "ln2_b": (d,), "w_1": (f, d), "b_1": (f,), "w_2": (d, f), "b_2": (d,)}
+    out = {}
+    for i, name in enumerate(_BLOB_NAMES):
+        n = int(np.prod(shapes[name]))
+        a = blob[off[i]:off[i] + 2 * n].view(torch.bfloat16).reshape(shapes[name]).double().cpu().numpy()
+        out[name] = a.T if a.ndim == 2 else a        # a view: the matrix products take either layout
+    return out
+
+
+def test_main_stage_layer_full_shape_forward_and_backward():
+    """One layer of the d=8192 / 64-head / FFN-32768 main-job stage on a whole sequence of 2048 tokens: forward
+    output, input gradient and EVERY parameter gradient against the float64 checker.  At this size the bf16 weight
+    gradients take the transposes + accumulating NT GEMM path (results of 8192 x 8192 and more), which no smaller
+    layer reaches."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(1, 8192, 64, 32768, 2048, 1, 0, True, "bf16")
+    md = pf.model_desc(shape)
+    blob = dev.random_layer_blob(md, 900)
+    P = _blob_to_params(pf, md, blob)
+    m = dev.RawModel(shape, [blob], None, None, None, None, g=1, training=True)
+    try:
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(901)
+        x = torch.randn(1, shape.seq_len, shape.d_model, device="cuda", generator=gen).to(torch.bfloat16)
+        dy = torch.randn(1, shape.seq_len, shape.d_model, device="cuda", generator=gen).to(torch.bfloat16)
+        st = torch.cuda.Stream()
+        m.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, 0, x.data_ptr(), st.cuda_stream)
+        y = torch.empty_like(x)
+        m.ctx.pf_main_stage_read(0, 0, y.data_ptr(), y.numel() * 2, st.cuda_stream)
+        m.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, 0, dy.data_ptr(), st.cuda_stream)
+        dx = torch.empty_like(x)
+        m.ctx.pf_main_stage_read(1, 0, dx.data_ptr(), dx.numel() * 2, st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        # the checker, on the same bf16 values widened to float64
+        yr, cache = ot.layer_forward(x.double().cpu().numpy(), P, shape.n_heads, True, shape.eps, keep=True)
+        assert rel_err(y.float().cpu().numpy(), yr) < 2e-2
+        dxr, G = ot.layer_backward(dy.double().cpu().numpy(), cache, P, shape.n_heads)
+        del cache
+        assert rel_err(dx.float().cpu().numpy(), dxr) < 2e-2
+        md32 = pf.pf_model_desc.from_buffer_copy(m.md)
+        md32.dtype = pf.PF_DTYPE_F32
+        size, _ = pf.pf_layer_blob_layout(md32)
+        buf = torch.empty(size, dtype=torch.uint8, device="cuda")
+        m.ctx.pf_ctx_read_params(0, 0, buf.data_ptr(), size)
+        m.ctx.pf_ctx_sync()
+        got = pf.unpack_layer_blob_f32(m.md, buf.cpu().numpy())[0]
+        for k, ref in G.items():
+            assert rel_err(got[k], ref) < 2e-2, k
+    finally:
+        m.close()
+
+
+def test_training_head_loss_and_adam_at_the_full_vocabulary():
+    """The training fill job's head at its real size (d=1024, 8 x 1024 tokens, vocabulary 50257, padded to 50304
+    inside the library): loss and every gradient of one microbatch through one layer against the float64 checker,
+    then the Adam step at full size (51.5 M embedding and 12.6 M layer parameters) against the checker's update
+    rule applied to the gradients the device produced."""
+    from test_gpu_training import read_emb, read_layer
+    pf, dev = _mods()
+    s4 = synth.WORKLOADS["cfg4"]
+    shape = synth.ModelShape(1, s4.d_model, s4.n_heads, s4.d_ff, s4.seq_len, s4.batch, s4.vocab, True, "bf16")
+    params = synth.make_model_params(shape, seed=310)
+    Pr = ot.cast_params(params)
+    lr = 1e-3
+    m = dev.DeviceModel(shape, params, training=True, adam=pf.pf_adam(lr, 0.9, 0.999, 1e-8, 2))
+    try:
+        ids = synth.make_token_ids(shape, seed=311)
+        m.set_io(dev.to_device(ids[None, None].astype(np.int32)), 1, None, 0)
+        st = torch.cuda.Stream()
+        nF = len(m.chain)
+        m.ctx.pf_fill_chunk(pf.pf_chunk(0, 0, 0, nF, 0, 0), m.chain, stream=st.cuda_stream)   # accumulates, no step yet
+        m.ctx.pf_ctx_sync()
+        loss_ref, G = ot.model_loss_and_grads(ids, Pr, shape.n_heads, True, shape.eps)
+        g_layer, g_emb = read_layer(m, 0, 0), read_emb(m, 0)
+        for k, ref in G["layers"][0].items():
+            assert rel_err(g_layer[k], ref) < 2e-2, k
+        for k in ("tok_emb", "pos_emb", "lnf_g", "lnf_b"):
+            assert rel_err(g_emb[k], G[k]) < 2e-2, k
+        # rows of the vocabulary that no token and no target touches still get the softmax's (small) gradient:
+        # compared on their own scale
+        untouched = np.setdiff1d(np.arange(shape.vocab), ids.reshape(-1))
+        assert len(untouched) > 1000
+        assert rel_err(g_emb["tok_emb"][untouched], G["tok_emb"][untouched]) < 2e-2
+        # the same microbatch again completes the accumulation of two: Adam on the mean gradient = that gradient
+        m.ctx.pf_fill_chunk(pf.pf_chunk(0, 0, nF, 2 * nF, 0, 0), m.chain, stream=st.cuda_stream)
+        m.ctx.pf_ctx_sync()
+        loss, steps = m.ctx.pf_ctx_train_state()
+        assert steps == 1 and abs(loss - loss_ref) < 2e-3 * loss_ref
+        for name, g_dev, th0, got in (("tok_emb", g_emb["tok_emb"], Pr["tok_emb"], read_emb(m, 1)["tok_emb"]),
+                                      ("w_1", g_layer["w_1"], Pr["layers"][0]["w_1"], read_layer(m, 1, 0)["w_1"])):
+            g64 = g_dev.astype(np.float64)                     # two equal microbatches: the mean is the gradient itself
+            th1, m1, v1 = ot.adam_step(th0, 0.0, 0.0, g64, 1, lr=lr)
+            # fp32 arithmetic on an update of size lr: the error is a few ulps of theta, far below the update
+            assert np.abs(got.astype(np.float64) - th1).max() < 1e-3 * lr + 4e-7 * np.abs(th0).max(), name
+        mom = read_emb(m, 2)["tok_emb"].astype(np.float64)
+        assert np.abs(mom - 0.1 * g_emb["tok_emb"]).max() <= 1e-6 * np.abs(mom).max() + 1e-12
+        assert not np.any(read_emb(m, 0)["tok_emb"])         # accumulators cleared by the step
+    finally:
+        m.close()
