@@ -21,6 +21,8 @@ Workloads (--workload):
   cfg2            12-layer bf16 encoder inference fill job, weights resident, 1F1B p=8 m=16
                   t_f=15 ms t_b=30 ms, 24 GiB free; the steps are shared evenly by the 8 stages.
                   --schedule gpipe fills the two contiguous windows of a GPipe main job instead.
+  probe           the doubling probe of Sec. 4.2 against the real d=8192 main stage (small pipeline), next
+                  to the closed-form windows; not a throughput line.
   cfg3            24-layer d=2048 causal decoder inference, weights streamed from pinned host memory,
                   explicit 40 ms bubbles separated by 20 ms, 8 GiB cap; g microbatches per layer
                   visit chosen by the planner.
@@ -617,12 +619,62 @@ def run_cfg5(args, np, torch, pf, dev, synth):
     return out
 
 
+# --------------------------------------------------------------------------------------------- probe
+def run_probe(args, np, torch, pf, dev, synth):
+    """Bubble characterisation (Sec. 4.2) of the real d=8192 main stage: the doubling probe with the stage's kernels
+    running and the other stages simulated from the measured t_f / t_b, next to the closed-form windows and to the
+    host simulation of the same probe.  A small pipeline (p=4, m=8 by default) keeps the probe to about a minute;
+    not a throughput measurement: `value` is the number of windows probed."""
+    shape5 = synth.WORKLOADS["cfg5"]
+    p, m, stage = args.probe_p, args.probe_m, args.stage if args.stage < args.probe_p else 1
+    md5 = pf.model_desc(shape5)
+    blobs5 = [dev.random_layer_blob(md5, 500 + l) for l in range(shape5.n_layers)]
+    main = dev.RawModel(shape5, blobs5, None, None, None, None, g=min(p - stage, m), training=True)
+    del blobs5
+    main.blobs = []
+    torch.cuda.empty_cache()
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    x = torch.randn(shape5.batch, shape5.seq_len, shape5.d_model, device="cuda", generator=gen).to(torch.bfloat16)
+    st = torch.cuda.Stream()
+    tfs, tbs = [], []
+    for _ in range(4):      # an instruction as the probe sees it: launch to the end of a host synchronisation
+        torch.cuda.synchronize()
+        t0 = time.perf_counter_ns()
+        main.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, 0, x.data_ptr(), st.cuda_stream)
+        st.synchronize()
+        t1 = time.perf_counter_ns()
+        main.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, 0, x.data_ptr(), st.cuda_stream)
+        st.synchronize()
+        t2 = time.perf_counter_ns()
+        tfs.append(t1 - t0)
+        tbs.append(t2 - t1)
+    tf, tb = sorted(tfs[1:])[1], sorted(tbs[1:])[1]
+    first, tol = int(args.probe_first_ms * 1e6), args.probe_tol_ppm
+    t0 = time.perf_counter()
+    est, base = pf.pf_probe_bubbles_live(main.ctx, x.data_ptr(), p, m, stage, tf, tb, first, tol, st.cuda_stream)
+    wall = time.perf_counter() - t0
+    windows = pf.pf_schedule_1f1b(p, m, stage, tf, tb, 0, True, 0)
+    host = pf.pf_probe_bubbles(p, m, stage, tf, tb, first, tol)
+    main.close()
+    return {"metric": "bubble windows probed", "value": len(est), "unit": "windows", "n_gpus": 1, "steps": 1, "warmup": 0,
+            "ms_per_step": wall * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+            "data": "synthetic",
+            "config": {"workload": f"probe: doubling probe of the d=8192 main stage (3 layers, seq 2048), 1F1B p={p} m={m} "
+                                   f"stage {stage}, first wait {args.probe_first_ms:g} ms, tolerance {tol} ppm"},
+            "t_f_ms": tf * 1e-6, "t_b_ms": tb * 1e-6, "undisturbed_period_ms": base * 1e-6,
+            "schedule_iteration_ms": (m + p - 1) * (tf + tb) * 1e-6,
+            "windows_ms": [w["dur"] * 1e-6 for w in windows], "window_kinds": [w["kind"] for w in windows],
+            "estimates_ms": [e * 1e-6 for e in est], "host_simulation_estimates_ms": [e * 1e-6 for e in host],
+            "roofline": None}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5", "probe"])
     ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
     ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
     ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles (cfg2)")
@@ -639,6 +691,10 @@ def main():
                     help="cfg5: the main stage ends each iteration with a gradient synchronisation and an optimizer "
                          "update, and offloads optimizer state to pinned host memory around them")
     ap.add_argument("--sync-ms", type=float, default=100.0, help="cfg5 --main-offload: gradient synchronisation time")
+    ap.add_argument("--probe-p", type=int, default=4)
+    ap.add_argument("--probe-m", type=int, default=8)
+    ap.add_argument("--probe-first-ms", type=float, default=5.0, help="probe: first wait tried at a bubble instruction")
+    ap.add_argument("--probe-tol-ppm", type=int, default=20_000, help="probe: slowdown of the period that counts as none")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device-to-device copy 10 times (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -647,7 +703,7 @@ def main():
         print("bench.py: this build runs on ONE GPU; the fill path has no cross-GPU step "
               "(one independent Executor per device). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
-    defaults = {"cfg2": (16, 2), "cfg3": (50, 3), "cfg4": (16, 1), "cfg5": (6, 1)}
+    defaults = {"cfg2": (16, 2), "cfg3": (50, 3), "cfg4": (16, 1), "cfg5": (6, 1), "probe": (1, 0)}
     if args.steps is None:
         args.steps = defaults[args.workload][0]
     if args.warmup is None:
@@ -671,7 +727,7 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}))
         return
-    run = {"cfg2": run_cfg2, "cfg3": run_cfg3, "cfg4": run_cfg4, "cfg5": run_cfg5}[args.workload]
+    run = {"cfg2": run_cfg2, "cfg3": run_cfg3, "cfg4": run_cfg4, "cfg5": run_cfg5, "probe": run_probe}[args.workload]
     out = run(args, np, torch, pf, dev, synth)
     print(json.dumps(out))
 

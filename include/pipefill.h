@@ -213,6 +213,23 @@ int32_t pf_probe_bubbles(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int
                          int64_t first_wait_ns, int64_t tol_ppm, int64_t* est_ns, int32_t cap,
                          int32_t* n_out);
 
+/* The same probe against the emulated stage (Sec. 4.2: the engine profiles at the start of the main job).  Stage
+ * `stage` runs for real: its forward and backward instructions are executed by main_ctx on main_stream (as in
+ * pf_main_stage_step, input / upstream gradient main_io) and their finish times are measured on the host; the
+ * other p - 1 stages are simulated from tf_ns / tb_ns and from those measured times (forward j of a stage needs
+ * forward j of the stage before, backward j the backward j of the stage after), and an instruction of the real
+ * stage starts when the simulation says its input has arrived.  At bubble instruction k the stage holds back
+ * for the trial wait.  A trial is four iterations; its period is the time between the ends of the last two.
+ * The undisturbed period is the smaller of two trials without waits (*base_period_ns, may be NULL); the bubble
+ * instructions are then probed one after the other exactly as in pf_probe_bubbles, with tol_ppm absorbing the
+ * run-to-run noise of real kernels (1-2 % is typical).  est_ns, cap, n_out as in pf_probe_bubbles.
+ * Synchronises main_stream after every instruction.  Takes about (4 * windows * log2(window / first_wait))
+ * iterations of the stage.  PF_ERR_ARG if main_ctx has fewer checkpoint slots than min(p - stage, m). */
+int32_t pf_probe_bubbles_live(pf_ctx* main_ctx, const void* main_io, int32_t p, int32_t m, int32_t stage,
+                              int64_t tf_ns, int64_t tb_ns, int64_t first_wait_ns, int64_t tol_ppm,
+                              int64_t* est_ns, int32_t cap, int32_t* n_out, int64_t* base_period_ns,
+                              void* main_stream);
+
 /* Plan of the main job's optimizer-state offload (Sec. 4.2, "Main job offloading"): the moment
  * estimates are only read by the optimizer update, so part of them leaves the device while the
  * iteration runs and the idle windows gain that memory.  One slice leaves with each of the m

@@ -35,7 +35,7 @@ EXPORTS = [
     "pf_fill_chunk_bwd", "pf_fill_chunk", "pf_profile_chain", "pf_main_stage_step", "pf_timeline_run",
     "pf_ctx_set_replan", "pf_main_opt_state_bytes", "pf_ctx_set_main_offload", "pf_ctx_kernel_timing_every", "pf_ctx_train_state", "pf_ctx_read_params", "pf_op_gemm", "pf_op_layernorm", "pf_op_attention",
     "pf_op_embed", "pf_ctx_kernel_timing", "pf_ctx_kernel_stats", "pf_op_attention_bwd", "pf_op_layernorm_bwd", "pf_op_transpose", "pf_op_gemm_tn",
-    "pf_op_layernorm_bwd_static", "pf_select_config_stream", "pf_main_stage_read",
+    "pf_op_layernorm_bwd_static", "pf_select_config_stream", "pf_main_stage_read", "pf_probe_bubbles_live",
 ]
 PF_K_GEMM_QKV, PF_K_GEMM_OUT, PF_K_GEMM_FFN1, PF_K_GEMM_FFN2, PF_K_ATTENTION, PF_K_LAYERNORM, PF_K_EMBED, PF_K_COPY_WAIT = range(8)
 
@@ -136,6 +136,7 @@ def _load():
     lib.pf_fill_chunk.argtypes = [VP, P(pf_chunk), P(pf_node), I32, I64, VP]
     lib.pf_profile_chain.argtypes = [VP, P(pf_node), I32, I32, I32, VP]
     lib.pf_main_stage_step.argtypes = [VP, I32, I32, VP, VP]
+    lib.pf_probe_bubbles_live.argtypes = [VP, VP, I32, I32, I32, I64, I64, I64, I64, P(I64), I32, P(I32), P(I64), VP]
     lib.pf_main_stage_read.argtypes = [VP, I32, I32, VP, I64, VP]
     lib.pf_timeline_run.argtypes = [VP, VP, VP, I32, I32, I32, I64, I64, P(pf_bubble), I32, P(pf_chunk), I32,
                                     P(pf_node), I32, P(I32), VP, VP, P(pf_timeline_stats)]
@@ -239,6 +240,16 @@ def pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm=0):
     out = (C.c_int64 * max(1, n.value))()
     _check(lib.pf_probe_bubbles(p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm, out, n.value, C.byref(n)))
     return [int(out[i]) for i in range(n.value)]
+
+
+def pf_probe_bubbles_live(main_ctx, main_io, p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm, stream=None):
+    """The doubling probe with the stage's instructions run on the device.  Returns (estimates, undisturbed period)."""
+    n = C.c_int32(0)
+    out = (C.c_int64 * (m + 2))()
+    base = C.c_int64(0)
+    _check(lib.pf_probe_bubbles_live(main_ctx.handle, main_io, p, m, stage, tf_ns, tb_ns, first_wait_ns, tol_ppm, out,
+                                     m + 2, C.byref(n), C.byref(base), stream))
+    return [int(out[i]) for i in range(n.value)], int(base.value)
 
 
 def pf_offload_plan(p, m, stage, tf_ns, sync_ns, state_bytes, d2h_bytes_per_s, h2d_bytes_per_s):

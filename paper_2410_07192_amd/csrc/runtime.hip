@@ -8,6 +8,7 @@
 #include <new>
 
 #include "pf_kernels.h"
+#include "pf_pipeline_sim.h"
 
 #define PF_HIP(expr)                                                                              \
   do {                                                                                            \
@@ -876,6 +877,67 @@ int32_t pf_timeline_run(pf_ctx* fc, pf_ctx* mc, const void* main_io, int32_t p, 
   }
   if (tstream) (void)hipStreamDestroy(tstream);
   return rc;
+}
+
+int32_t pf_probe_bubbles_live(pf_ctx* mc, const void* main_io, int32_t p, int32_t m, int32_t stage, int64_t tf_ns,
+                              int64_t tb_ns, int64_t first_wait_ns, int64_t tol_ppm, int64_t* est_ns, int32_t cap,
+                              int32_t* n_out, int64_t* base_period_ns, void* main_stream) {
+  if (!mc || !main_io || p < 1 || m < 1 || stage < 0 || stage >= p || tf_ns <= 0 || tb_ns <= 0 || first_wait_ns < 1 ||
+      tol_ppm < 0 || cap < 0 || !n_out || (cap > 0 && !est_ns) || (int64_t)p * m > (int64_t)1 << 16)
+    return pf::fail(PF_ERR_ARG, "pf_probe_bubbles_live: bad argument");
+  if (!mc->tr || mc->md.vocab != 0)
+    return pf::fail(PF_ERR_STATE, "pf_probe_bubbles_live: needs a training context without vocabulary");
+  if (mc->cfg.g < std::min(p - stage, m))
+    return pf::fail(PF_ERR_ARG, "pf_probe_bubbles_live: stage %d of %d keeps %d microbatches in flight, the main context has "
+                    "checkpoint slots for %d", stage, p, std::min(p - stage, m), mc->cfg.g);
+  std::vector<std::vector<pf::StageOp>> ops;
+  for (int32_t q = 0; q < p; ++q) ops.push_back(pf::stage_ops(p, m, q));
+  int32_t n = 0;
+  for (const pf::StageOp& o : ops[stage]) n += (o.op == 2);
+  *n_out = n;
+  if (n > cap) return pf::fail(PF_ERR_CAPACITY, "pf_probe_bubbles_live: %d windows, capacity %d", n, cap);
+  hipStream_t st = (hipStream_t)main_stream;
+  int32_t rc = PF_OK;
+  // One trial = four iterations of the pipeline: the other stages are simulated from tf_ns / tb_ns, this stage's
+  // instructions run on the device when the simulation says their inputs have arrived (never earlier than the
+  // wall clock allows), and their measured finish times go back into the simulation.
+  auto trial = [&](const std::vector<int64_t>& waits) -> int64_t {
+    (void)hipStreamSynchronize(st);
+    const int64_t origin = now_ns();
+    return pf::period_with_waits(p, m, tf_ns, tb_ns, stage, waits, ops, [&](int32_t op, int32_t idx, int64_t start) -> int64_t {
+      wait_until(origin + start);
+      rc = pf_main_stage_step(mc, op == 0 ? PF_INSTR_FWD : PF_INSTR_BWD, idx, main_io, main_stream);
+      if (rc != PF_OK) return -1;
+      if (hipStreamSynchronize(st) != hipSuccess) {
+        rc = pf::fail(PF_ERR_HIP, "pf_probe_bubbles_live: stream synchronisation failed");
+        return -1;
+      }
+      return now_ns() - origin;
+    });
+  };
+  std::vector<int64_t> waits(n, 0);
+  (void)trial(waits);   // warm-up
+  int64_t base = trial(waits);
+  if (base >= 0) base = std::min(base, trial(waits));
+  if (base < 0) return rc;
+  if (base_period_ns) *base_period_ns = base;
+  const int64_t limit = base + (int64_t)((__int128)base * tol_ppm / 1000000);
+  for (int32_t k = 0; k < n; ++k) {
+    int64_t w = first_wait_ns;
+    for (;;) {
+      const int64_t keep = waits[k];
+      waits[k] = w;
+      const int64_t per = trial(waits);
+      if (per < 0) return rc;
+      if (per > limit || w > base) {   // a wait longer than a whole iteration cannot be harmless
+        waits[k] = keep;
+        break;
+      }
+      w *= 2;
+    }
+  }
+  for (int32_t k = 0; k < n; ++k) est_ns[k] = waits[k];
+  return PF_OK;
 }
 
 int32_t pf_ctx_set_replan(pf_ctx* c, int32_t enable, int64_t fill_ppm, int64_t switch_ns) {

@@ -582,3 +582,58 @@ def test_gemm_tn_argument_errors():
         assert e.value.code == pf.PF_ERR_ARG
     with pytest.raises(pf.PipeFillError):
         pf.pf_op_gemm_tn(pf.PF_DTYPE_BF16, t.data_ptr() + 2, t.data_ptr(), c.data_ptr(), 8, 8, 64)
+
+
+def test_doubling_probe_against_the_emulated_stage():
+    """Sec. 4.2, bubble characterisation: the probe with the stage's forward / backward kernels really running and
+    the other stages simulated from the measured t_f / t_b.  The estimates are powers of two times the first wait;
+    against the closed-form windows of the same schedule: no estimate is harmless beyond what the stage's idle time
+    allows (each at most its own window plus the slack of the later ones, the sum at most the idle total), and the
+    long fwd-bwd window is found to within the probe's factor of two, where the host simulation of the same probe,
+    fed the measured times, puts it up to one doubling."""
+    pf, dev = _mods()
+    shape = synth.ModelShape(3, 1024, 16, 4096, 1024, 4, 0, True, "bf16")     # t_f about 1 ms, t_b about 3 ms
+    params = synth.make_model_params(shape, seed=47)
+    p, mm, stage = 4, 6, 1
+    m = dev.DeviceModel(shape, params, g=min(p - stage, mm), training=True)
+    try:
+        x = dev.storage_tensor(synth.make_hidden(shape, seed=61), m.md)
+        st = torch.cuda.Stream()
+        import time
+        # t_f, t_b as the probe itself sees an instruction: launch to the end of a host synchronisation, so that the
+        # simulated neighbours are as fast as the real stage and the schedule is balanced
+        tfs, tbs = [], []
+        for _ in range(7):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter_ns()
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_FWD, 0, x.data_ptr(), st.cuda_stream)
+            st.synchronize()
+            t1 = time.perf_counter_ns()
+            m.ctx.pf_main_stage_step(pf.PF_INSTR_BWD, 0, x.data_ptr(), st.cuda_stream)
+            st.synchronize()
+            t2 = time.perf_counter_ns()
+            tfs.append(t1 - t0)
+            tbs.append(t2 - t1)
+        tf, tb = sorted(tfs)[3], sorted(tbs)[3]
+        assert tf > 100_000 and tb > tf
+        first = tf // 4
+        tol = 30_000                                           # 3 %: kernel and host-synchronisation noise
+        est, base = pf.pf_probe_bubbles_live(m.ctx, x.data_ptr(), p, mm, stage, tf, tb, first, tol, st.cuda_stream)
+        windows = pf.pf_schedule_1f1b(p, mm, stage, tf, tb, 1 << 30, True, 0)
+        durs = [w["dur"] for w in windows]
+        assert len(est) == len(durs)
+        ideal = (mm + p - 1) * (tf + tb)
+        assert abs(base - ideal) < 0.08 * ideal                # the undisturbed period is the schedule's iteration time
+        slack = 0.06 * ideal                                   # what the tolerance lets through, plus timing noise
+        assert sum(est) <= sum(durs) + slack
+        for k, e in enumerate(est):
+            assert e == 0 or (e % first == 0 and (e // first) & (e // first - 1) == 0)      # first * 2^i
+            assert e <= sum(durs[k:]) + slack, (k, est, durs)
+        # the long first window (the fwd-bwd bubble) is found to within the probe's factor of two, and the host
+        # simulation of the same probe on the measured times agrees on it up to one doubling; the later, short
+        # windows share what slack the first estimate left, which run-to-run noise distributes differently
+        assert est[0] > durs[0] // 2 - slack
+        host = pf.pf_probe_bubbles(p, mm, stage, tf, tb, first, tol)
+        assert est[0] in (host[0], 2 * host[0], host[0] // 2), (est, host)
+    finally:
+        m.close()
