@@ -307,24 +307,38 @@ def run_cfg2(args, np, torch, pf, dev, synth):
 
 
 # ---------------------------------------------------------------------------------------------- cfg3
-def make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4), n_slots=3):
+def make_cfg3_models(torch, pf, dev, synth, gs=(1, 2, 4), slot_counts=(3,), resident=False, batches=(16,)):
+    """The candidate configurations of the 24-layer decoder fill job (Sec. 4.3: batch size x execution technique):
+    sequences per microbatch x g microbatches per layer visit x {weights streamed from pinned host memory through n
+    HBM slots for n in slot_counts, and, if `resident`, all weights kept in HBM}.  One context per candidate; the
+    pinned blobs (and the device copies for the resident candidates) are shared."""
+    import dataclasses
     shape = synth.WORKLOADS["cfg3"]
     md = pf.model_desc(shape)
     blobs = [dev.random_layer_blob(md, 300 + l, pinned=True) for l in range(shape.n_layers)]
+    dev_blobs = [b.cuda() for b in blobs] if resident else None
     gen = torch.Generator(device="cuda")
     gen.manual_seed(299)
     mk = lambda *s: (torch.randn(*s, device="cuda", generator=gen) * 0.02).to(torch.bfloat16)
     tok, pos = mk(shape.vocab, shape.d_model), mk(shape.seq_len, shape.d_model)
     lnf_g, lnf_b = mk(shape.d_model) + 1.0, mk(shape.d_model)
     models = []
-    for g in gs:
-        mdl = dev.RawModel(shape, blobs, tok, pos, lnf_g, lnf_b, g=g, streamed=True, n_slots=n_slots)
-        n_ring = 2
-        ids = torch.randint(0, shape.vocab, (n_ring, g, shape.batch, shape.seq_len), dtype=torch.int32, device="cuda",
-                            generator=gen)
-        out = dev.empty_storage((1, g, shape.batch, shape.seq_len, shape.d_model), mdl.md)
-        mdl.set_io(ids, n_ring, out, 1)
-        models.append(mdl)
+    techniques = [("streamed", n) for n in slot_counts] + ([("resident", 0)] if resident else [])
+    for tech, n_slots in techniques:
+        for batch in batches:
+            sh = dataclasses.replace(shape, batch=batch)
+            for g in gs:
+                if tech == "streamed":
+                    mdl = dev.RawModel(sh, blobs, tok, pos, lnf_g, lnf_b, g=g, streamed=True, n_slots=n_slots)
+                else:
+                    mdl = dev.RawModel(sh, dev_blobs, tok, pos, lnf_g, lnf_b, g=g)
+                mdl.label = f"{tech}{n_slots if n_slots else ''}/g={g}" + (f"/batch={batch}" if len(batches) > 1 else "")
+                n_ring = 2
+                ids = torch.randint(0, sh.vocab, (n_ring, g, batch, sh.seq_len), dtype=torch.int32, device="cuda",
+                                    generator=gen)
+                out = dev.empty_storage((1, g, batch, sh.seq_len, sh.d_model), mdl.md)
+                mdl.set_io(ids, n_ring, out, 1)
+                models.append(mdl)
     return shape, models
 
 
@@ -333,7 +347,7 @@ def choose_streamed_config(pf, windows, models, shape, fill_ppm, switch_ns):
     run of back-to-back batches that covers eight bubble cycles (the same job follows itself).  Returns (best index
     or -1, per candidate: batches in the run, cycles the run takes)."""
     cfgs = [dict(F=[(n.dur_ns, n.mem_bytes, n.op, n.layer, n.mb_first, n.mb_count) for n in m_.chain],
-                 samples=m_.cfg.g * shape.batch) for m_ in models]
+                 samples=m_.cfg.g * m_.shape.batch) for m_ in models]
     best, runs, cyc, _ = pf.pf_select_config_stream(windows, cfgs, fill_ppm, switch_ns, 0, 8)
     return best, runs, cyc
 
@@ -362,12 +376,17 @@ def timed_fill_run(ctx, pf, torch, run_step, steps, verbose=False):
 
 
 def candidates_report(models, runs, cyc):
-    return {f"g={m_.cfg.g}": {"batches_in_run": runs[i], "cycles_of_run": cyc[i],
-                              "chain_ms": sum(n.dur_ns for n in m_.chain) * 1e-6} for i, m_ in enumerate(models)}
+    return {m_.label: {"batches_in_run": runs[i], "cycles_of_run": cyc[i],
+                       "chain_ms": sum(n.dur_ns for n in m_.chain) * 1e-6,
+                       "mem_gib": max(n.mem_bytes for n in m_.chain) / GIB} for i, m_ in enumerate(models)}
 
 
 def run_cfg3(args, np, torch, pf, dev, synth):
-    shape, models = make_cfg3_models(torch, pf, dev, synth)
+    if args.candidates == "all":
+        shape, models = make_cfg3_models(torch, pf, dev, synth, gs=(1, 4), slot_counts=(2, 3), resident=True,
+                                         batches=(16, 4, 1))
+    else:
+        shape, models = make_cfg3_models(torch, pf, dev, synth)
     fill, main_s = torch.cuda.Stream(), torch.cuda.Stream()
     bubble_ns, cap = int(args.bubble_ms * 1e6), int(args.cap_gib * GIB)
     windows = [dict(start=bubble_ns // 2, dur=bubble_ns, free=cap, kind=pf.PF_BUBBLE_EXPLICIT, fillable=1)]
@@ -377,6 +396,7 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     if best < 0:
         raise RuntimeError(f"no configuration of the streamed job fits the {args.bubble_ms} ms / {args.cap_gib} GiB bubbles")
     mdl = models[best]
+    shape = mdl.shape                    # the chosen candidate's sequences per microbatch
     plan, n_plan, k = pf.pf_plan_bubbles(windows, mdl.chain, args.fill_ppm, args.switch_ns, 0, raw=True)
     cursor = C.c_int32(0)
     mdl.ctx.pf_ctx_set_replan(True, args.fill_ppm, args.switch_ns)
@@ -401,20 +421,25 @@ def run_cfg3(args, np, torch, pf, dev, synth):
     layer_visits = sum(1 for n in mdl.chain if n.op == pf.PF_OP_LAYER_FWD) * agg["replicas_done"]
     out = base_line(args, tokens / (agg["offered_ns"] * 1e-9), wall, {
         "config": {"workload": "cfg3: 24-layer bf16 causal decoder inference fill job d=2048 h=16 ff=8192 seq=1024 "
-                               "batch=16, weights streamed per layer from pinned host memory (3 HBM slots), "
+                               + ("batch=16, weights streamed per layer from pinned host memory (3 HBM slots), "
+                                  if args.candidates == "streamed" else
+                                  "batch 16, 4 or 1, weights streamed from pinned host memory (2 or 3 HBM slots) or resident "
+                                  "in HBM, 1 or 4 microbatches per layer visit, whichever the planner picks under the cap, ") +
                                f"explicit {args.bubble_ms:g} ms bubbles separated by {args.bubble_ms / 2:g} ms, "
                                f"{args.cap_gib:g} GiB cap",
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
-                   "microbatches_per_layer_visit": g, "candidates": candidates_report(models, runs, cyc)},
+                   "microbatches_per_layer_visit": g, "chosen": mdl.label,
+                   "candidates": candidates_report(models, runs, cyc)},
         **fill_stats(agg, wait_ns), "main_slowdown_pct": None,
         "fill_tflops_in_bubbles": agg["replicas_done"] * g * shape.n_layers * layer_fwd_flops(shape) /
         (agg["offered_ns"] * 1e-9) * 1e-12,
-        "host_to_hbm_gbs_in_bubbles": layer_visits * blob_bytes / (agg["offered_ns"] * 1e-9) * 1e-9,
-        "roofline": ffn1_roofline(kernels, shape, "cfg3_ffn1"), "kernels": kernels})
+        "host_to_hbm_gbs_in_bubbles": (layer_visits * blob_bytes if mdl.cfg.streamed else 0) / (agg["offered_ns"] * 1e-9) * 1e-9,
+        "roofline": ffn1_roofline(kernels, shape, "cfg3_ffn1" if shape.batch == 16 else "cfg3_ffn1_small_batch"),
+        "kernels": kernels})
     for m_ in models:
         m_.close()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline_layer(shape, synth, args.cpu_seqs or 16)
+        out["cpu_baseline"] = cpu_baseline_layer(synth.WORKLOADS["cfg3"], synth, args.cpu_seqs or 16)
     return out
 
 
@@ -691,6 +716,9 @@ def main():
                     help="cfg5: the main stage ends each iteration with a gradient synchronisation and an optimizer "
                          "update, and offloads optimizer state to pinned host memory around them")
     ap.add_argument("--sync-ms", type=float, default=100.0, help="cfg5 --main-offload: gradient synchronisation time")
+    ap.add_argument("--candidates", default="streamed", choices=["streamed", "all"],
+                    help="cfg3: configurations offered to the planner: the workload's own (weights streamed through 3 "
+                         "slots, 1/2/4 microbatches per layer visit) or also 2 slots and weights resident in HBM")
     ap.add_argument("--probe-p", type=int, default=4)
     ap.add_argument("--probe-m", type=int, default=8)
     ap.add_argument("--probe-first-ms", type=float, default=5.0, help="probe: first wait tried at a bubble instruction")

@@ -31,6 +31,8 @@ def run_point(name, knob, value, extra):
         line = json.loads(out.stdout.strip().splitlines()[-1])
         rec.update({k: line.get(k) for k in KEEP})
         rec["microbatches_per_layer_visit"] = line.get("config", {}).get("microbatches_per_layer_visit")
+        rec["chosen"] = line.get("config", {}).get("chosen")
+        rec["copy_wait_pct_of_offered"] = line.get("copy_wait_pct_of_offered")
         if "main_offload" in line:
             rec["main_offload"] = line["main_offload"]
     print(json.dumps(rec), flush=True)
@@ -39,6 +41,7 @@ def run_point(name, knob, value, extra):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--which", default="fill,bubble,memory,offload")
+    ap.add_argument("--caps", default="0.4,0.5,0.75,1,1.5,2,4,8", help="memory sweep: free GiB inside the bubbles")
     args = ap.parse_args()
     which = set(args.which.split(","))
     if "fill" in which:      # real main-stage kernels (cfg5) with the streamed fill job inside its bubbles
@@ -49,9 +52,12 @@ def main():
         for ms in (5, 10, 20, 40, 80, 160):   # at least 20 bubbles and 3.2 s of them: a batch spans several small ones
             run_point("bubble_size", "bubble_ms", ms, ["--workload", "cfg3", "--bubble-ms", str(ms), "--steps",
                                                         str(max(20, 3200 // ms))])
-    if "memory" in which:    # the same job with less and less free memory
-        for gib in (1, 2, 3, 4, 6, 8):
-            run_point("free_memory", "cap_gib", gib, ["--workload", "cfg3", "--cap-gib", str(gib), "--steps", "20"])
+    if "memory" in which:    # the same job with less and less free memory; the planner may keep the weights resident,
+        # or stream them through 3 or 2 slots, with 16, 4 or 1 sequences per microbatch and 1 or 4 microbatches per layer
+        # visit (Sec. 4.3: batch size x technique)
+        for gib in (float(c) for c in args.caps.split(",")):
+            run_point("free_memory", "cap_gib", gib, ["--workload", "cfg3", "--candidates", "all", "--cap-gib", str(gib),
+                                                       "--steps", "50"])
     if "offload" in which:   # cfg5 with 1 GiB free: the fill job only fits the windows that the offload enlarges
         for ms in (10, 25, 50, 100, 200, 400):
             run_point("main_offload", "sync_ms", ms, ["--workload", "cfg5", "--main-offload", "--cap-gib", "1", "--sync-ms",

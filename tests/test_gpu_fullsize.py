@@ -448,3 +448,20 @@ def test_training_head_loss_and_adam_at_the_full_vocabulary():
         assert not np.any(read_emb(m, 0)["tok_emb"])         # accumulators cleared by the step
     finally:
         m.close()
+
+
+def test_one_point_of_the_free_memory_sweep():
+    """One point of the sweep over the memory free inside the bubbles (Sec. 6.4): with 0.75 GiB neither the candidates
+    that keep the 2.6 GB of weights resident nor those with 16 sequences per microbatch fit a bubble, so the planner
+    streams the weights and takes 4 sequences per microbatch."""
+    import json
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-m", "paper_2410_07192_amd.sweeps", "--which", "memory", "--caps", "0.75"],
+                         capture_output=True, text=True, timeout=300, cwd=root)
+    assert out.returncode == 0, out.stderr[-2000:]
+    rec = json.loads(out.stdout.strip().splitlines()[-1])
+    assert rec["sweep"] == "free_memory" and rec["cap_gib"] == 0.75 and "error" not in rec, rec
+    assert rec["chosen"].startswith("streamed") and rec["chosen"].endswith("batch=4"), rec
+    assert rec["value"] > 1e5 and rec["pct_bubble_filled"] > 50.0
