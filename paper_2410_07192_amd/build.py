@@ -9,9 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpipefill.so")
 SOURCES = ["planner.cpp", "scheduler.cpp", "gemm_inst_a.hip", "gemm_inst_b.hip", "gemm_inst_c.hip", "gemm_inst_d.hip", "gemm.hip", "gemm_tn.hip", "elementwise.hip", "attention.hip", "attention_bwd.hip", "train_kernels.hip", "runtime.hip", "runtime_train.hip"]
-# -Wno-inline-asm: the direct-to-LDS copies set M0 in inline assembly and name it as clobbered, which clang reports
-# as a reserved register on every use
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

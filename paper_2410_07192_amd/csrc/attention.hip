@@ -108,7 +108,7 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
       int row = k0 + st_row + NW * (i % HALF) * RPI;
       row = row < S ? row : S - 1;
       const bf16_t* p = base + (uint64_t)(uint32_t)row * rs32 + (is_v ? st_col_v : st_col_k);
-      asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p) : "memory", "m0");
+      lds_direct_load_1k(dst, p);
     }
   };
 

@@ -70,7 +70,7 @@ __device__ __forceinline__ int swz_rt(int r) {
 
 // one wave-wide copy of 1 KB, global -> LDS directly: lane i's 16 bytes land at dst + 16 i (dst wave-uniform)
 __device__ __forceinline__ void copy_1k(uint32_t dst, const bf16_t* p) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p) : "memory", "m0");
+  lds_direct_load_1k(dst, p);
 }
 
 // Byte offsets of a lane's transposing reads inside a tile, for the 32-column block dt and K step 0: lane 16 G + p

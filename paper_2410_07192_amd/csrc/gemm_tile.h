@@ -209,8 +209,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
     const int g = wave + i * NW;
     const uint32_t dst = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)((stage * STAGE + g * 64) * 16));
     const bf16_t* p = src[i] + k0;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p)
-                 : "memory", "m0");
+    lds_direct_load_1k(dst, p);
   };
   int offW[TN], offX[TM], swW[TN], swX[TM];
 #pragma unroll

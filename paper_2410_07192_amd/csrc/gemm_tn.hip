@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tn_acc_kernel(const bf16_t* 
     const uint32_t dst =
         __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(stage * STAGE + (q < 16 ? 0 : BOFF) + (q & 15) * 1024));
     const bf16_t* p = src[i] + kstep * 64 * (q < 16 ? M : N);
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(p) : "memory", "m0");
+    lds_direct_load_1k(dst, p);
   };
 
   // fragment addressing: lane 16 g + i points at k-row (g / 2) * 8 + r * 4 + i / 4 of the 16-row substep and at

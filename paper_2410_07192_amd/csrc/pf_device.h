@@ -184,4 +184,18 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+
+// One wave-wide copy of 1 KB from global memory straight into LDS (global_load_lds_dwordx4): lane i's 16 bytes at p land
+// at LDS byte address dst + 16 i, dst wave-uniform.  The instruction takes the LDS address from M0.  M0 is a register
+// the compiler reserves for itself and does not model as clobberable by inline assembly, so the statement puts back
+// the value it found: M0 is the same before and after, whatever the compiler keeps there.  Asynchronous: counted by
+// vmcnt, not ordered against LDS reads by the compiler (which is why this is not the builtin).
+__device__ __forceinline__ void lds_direct_load_1k(uint32_t dst, const void* p) {
+  uint32_t saved;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved)
+               : "s"(dst), "v"(p)
+               : "memory");
+}
+
 }  // namespace pf
