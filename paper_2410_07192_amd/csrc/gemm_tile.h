@@ -135,6 +135,270 @@ __device__ __forceinline__ void static_for(F&& f) {
 // ------------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
+// The LDS tables of the staged epilogues, behind the two operand stages; every workgroup builds its copy before the
+// K loop, whose barriers publish it.
+// GELU for bf16 results by table: h(x) = gelu(x) - max(x, 0) is bounded and vanishes at both ends; 1024 segments
+// of 1/64 on [-8, 8), value and slope per segment, linear interpolation (error below 2.5e-5, a hundredth of a bf16
+// ulp at 1).  The same for GELU' (between -0.13 and 1.13, 0 and 1 beyond the ends), where the saved
+// pre-activation is bf16.
+template <int NW, typename OutT, int EPI>
+__device__ __forceinline__ void build_epilogue_tables(float2* gelu_tab) {
+  constexpr bool GELU_TAB = std::is_same<OutT, bf16_t>::value && (EPI & E_GELU) && !(EPI & E_ACC) && NW >= 8;
+  if constexpr (GELU_TAB) {
+    for (int e = threadIdx.x; e < 1024; e += 64 * NW) {
+      const float x0 = -8.0f + (float)e * (1.0f / 64.0f), x1 = x0 + 1.0f / 64.0f;
+      const float h0 = gelu_f(x0) - fmaxf(x0, 0.f), h1 = gelu_f(x1) - fmaxf(x1, 0.f);
+      gelu_tab[e] = make_float2(h0, h1 - h0);
+    }
+  }
+  constexpr bool GRAD_TAB = std::is_same<OutT, bf16_t>::value && EPI == E_DACT;
+  if constexpr (GRAD_TAB) {
+    for (int e = threadIdx.x; e < 1024; e += 64 * NW) {
+      const float x0 = -8.0f + (float)e * (1.0f / 64.0f);
+      const float d0 = gelu_grad_f(x0), d1 = gelu_grad_f(x0 + 1.0f / 64.0f);
+      gelu_tab[e] = make_float2(d0, d1 - d0);
+    }
+  }
+}
+
+// What a workgroup does with its finished accumulators: acc[a][b] is the 32x32 block at rows (wm * TM + b) * 32,
+// columns (wn * TN + a) * 32 of the BM x BN tile at (m0, n0).  smem: the two operand stages (free after the K loop)
+// followed by the table of build_epilogue_tables.
+template <int WGM, int WGN, int TM, int TN, typename OutT, int EPI>
+__device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TN][TM], uint4* smem, OutT* __restrict__ C, int64_t M,
+                                              int64_t N, const EpiDev& ep, int64_t m0, int64_t n0) {
+  constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32, NW = WGM * WGN;
+  constexpr int STAGE = (BM + BN) * 8;
+  float2* gelu_tab = (float2*)(smem + 2 * STAGE);
+  auto gelu_grad_tab = [&](float x) {
+    const float u = __builtin_amdgcn_fmed3f(fmaf(x, 64.0f, 512.0f), 0.0f, 1023.996f);
+    const float2 e = gelu_tab[(int)u];
+    return fmaf(e.y, __builtin_amdgcn_fractf(u), e.x);
+  };
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WGM, wn = wave / WGM;
+  const int lr = lane & 31, lk = lane >> 5;
+  // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
+  // Indices into acc must be compile-time constants or the accumulators leave the register file.
+  const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
+  // Split K: the fp32 tile goes through LDS (row-major, 16-byte units XOR-swizzled by row) and is added to C with
+  // hardware fp32 atomics, 64 consecutive columns of a row per wave instruction.  A lane-per-row atomic would touch 32
+  // cache lines per instruction.  Only tiles whose fp32 image fits the two LDS stages split K (the launcher knows).
+  if constexpr (std::is_same<OutT, float>::value && EPI == E_ACC && BM * BN * 4 <= 2 * STAGE * 16) {
+    if (gridDim.y > 1) {
+      float* stf = (float*)smem;
+      constexpr int UNITS = BN / 4, NT = 64 * NW;
+      static_for<0, TN>([&](auto a) {
+        static_for<0, TM>([&](auto b) {
+          const int row = (wm * TM + b) * 32 + lr;
+          static_for<0, 4>([&](auto rg) {
+            const int unit = ((wn * TN + a) * 32 + rg * 8 + lk * 4) / 4;
+            *(float4*)(stf + row * BN + ((unit ^ (row & (UNITS - 1))) * 4)) =
+                make_float4(acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2], acc[a][b][rg * 4 + 3]);
+          });
+        });
+      });
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_s_barrier();
+#pragma unroll 8
+      for (int i = 0; i < BM * BN / NT; ++i) {
+        const int e = i * NT + tid, row = e / BN, col = e % BN;
+        const float v = stf[row * BN + (((col >> 2) ^ (row & (UNITS - 1))) * 4) + (col & 3)];
+        if (m0 + row < M && n0 + col < N) unsafeAtomicAdd((float*)C + (m0 + row) * N + n0 + col, v);
+      }
+      return;
+    }
+  }
+  // Staged epilogue (bf16 output): bias and GELU are applied in registers, the bf16 tile goes through LDS (free
+  // after the K loop; 16-byte slots XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the
+  // tile, the residual being added on the way out from equally coalesced loads.  The two training forms use the same
+  // route: the pre-activation is a second tile staged and stored before the activated one, and the saved tensor whose
+  // GELU' multiplies the result comes in the other way round, coalesced loads -> LDS -> the accumulator layout.
+  constexpr bool STAGED = std::is_same<OutT, bf16_t>::value && !(EPI & E_ACC);
+  if constexpr (STAGED) {
+    static_assert(!(EPI & E_DACT) || EPI == E_DACT, "GELU' multiplies the plain product only");
+    const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid | (uintptr_t)ep.preact_out |
+                                                 (uintptr_t)ep.dact_in) & 15) == 0);
+    if (interior && aligned16) {
+      constexpr int SLOTS = BN / 8, NT = 64 * NW, PER = BM * BN / 8 / NT;
+      // 16-byte slot of a row, moved per row so that the lanes of a wave (32 rows, same column group) spread
+      // over the banks: XOR when the slot count is a power of two, rotation otherwise
+      auto swz = [](int slot, int row) {
+        if constexpr ((SLOTS & (SLOTS - 1)) == 0) return slot ^ (row & (SLOTS - 1));
+        else return (slot + row) % SLOTS;
+      };
+      uint2* st8 = (uint2*)smem;
+      if constexpr (EPI & E_DACT) {
+        // tile of the saved pre-activation: eight 16-byte pieces per thread at a time (more would not fit beside
+        // the accumulators), then every lane picks up the values of its own accumulator elements
+        constexpr int CH = PER < 8 ? PER : 8;
+#pragma unroll
+        for (int i0 = 0; i0 < PER; i0 += CH) {
+          uint4 t[CH];
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            if (i0 + i < PER) {
+              const int q = (i0 + i) * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+              t[i] = *(const uint4*)((const bf16_t*)ep.dact_in + (m0 + row) * N + n0 + slot * 8);
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < CH; ++i) {
+            if (i0 + i < PER) {
+              const int q = (i0 + i) * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+              smem[row * SLOTS + swz(slot, row)] = t[i];
+            }
+          }
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+        static_for<0, TN>([&](auto a) {
+          static_for<0, TM>([&](auto b) {
+            const int row = (wm * TM + b) * 32 + lr;
+            static_for<0, 4>([&](auto rg) {
+              const int slot = (wn * TN + a) * 4 + rg;
+              const uint2 u = st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk];
+              acc[a][b][rg * 4 + 0] *= gelu_grad_tab(bf16_bits_to_f32(u.x & 0xffffu));
+              acc[a][b][rg * 4 + 1] *= gelu_grad_tab(bf16_bits_to_f32(u.x >> 16));
+              acc[a][b][rg * 4 + 2] *= gelu_grad_tab(bf16_bits_to_f32(u.y & 0xffffu));
+              acc[a][b][rg * 4 + 3] *= gelu_grad_tab(bf16_bits_to_f32(u.y >> 16));
+            });
+          });
+        });
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();   // everyone has its values: the tile's place in LDS is free again
+      }
+      // accumulators (+ bias) (-> GELU) -> bf16 -> LDS in the swizzled row-major layout
+      auto stage_tile = [&](auto with_gelu) {
+        static_for<0, TN>([&](auto a) {
+          float bias4[4][4] = {};
+          if constexpr (EPI & E_BIAS) {
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg)
+              load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
+          }
+          static_for<0, TM>([&](auto b) {
+            const int row = (wm * TM + b) * 32 + lr;
+            static_for<0, 4>([&](auto rg) {
+              float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                            acc[a][b][rg * 4 + 3]};
+              if constexpr (EPI & E_BIAS) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] += bias4[rg][j];
+              }
+              if constexpr (decltype(with_gelu)::value) {
+                // Eight waves: GELU from the table (9.5 VALU slots and one LDS gather per element; the second wave of
+                // the SIMD covers the gather's latency).  Four waves, one per SIMD: nothing covers it, and the
+                // arithmetic form (one exp2 and one reciprocal per element) is the faster one.
+                if constexpr (NW >= 8) {
+#pragma unroll
+                  for (int j = 0; j < 4; ++j) {
+                    const float u = __builtin_amdgcn_fmed3f(fmaf(v[j], 64.0f, 512.0f), 0.0f, 1023.996f);
+                    const float2 e = gelu_tab[(int)u];
+                    v[j] = fmaxf(v[j], 0.f) + fmaf(e.y, __builtin_amdgcn_fractf(u), e.x);
+                  }
+                } else {
+#pragma unroll
+                  for (int j = 0; j < 4; ++j) v[j] = gelu_bf16_f(v[j]);
+                }
+              }
+              uint2 pk;
+              pk.x = pack_bf16x2(v[0], v[1]);
+              pk.y = pack_bf16x2(v[2], v[3]);
+              const int slot = (wn * TN + a) * 4 + rg;
+              st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk] = pk;
+            });
+          });
+        });
+      };
+      if constexpr (EPI & E_PRE) {   // the value before the activation leaves first, the same way
+        stage_tile(std::false_type{});
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          *(uint4*)((bf16_t*)ep.preact_out + (m0 + row) * N + n0 + slot * 8) = smem[row * SLOTS + swz(slot, row)];
+        }
+        __builtin_amdgcn_s_waitcnt(0xc07f);
+        __builtin_amdgcn_s_barrier();
+      }
+      // the residual tile is requested first, in the layout of the final stores, so that it arrives while the
+      // accumulators go through bias / GELU / LDS
+      constexpr int EARLY = PER < 8 ? PER : 8;   // more would not fit beside the accumulators
+      uint4 rres[(EPI & E_RESID) ? PER : 1];
+      if constexpr (EPI & E_RESID) {
+#pragma unroll
+        for (int i = 0; i < EARLY; ++i) {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
+        }
+      }
+      stage_tile(std::integral_constant<bool, (EPI & E_GELU) != 0>{});
+      if constexpr (EPI & E_RESID) {   // the accumulators are dead now: the rest of the residual tile
+#pragma unroll
+        for (int i = EARLY; i < PER; ++i) {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
+        }
+      }
+      __builtin_amdgcn_s_waitcnt(0xc07f);
+      __builtin_amdgcn_s_barrier();
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+        uint4 v = smem[row * SLOTS + swz(slot, row)];
+        const int64_t off = (m0 + row) * N + n0 + slot * 8;
+        if constexpr (EPI & E_RESID) {
+          const uint4 r = rres[i];
+          const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, rw[4] = {r.x, r.y, r.z, r.w};
+          uint32_t ow[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float lo = bf16_bits_to_f32(vw[j] & 0xffffu) + bf16_bits_to_f32(rw[j] & 0xffffu);
+            const float hi = bf16_bits_to_f32(vw[j] >> 16) + bf16_bits_to_f32(rw[j] >> 16);
+            ow[j] = pack_bf16x2(lo, hi);
+          }
+          v = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+        }
+        *(uint4*)((bf16_t*)C + off) = v;
+      }
+      return;
+    }
+  }
+  if (interior) {
+    static_for<0, TN>([&](auto a) {
+      float bias4[4][4] = {};
+      if constexpr (EPI & E_BIAS) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg)
+          load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
+      }
+      static_for<0, TM>([&](auto b) {
+        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
+        static_for<0, 4>([&](auto rg) {
+          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
+          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                        acc[a][b][rg * 4 + 3]};
+          epilogue4_static<EPI, OutT>(v, bias4[rg], m * N + n, C, ep);
+        });
+      });
+    });
+  } else {
+    static_for<0, TN>([&](auto a) {
+      static_for<0, TM>([&](auto b) {
+        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
+        static_for<0, 4>([&](auto rg) {
+          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
+          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
+                        acc[a][b][rg * 4 + 3]};
+          epilogue4_scalar<bf16_t, OutT>(v, m, n, M, N, C, ep);
+        });
+      });
+    });
+  }
+}
+
 template <int WGM, int WGN, int TM, int TN, typename OutT, int EPI>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
     const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, OutT* __restrict__ C, int64_t M, int64_t N,
@@ -144,33 +408,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
   constexpr int STAGE = (BM + BN) * 8;                          // uint4 per LDS stage
   static_assert(G % NW == 0 && GPW <= 32, "tile / wave mismatch");
   extern __shared__ uint4 smem[];
-  // GELU for bf16 results by table: h(x) = gelu(x) - max(x, 0) is bounded and vanishes at both ends; 1024 segments
-  // of 1/64 on [-8, 8), value and slope per segment, linear interpolation (error below 2.5e-5, a hundredth of a bf16
-  // ulp at 1).  Every workgroup builds its copy behind the two stages; the K loop's barriers publish it.
-  constexpr bool GELU_TAB = std::is_same<OutT, bf16_t>::value && (EPI & E_GELU) && !(EPI & E_ACC);
-  float2* gelu_tab = (float2*)(smem + 2 * STAGE);
-  if constexpr (GELU_TAB) {
-    for (int e = threadIdx.x; e < 1024; e += 64 * NW) {
-      const float x0 = -8.0f + (float)e * (1.0f / 64.0f), x1 = x0 + 1.0f / 64.0f;
-      const float h0 = gelu_f(x0) - fmaxf(x0, 0.f), h1 = gelu_f(x1) - fmaxf(x1, 0.f);
-      gelu_tab[e] = make_float2(h0, h1 - h0);
-    }
-  }
-  // the same for GELU' (between -0.13 and 1.13, 0 and 1 beyond the ends), where the saved pre-activation is bf16
-  constexpr bool GRAD_TAB = std::is_same<OutT, bf16_t>::value && EPI == E_DACT;
-  if constexpr (GRAD_TAB) {
-    for (int e = threadIdx.x; e < 1024; e += 64 * NW) {
-      const float x0 = -8.0f + (float)e * (1.0f / 64.0f);
-      const float d0 = gelu_grad_f(x0), d1 = gelu_grad_f(x0 + 1.0f / 64.0f);
-      gelu_tab[e] = make_float2(d0, d1 - d0);
-    }
-  }
-  auto gelu_grad_tab = [&](float x) {
-    const float u = __builtin_amdgcn_fmed3f(fmaf(x, 64.0f, 512.0f), 0.0f, 1023.996f);
-    const float2 e = gelu_tab[(int)u];
-    return fmaf(e.y, __builtin_amdgcn_fractf(u), e.x);
-  };
-
+  build_epilogue_tables<NW, OutT, EPI>((float2*)(smem + 2 * STAGE));
   const int64_t tile = xcd_contiguous(blockIdx.x, (int64_t)tiles_m * tiles_n);
   const int64_t per_group = (int64_t)group_m * tiles_n;
   const int64_t grp = tile / per_group;
@@ -298,217 +536,166 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_nt_kernel(
     __builtin_amdgcn_sched_barrier(0);
   }
 
-  // D[i][j]: lane holds j = lane%32 (row of C) and i = 8*(r/4) + 4*(lane/32) + r%4 (column of C).
-  // Indices into acc must be compile-time constants or the accumulators leave the register file.
-  const bool interior = (m0 + BM <= M) && (n0 + BN <= N) && ((N & 3) == 0);
-  // Split K: the fp32 tile goes through LDS (row-major, 16-byte units XOR-swizzled by row) and is added to C with
-  // hardware fp32 atomics, 64 consecutive columns of a row per wave instruction.  A lane-per-row atomic would touch 32
-  // cache lines per instruction.  Only tiles whose fp32 image fits the two LDS stages split K (the launcher knows).
-  if constexpr (std::is_same<OutT, float>::value && EPI == E_ACC && BM * BN * 4 <= 2 * STAGE * 16) {
-    if (gridDim.y > 1) {
-      float* stf = (float*)smem;
-      constexpr int UNITS = BN / 4, NT = 64 * NW;
-      static_for<0, TN>([&](auto a) {
-        static_for<0, TM>([&](auto b) {
-          const int row = (wm * TM + b) * 32 + lr;
-          static_for<0, 4>([&](auto rg) {
-            const int unit = ((wn * TN + a) * 32 + rg * 8 + lk * 4) / 4;
-            *(float4*)(stf + row * BN + ((unit ^ (row & (UNITS - 1))) * 4)) =
-                make_float4(acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2], acc[a][b][rg * 4 + 3]);
-          });
-        });
-      });
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_s_barrier();
-#pragma unroll 8
-      for (int i = 0; i < BM * BN / NT; ++i) {
-        const int e = i * NT + tid, row = e / BN, col = e % BN;
-        const float v = stf[row * BN + (((col >> 2) ^ (row & (UNITS - 1))) * 4) + (col & 3)];
-        if (m0 + row < M && n0 + col < N) unsafeAtomicAdd((float*)C + (m0 + row) * N + n0 + col, v);
-      }
-      return;
-    }
+  tile_epilogue<WGM, WGN, TM, TN, OutT, EPI>(acc, smem, C, M, N, ep, m0, n0);
+}
+
+// The 256x256 tile on FOUR waves (one per SIMD, wave tile 128x128, accumulators in 256 registers): per K step the
+// fragment reads take 128 KB out of LDS instead of the 192 KB the eight-wave form reads, and operands travel
+// global -> registers -> LDS with every load in flight for a whole K step.  A wave moves sixteen 1 KB groups per step;
+// slot i of a step writes the group that was loaded into register quad i one step earlier to the LDS stage that was
+// freed by the previous barrier, and then reuses the quad for the load of the stage after next: sixty-four registers
+// hold one stage in flight, the memory pipeline never drains, and the one barrier of a step (in the middle of the
+// last MFMA block, so that queued MFMAs cover it) both publishes the next stage and frees the current one.
+// Plain loads and stores: the compiler derives the vmcnt / lgkmcnt waits; the scheduling fences keep its order.
+template <typename OutT, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_nt_w4_kernel(
+    const bf16_t* __restrict__ X, const bf16_t* __restrict__ W, OutT* __restrict__ C, int64_t M, int64_t N,
+    int64_t K, EpiDev ep, int32_t tiles_m, int32_t tiles_n, int32_t group_m) {
+  constexpr int WGM = 2, WGN = 2, TM = 4, TN = 4;
+  constexpr int BM = 256, BN = 256, NW = 4;
+  constexpr int GX = BM / 8, G = (BM + BN) / 8, GPW = G / NW;   // 8-row groups of 1 KB; sixteen per wave
+  constexpr int STAGE = (BM + BN) * 8;                          // uint4 per LDS stage
+  extern __shared__ uint4 smem[];
+  build_epilogue_tables<NW, OutT, EPI>((float2*)(smem + 2 * STAGE));
+
+  const int64_t tile = xcd_contiguous(blockIdx.x, (int64_t)tiles_m * tiles_n);
+  const int64_t per_group = (int64_t)group_m * tiles_n;
+  const int64_t grp = tile / per_group;
+  const int32_t first_m = (int32_t)(grp * group_m);
+  const int32_t rows_in_group = (tiles_m - first_m < group_m) ? tiles_m - first_m : group_m;
+  const int32_t tm_i = first_m + (int32_t)((tile % per_group) % rows_in_group);
+  const int32_t tn_i = (int32_t)((tile % per_group) / rows_in_group);
+  const int64_t m0 = (int64_t)tm_i * BM, n0 = (int64_t)tn_i * BN;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WGM, wn = wave / WGM;
+  const int lr = lane & 31, lk = lane >> 5;
+
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a first-class vector: a struct-typed quad would live in private memory
+  // Global source of this lane for each group: a 32-bit byte offset from the tile's first row (rows past the end are
+  // clamped: their products are never stored), added by the load instruction itself to a wave-uniform base that
+  // advances by one K step; no vector arithmetic per load.  Groups 0..7 of a wave are rows of X, 8..15 rows of W.
+  static_assert(GX == 8 * NW, "a wave's first eight groups are X rows");
+  uint32_t off[GPW];
+#pragma unroll
+  for (int i = 0; i < GPW; ++i) {
+    const int g = wave + i * NW;
+    const bool isx = i < GPW / 2;
+    const int r = (isx ? g : g - GX) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((r >> 1) & 7);
+    const int64_t last = (isx ? M - m0 : N - n0) - 1;   // last valid row of the tile
+    const int64_t row = r <= last ? r : last;
+    off[i] = (uint32_t)((row * K + c * 8) * 2);
   }
-  // Staged epilogue (bf16 output): bias and GELU are applied in registers, the bf16 tile goes through LDS (free
-  // after the K loop; 16-byte slots XOR-swizzled by row) and leaves as 16-byte stores that cover whole rows of the
-  // tile, the residual being added on the way out from equally coalesced loads.  The two training forms use the same
-  // route: the pre-activation is a second tile staged and stored before the activated one, and the saved tensor whose
-  // GELU' multiplies the result comes in the other way round, coalesced loads -> LDS -> the accumulator layout.
-  constexpr bool STAGED = std::is_same<OutT, bf16_t>::value && !(EPI & E_ACC);
-  if constexpr (STAGED) {
-    static_assert(!(EPI & E_DACT) || EPI == E_DACT, "GELU' multiplies the plain product only");
-    const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid | (uintptr_t)ep.preact_out |
-                                                 (uintptr_t)ep.dact_in) & 15) == 0);
-    if (interior && aligned16) {
-      constexpr int SLOTS = BN / 8, NT = 64 * NW, PER = BM * BN / 8 / NT;
-      // 16-byte slot of a row, moved per row so that the lanes of a wave (32 rows, same column group) spread
-      // over the banks: XOR when the slot count is a power of two, rotation otherwise
-      auto swz = [](int slot, int row) {
-        if constexpr ((SLOTS & (SLOTS - 1)) == 0) return slot ^ (row & (SLOTS - 1));
-        else return (slot + row) % SLOTS;
-      };
-      uint2* st8 = (uint2*)smem;
-      if constexpr (EPI & E_DACT) {
-        // tile of the saved pre-activation: eight 16-byte pieces per thread at a time (more would not fit beside
-        // the accumulators), then every lane picks up the values of its own accumulator elements
-        constexpr int CH = PER < 8 ? PER : 8;
+  const char* const xbase = (const char*)(X + m0 * K);
+  const char* const wbase = (const char*)(W + n0 * K);
+  auto gload = [&](auto ic, int64_t k0) {
+    constexpr int i = decltype(ic)::value;
+    return *(const u32x4*)((i < GPW / 2 ? xbase : wbase) + k0 * 2 + (uint64_t)off[i]);
+  };
+  const int wro = wave * 64 + lane;   // group g of a stage starts at uint4 index g * 64: this lane's place in group `wave`
+  int offW[TN], offX[TM], swW[TN], swX[TM];
 #pragma unroll
-        for (int i0 = 0; i0 < PER; i0 += CH) {
-          uint4 t[CH];
-#pragma unroll
-          for (int i = 0; i < CH; ++i) {
-            if (i0 + i < PER) {
-              const int q = (i0 + i) * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-              t[i] = *(const uint4*)((const bf16_t*)ep.dact_in + (m0 + row) * N + n0 + slot * 8);
-            }
-          }
-#pragma unroll
-          for (int i = 0; i < CH; ++i) {
-            if (i0 + i < PER) {
-              const int q = (i0 + i) * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-              smem[row * SLOTS + swz(slot, row)] = t[i];
-            }
-          }
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();
-        static_for<0, TN>([&](auto a) {
-          static_for<0, TM>([&](auto b) {
-            const int row = (wm * TM + b) * 32 + lr;
-            static_for<0, 4>([&](auto rg) {
-              const int slot = (wn * TN + a) * 4 + rg;
-              const uint2 u = st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk];
-              acc[a][b][rg * 4 + 0] *= gelu_grad_tab(bf16_bits_to_f32(u.x & 0xffffu));
-              acc[a][b][rg * 4 + 1] *= gelu_grad_tab(bf16_bits_to_f32(u.x >> 16));
-              acc[a][b][rg * 4 + 2] *= gelu_grad_tab(bf16_bits_to_f32(u.y & 0xffffu));
-              acc[a][b][rg * 4 + 3] *= gelu_grad_tab(bf16_bits_to_f32(u.y >> 16));
-            });
-          });
-        });
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();   // everyone has its values: the tile's place in LDS is free again
-      }
-      // accumulators (+ bias) (-> GELU) -> bf16 -> LDS in the swizzled row-major layout
-      auto stage_tile = [&](auto with_gelu) {
-        static_for<0, TN>([&](auto a) {
-          float bias4[4][4] = {};
-          if constexpr (EPI & E_BIAS) {
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg)
-              load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
-          }
-          static_for<0, TM>([&](auto b) {
-            const int row = (wm * TM + b) * 32 + lr;
-            static_for<0, 4>([&](auto rg) {
-              float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                            acc[a][b][rg * 4 + 3]};
-              if constexpr (EPI & E_BIAS) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) v[j] += bias4[rg][j];
-              }
-              if constexpr (decltype(with_gelu)::value) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                  const float u = __builtin_amdgcn_fmed3f(fmaf(v[j], 64.0f, 512.0f), 0.0f, 1023.996f);
-                  const float2 e = gelu_tab[(int)u];
-                  v[j] = fmaxf(v[j], 0.f) + fmaf(e.y, __builtin_amdgcn_fractf(u), e.x);
-                }
-              }
-              uint2 pk;
-              pk.x = pack_bf16x2(v[0], v[1]);
-              pk.y = pack_bf16x2(v[2], v[3]);
-              const int slot = (wn * TN + a) * 4 + rg;
-              st8[row * (SLOTS * 2) + swz(slot, row) * 2 + lk] = pk;
-            });
-          });
-        });
-      };
-      if constexpr (EPI & E_PRE) {   // the value before the activation leaves first, the same way
-        stage_tile(std::false_type{});
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-          *(uint4*)((bf16_t*)ep.preact_out + (m0 + row) * N + n0 + slot * 8) = smem[row * SLOTS + swz(slot, row)];
-        }
-        __builtin_amdgcn_s_waitcnt(0xc07f);
-        __builtin_amdgcn_s_barrier();
-      }
-      // the residual tile is requested first, in the layout of the final stores, so that it arrives while the
-      // accumulators go through bias / GELU / LDS
-      constexpr int EARLY = PER < 8 ? PER : 8;   // more would not fit beside the accumulators
-      uint4 rres[(EPI & E_RESID) ? PER : 1];
-      if constexpr (EPI & E_RESID) {
-#pragma unroll
-        for (int i = 0; i < EARLY; ++i) {
-          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
-        }
-      }
-      stage_tile(std::integral_constant<bool, (EPI & E_GELU) != 0>{});
-      if constexpr (EPI & E_RESID) {   // the accumulators are dead now: the rest of the residual tile
-#pragma unroll
-        for (int i = EARLY; i < PER; ++i) {
-          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
-        }
-      }
-      __builtin_amdgcn_s_waitcnt(0xc07f);
-      __builtin_amdgcn_s_barrier();
-#pragma unroll
-      for (int i = 0; i < PER; ++i) {
-        const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-        uint4 v = smem[row * SLOTS + swz(slot, row)];
-        const int64_t off = (m0 + row) * N + n0 + slot * 8;
-        if constexpr (EPI & E_RESID) {
-          const uint4 r = rres[i];
-          const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, rw[4] = {r.x, r.y, r.z, r.w};
-          uint32_t ow[4];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const float lo = bf16_bits_to_f32(vw[j] & 0xffffu) + bf16_bits_to_f32(rw[j] & 0xffffu);
-            const float hi = bf16_bits_to_f32(vw[j] >> 16) + bf16_bits_to_f32(rw[j] >> 16);
-            ow[j] = pack_bf16x2(lo, hi);
-          }
-          v = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-        }
-        *(uint4*)((bf16_t*)C + off) = v;
-      }
-      return;
-    }
+  for (int a = 0; a < TN; ++a) {
+    const int r = (wn * TN + a) * 32 + lr;
+    offW[a] = BM * 8 + r * 8;
+    swW[a] = (r >> 1) & 7;
   }
-  if (interior) {
-    static_for<0, TN>([&](auto a) {
-      float bias4[4][4] = {};
-      if constexpr (EPI & E_BIAS) {
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg)
-          load4((const bf16_t*)ep.bias + n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4, bias4[rg]);
+  for (int b = 0; b < TM; ++b) {
+    const int r = (wm * TM + b) * 32 + lr;
+    offX[b] = r * 8;
+    swX[b] = (r >> 1) & 7;
+  }
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int a = 0; a < TN; ++a)
+#pragma unroll
+    for (int b = 0; b < TM; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  bf16x8 fw[2][TN], fx[2][TM];
+  // fragment j of a 16-wide slice, in the order the MFMAs first need them: W block 0, the four X blocks, W blocks 1..3
+  auto load_frag = [&](auto bufc, auto jc, const uint4* st, int kk) {
+    constexpr int buf = decltype(bufc)::value, j = decltype(jc)::value;
+    const int c = kk * 2 + lk;
+    if constexpr (j == 0) fw[buf][0] = as_bf16x8(st[offW[0] + (c ^ swW[0])]);
+    else if constexpr (j <= 4) fx[buf][j - 1] = as_bf16x8(st[offX[j - 1] + (c ^ swX[j - 1])]);
+    else fw[buf][j - 4] = as_bf16x8(st[offW[j - 4] + (c ^ swW[j - 4])]);
+  };
+  u32x4 R[GPW];
+  constexpr int MF = TM * TN;   // 16 MFMAs per 16-wide slice of the K step
+  // One 16-wide slice KK of a K step: sixteen MFMAs on fragment buffer KK & 1, each preceded by exactly ONE memory
+  // instruction, so that none of them has to wait for an issue slot behind another (a wave issues in order, and with
+  // one wave per SIMD whatever stalls it stalls the MFMA pipe).  Slices 0..2: eight fragment reads for the next slice,
+  // then four times {write register quad q to the next stage, reload it for the stage after next}.  Slice 3: the last
+  // four writes and reloads first, the barrier behind the eighth MFMA, then the first fragments of the next stage.
+  // WR: stage kt + 1 exists (its groups wait in R); LD: stage kt + 2 exists.
+  auto slice = [&](auto kkc, auto wrc, auto ldc, const uint4* sc, uint4* sn, int64_t k_next2) {
+    constexpr int KK = decltype(kkc)::value, buf = KK & 1, nbuf = buf ^ 1;
+    constexpr bool WR = decltype(wrc)::value, LD = decltype(ldc)::value;
+    static_for<0, MF>([&](auto mi) {
+      if constexpr (KK < 3) {
+        if constexpr (mi < 8) {
+          load_frag(std::integral_constant<int, nbuf>{}, mi, sc, KK + 1);
+        } else {
+          constexpr int q = 4 * KK + (mi - 8) / 2;
+          if constexpr ((mi & 1) == 0) {
+            if constexpr (WR) *(u32x4*)(sn + wro + q * NW * 64) = R[q];
+          } else {
+            if constexpr (LD) R[q] = gload(std::integral_constant<int, q>{}, k_next2);
+          }
+        }
+      } else {
+        if constexpr (mi < 4) {
+          if constexpr (WR) *(u32x4*)(sn + wro + (12 + mi) * NW * 64) = R[12 + mi];
+        } else if constexpr (mi < 8) {
+          if constexpr (LD) R[8 + mi] = gload(std::integral_constant<int, 8 + mi>{}, k_next2);
+        } else {
+          if constexpr (mi == 8) {
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): my LDS writes are done, my last fragments are in registers
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if constexpr (WR) load_frag(std::integral_constant<int, nbuf>{}, std::integral_constant<int, mi - 8>{}, sn, 0);
+        }
       }
-      static_for<0, TM>([&](auto b) {
-        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
-        static_for<0, 4>([&](auto rg) {
-          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
-          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                        acc[a][b][rg * 4 + 3]};
-          epilogue4_static<EPI, OutT>(v, bias4[rg], m * N + n, C, ep);
-        });
-      });
+      __builtin_amdgcn_sched_barrier(0);
+      constexpr int a = mi / TM, b = mi % TM;
+      acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fw[buf][a], fx[buf][b], acc[a][b], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     });
-  } else {
-    static_for<0, TN>([&](auto a) {
-      static_for<0, TM>([&](auto b) {
-        const int64_t m = m0 + (wm * TM + b) * 32 + lr;
-        static_for<0, 4>([&](auto rg) {
-          const int64_t n = n0 + (wn * TN + a) * 32 + rg * 8 + lk * 4;
-          float v[4] = {acc[a][b][rg * 4 + 0], acc[a][b][rg * 4 + 1], acc[a][b][rg * 4 + 2],
-                        acc[a][b][rg * 4 + 3]};
-          epilogue4_scalar<bf16_t, OutT>(v, m, n, M, N, C, ep);
-        });
-      });
-    });
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
+  auto step = [&](auto wrc, auto ldc, int cur, int64_t k_next2) {
+    const uint4* sc = smem + cur * STAGE;
+    uint4* sn = smem + (cur ^ 1) * STAGE;
+    slice(I0{}, wrc, ldc, sc, sn, k_next2);
+    slice(I1{}, wrc, ldc, sc, sn, k_next2);
+    slice(I2{}, wrc, ldc, sc, sn, k_next2);
+    slice(I3{}, wrc, ldc, sc, sn, k_next2);
+  };
+
+  const int64_t nk = K / 64;
+  // prologue: stage 0 through the registers into LDS, stage 1 into the registers
+  static_for<0, GPW>([&](auto i) { R[i] = gload(i, 0); });
+  static_for<0, GPW>([&](auto i) { *(u32x4*)(smem + wro + i * NW * 64) = R[i]; });
+  if (nk > 1) static_for<0, GPW>([&](auto i) { R[i] = gload(i, 64); });
+  __builtin_amdgcn_s_waitcnt(0xc07f);
+  __builtin_amdgcn_s_barrier();
+  static_for<0, 8>([&](auto j) { load_frag(I0{}, j, smem, 0); });
+  int64_t kt = 0;
+  for (; kt + 2 < nk; ++kt) step(std::true_type{}, std::true_type{}, (int)(kt & 1), (kt + 2) * 64);
+  if (kt + 1 < nk) {
+    step(std::true_type{}, std::false_type{}, (int)(kt & 1), 0);
+    ++kt;
   }
+  step(std::false_type{}, std::false_type{}, (int)(kt & 1), 0);
+
+  tile_epilogue<WGM, WGN, TM, TN, OutT, EPI>(acc, smem, C, M, N, ep, m0, n0);
 }
 
 template <typename OutT, typename Kern>
@@ -528,8 +715,8 @@ hipError_t launch_tiles(Kern kern, int BM, int BN, int threads, bool* attr_set, 
   return hipGetLastError();
 }
 
-// Main kernel for one epilogue combination.  Tile shapes: 256x256 (8 waves as 2x4, wave tile 128x64), 256x192
-// (8 waves as 4x2, wave tile 64x96), both one workgroup per CU, and 128x128 (4 waves, two workgroups per CU).
+// Main kernel for one epilogue combination.  Tile shapes: 256x256 (the four-wave kernel above, wave tile 128x128),
+// 256x192 (8 waves as 4x2, wave tile 64x96), both one workgroup per CU, and 128x128 (4 waves, two workgroups per CU).
 // A launch takes ceil(workgroups / resident workgroups) rounds of (K steps + a fixed cost of about 4 steps); the
 // shape with the least estimated time rounds x steps x area in flight per CU / efficiency is taken.  Efficiencies
 // are measured on MI355X relative to the 256x256 tile (0.96 and 0.85); a shape that leaves partial tiles along N
@@ -576,8 +763,7 @@ hipError_t launch_fast(const void* X, const void* W, void* C, int64_t M, int64_t
     }
   }
   if (best == 0)
-    return launch_tiles<OutT>(gemm_bf16_nt_kernel<2, 4, 4, 2, OutT, EPI>, 256, 256, 512, &attr_big, X, W, C, M, N, K, ep,
-                              1, stream);
+    return launch_tiles<OutT>(gemm_bf16_nt_w4_kernel<OutT, EPI>, 256, 256, 256, &attr_big, X, W, C, M, N, K, ep, 1, stream);
   if (best == 1)
     return launch_tiles<OutT>(gemm_bf16_nt_kernel<4, 2, 2, 3, OutT, EPI>, 256, 192, 512, &attr_wide, X, W, C, M, N, K, ep,
                               1, stream);
