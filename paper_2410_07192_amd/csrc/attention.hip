@@ -51,7 +51,9 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
   // repeated reads of that head's K and V.
   const int unit = (int)xcd_contiguous(blockIdx.x, n_wg);
   const int b = unit / (nq * h), hd = (unit / nq) % h;
-  const int q_blk = (unit % nq) * QB;
+  // causal: a query block's work grows with its position, so the blocks of a head are handed out last one first;
+  // the workgroups that start last are then the short ones
+  const int q_blk = (causal ? nq - 1 - unit % nq : unit % nq) * QB;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;                       // row stride of qkv
   const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;

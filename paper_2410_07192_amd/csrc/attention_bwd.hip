@@ -285,7 +285,7 @@ __global__ __launch_bounds__(256, DH == 64 ? 3 : 2) void attn_bwd_dq_bf16_kernel
   // the query blocks of one (batch, head) run on one XCD: they all re-read that head's K and V
   const int unit = (int)xcd_contiguous(blockIdx.x, n_wg);
   const int b = unit / (nblk * h), hd = (unit / nblk) % h;
-  const int q_blk = (unit % nblk) * 128;
+  const int q_blk = (causal ? nblk - 1 - unit % nblk : unit % nblk) * 128;   // causal: the long (late) blocks start first
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;
   const uint32_t rs32 = (uint32_t)rs;

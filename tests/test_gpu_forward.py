@@ -77,7 +77,10 @@ def test_gemm_plain_and_epilogues(dtype, M, N, K):
 
 # Shapes that make the tile chooser take the 256x192 and the 256x256 tile with ragged last tiles along M and N
 # (8292 = 32 * 256 + 100), with N a multiple of 8 (16-byte row-contiguous stores) and not (8- and 2-byte stores).
-@pytest.mark.parametrize("M,N,K", [(8292, 2368, 128), (8292, 3112, 128), (8292, 2370, 64), (4196, 6150, 64)])
+# K = 64, 128, 192 and 320 are one to five K steps: the 256x256 kernel's prologue alone, its two tail steps, and its
+# steady-state loop (a stage read, the next written, the one after loaded) run once and three times.
+@pytest.mark.parametrize("M,N,K", [(8292, 2368, 128), (8292, 3112, 128), (8292, 2370, 64), (4196, 6150, 64),
+                                   (8292, 3112, 192), (4196, 6152, 320)])
 def test_gemm_large_tiles_with_ragged_edges(M, N, K):
     pf, dev = _mods()
     md = _md("bf16")
