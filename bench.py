@@ -618,6 +618,7 @@ def run_cfg5(args, np, torch, pf, dev, synth):
                                    f"Adam update, and offloads {sum(offload['slices']) / GIB:.2f} of its "
                                    f"{offload['state'] / GIB:.2f} GiB of optimizer state" if offload else ""),
                    "fill_ppm": args.fill_ppm, "switch_ns": args.switch_ns,
+                   "chosen": fm.label, "microbatches_per_layer_visit": g,
                    "candidates": candidates_report(models, runs, cyc),
                    "iterations_without_fill": len(base)},
         **fill_stats(agg, wait_ns),
@@ -700,7 +701,9 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5", "probe"])
-    ap.add_argument("--fill-ppm", type=int, default=900_000, help="fraction of each bubble the plan may use")
+    ap.add_argument("--fill-ppm", type=int, default=None,
+                    help="fraction of each bubble the plan may use (default 0.95 for cfg5, whose chunks never overran their window\n"
+                         "up to 0.98 in the sweep, 0.90 for the others)")
     ap.add_argument("--switch-ns", type=int, default=100_000, help="fixed per-bubble cost subtracted before packing")
     ap.add_argument("--paper-mode", action="store_true", help="fill only the contiguous bubbles (cfg2)")
     ap.add_argument("--schedule", default="1f1b", choices=["1f1b", "gpipe"],
@@ -732,6 +735,8 @@ def main():
               "(one independent Executor per device). Use --gpus 1.", file=sys.stderr)
         sys.exit(2)
     defaults = {"cfg2": (16, 2), "cfg3": (50, 3), "cfg4": (16, 1), "cfg5": (6, 1), "probe": (1, 0)}
+    if args.fill_ppm is None:
+        args.fill_ppm = 950_000 if args.workload == "cfg5" else 900_000
     if args.steps is None:
         args.steps = defaults[args.workload][0]
     if args.warmup is None:
