@@ -196,7 +196,7 @@ def ffn1_roofline(kernels, shape, key):
     dom = kernels["gemm_ffn1"]
     return {"bound": "mfma", "achieved": dom["achieved"], "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": dom["frac"], "traffic": measured_traffic(key),
-            "kernel": "gemm_bf16_nt_kernel<bf16_t,bias+GELU> (FFN1: M=%d N=%d K=%d)" %
+            "kernel": "gemm_bf16_nt_w4_kernel<bf16_t,bias+GELU> (FFN1: M=%d N=%d K=%d)" %
                       (shape.tokens, shape.d_ff, shape.d_model),
             "launches": dom["launches"], "avg_us": dom["avg_us"]}
 
