@@ -4,8 +4,8 @@
 // 128 queries of one (batch, head); each wave owns 32 of them and walks the keys in tiles of 64 staged in LDS.  The
 // kernel computes S^T = K Q^T with the 32x32x16 bf16 MFMA (K tile rows are the "A" operand, the
 // wave's Q rows the "B" operand, kept in registers), so that a lane holds 32 of the 64 scores of ONE
-// query: running max / sum need a single cross-lane exchange (lane ^ 32) and the rescale factor
-// is a per-lane scalar.  The probabilities, already in the "B" operand layout, then feed
+// query: the running sum is kept per lane, the rescale factor is a per-lane scalar, and the two lanes of a
+// query (lane ^ 32) exchange values only when the reference point of the softmax moves and after the last tile.  The probabilities, already in the "B" operand layout, then feed
 // O^T = V^T P^T.  K and V tiles go global -> LDS directly, row-major as they lie in memory; the V^T "A" operand
 // comes out of the row-major V tile through the transposing LDS load (ds_read_b64_tr_b16), two per fragment.
 //
@@ -128,15 +128,29 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
     }
   }
 
+  // x[lane ^ 32] without the LDS: the swap leaves (low half of x, low half of x) in one register and (high half,
+  // high half) in the other; callers combine the two with a commutative operation.  (The results go through an
+  // empty asm statement: the compiler otherwise folds fmaxf of the two into the first.)
+  auto halves = [](float x, float& lo, float& hi) {
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    unsigned a = r[0], b = r[1];
+    asm volatile("" : "+v"(a), "+v"(b));
+    lo = __builtin_bit_cast(float, a);
+    hi = __builtin_bit_cast(float, b);
+  };
+
   // m_ref is the reference point of the running sum and of O (scaled scores, log2 units).  It follows the running
-  // maximum lazily: it moves only when some query of the wave exceeds it by more than 8, so p stays below 2^8 and
-  // most tiles skip the rescaling of O altogether; the result is the same up to rounding.
+  // maximum lazily: it moves only when a lane's share of a tile's row sum against it exceeds 2^7, so most tiles
+  // compute no maximum and skip the rescaling of O; the result is the same up to rounding.  l_run is this lane's
+  // share of the row sum (32 of every 64 keys).
   float m_ref = -INFINITY, l_run = 0.f;
-  // the Q fragments are waited for here, once: left pending, the compiler would wait for them in every iteration
-  // with a count that also holds back the copies issued just before
+  // The first tile's copies go out while the Q fragments are still on their way (one memory latency, not two);
+  // the fragments are then waited for here, once: left pending, the compiler would wait for them in every
+  // iteration with a count that also holds back the copies issued just before.
+  stage(0, 0);
 #pragma unroll
   for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fq[kk]));
-  stage(0, 0);
   for (int kt = 0; kt < n_tiles; ++kt) {
     const int k0 = kt * 64;
     // tile kt has landed (every wave waits for its own copies, then the barrier), and everyone has left tile
@@ -149,37 +163,61 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
     const char* sKb = smem + (kt & 1) * 2 * TILE;
     lds_char_ptr sVb = (lds_char_ptr)(lds_void_ptr)smem + (kt & 1) * 2 * TILE;
 
-    // S^T tile: 64 keys x 32 queries per wave
+    // S^T tile: 64 keys x 32 queries per wave; masked only in the tiles that touch the diagonal or the end of the
+    // sequence
     f32x16 accS[2];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) accS[ks][r] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
-        const int r = ks * 32 + lr, c = kk * 2 + g;
-        const uint4 fk = *(const uint4*)(sKb + r * ROWB + ((c ^ swz_k(r)) << 4));
-        accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fk), fq[kk], accS[ks], 0, 0, 0);
-      }
-    // mask (only the tiles that touch the diagonal or the end of the sequence), maximum of the raw scores
-    const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
-    if (need_mask) {
+    auto scores = [&] {
 #pragma unroll
       for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (key >= S || (causal && key > q_row)) accS[ks][r] = -INFINITY;
-        }
-    }
-    float mx = fmaxf(accS[0][0], accS[1][0]);
+        for (int r = 0; r < 16; ++r) accS[ks][r] = 0.f;
 #pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(fmaxf(mx, accS[0][r]), accS[1][r]);   // one three-input max each
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2e;
-    if (__any(mx > m_ref + 8.0f)) {   // also the first tile (m_ref = -inf)
-      const float m_new = fmaxf(m_ref, mx);
+      for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const int r = ks * 32 + lr, c = kk * 2 + g;
+          const uint4 fk = *(const uint4*)(sKb + r * ROWB + ((c ^ swz_k(r)) << 4));
+          accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fk), fq[kk], accS[ks], 0, 0, 0);
+        }
+      const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
+      if (need_mask) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+            if (key >= S || (causal && key > q_row)) accS[ks][r] = -INFINITY;
+          }
+      }
+    };
+    scores();
+    // The exponentials are taken against the reference point as it stands, without looking at the tile's maximum
+    // first; the lane's share of the row sum tells afterwards whether that was good enough.
+    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
+    float ps4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m));
+        ps4[r & 3] += accS[ks][r];
+      }
+    float tot = (ps4[0] + ps4[1]) + (ps4[2] + ps4[3]);   // this lane's 32 of the tile's 64 keys
+    // Rare path: some query of the wave has no reference point yet (first tile), or its probabilities against the
+    // old one add up to more than 2^7 per lane (also inf or NaN): the scores are computed again, the reference point
+    // moves to the running maximum, O and the running sum are rescaled, and the exponentials are taken against the
+    // new reference point.
+    if (__any(!(tot <= 128.0f) || m_ref == -INFINITY)) {
+      scores();
+      float mx0 = fmaxf(accS[0][0], accS[1][0]), mx1 = fmaxf(accS[0][1], accS[1][1]);   // three-input maxima
+#pragma unroll
+      for (int r = 2; r < 16; r += 2) {
+        mx0 = fmaxf(fmaxf(mx0, accS[0][r]), accS[1][r]);
+        mx1 = fmaxf(fmaxf(mx1, accS[0][r + 1]), accS[1][r + 1]);
+      }
+      float mlo, mhi;
+      halves(fmaxf(mx0, mx1), mlo, mhi);
+      const float m_new = fmaxf(m_ref, fmaxf(mlo, mhi) * scale_log2e);
       const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);   // m_ref = -inf -> 0
       l_run *= alpha;
 #pragma unroll
@@ -187,19 +225,17 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[i][r] *= alpha;
       m_ref = m_new;
+      const float neg_m2 = (m_ref == -INFINITY) ? 0.f : -m_ref;
+      tot = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m2));
+          tot += accS[ks][r];
+        }
     }
-    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
-    float ps = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m));
-        accS[ks][r] = p;
-        ps += p;
-      }
-    ps += __shfl_xor(ps, 32, 64);
-    l_run += ps;
+    l_run += tot;   // per lane: the two halves of a query's sum meet after the last tile
 
     // O^T += V^T P^T.  K step i covers keys 16i..16i+15; in operand slot (g, t) sits key
     // 16i + 8*(t/4) + 4g + t%4, which is register 8*(i%2) + t of accS[i/2].
@@ -221,6 +257,11 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
     }
   }
 
+  {
+    float llo, lhi;
+    halves(l_run, llo, lhi);
+    l_run = llo + lhi;
+  }
   if (q_row < S) {
     const float inv = (l_run > 0.f) ? 1.f / l_run : 0.f;
     bf16_t* orow = out + ((int64_t)b * S + q_row) * d + hd * DH;
