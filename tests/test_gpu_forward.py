@@ -244,6 +244,39 @@ def test_attention(dtype, B, S, h, dh, causal):
     assert np.abs(lse.cpu().numpy() - ref_lse).max() < (2e-2 if dtype == "bf16" else 1e-4)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("S,h,dh", [(300, 2, 64), (200, 2, 128)])
+def test_attention_when_the_softmax_reference_has_to_move(S, h, dh, causal):
+    # Keys grow along the sequence (scores of later tiles dwarf the running maximum, so the kernel's reference point
+    # has to move tile after tile), then a stretch of strongly negative scores (whose probabilities underflow against
+    # it), then small ones again.  Sec. 5 (the transformer fill job's attention); the oracle is the plain softmax.
+    pf, dev = _mods()
+    md = _md("bf16")
+    B, d = 2, h * dh
+    rng = np.random.default_rng(S + dh + int(causal))
+    qkv = _rand(rng, (B, S, 3 * d), "bf16", 1.5)
+    grow = np.concatenate([np.linspace(0.2, 9.0, S // 2), np.full(S // 4, -6.0), np.full(S - S // 2 - S // 4, 0.5)])
+    qkv[:, :, d:2 * d] *= grow[None, :, None].astype(qkv.dtype)
+    qkv = synth.round_to_bf16(qkv)
+    dq = dev.storage_tensor(qkv, md)
+    out = dev.empty_storage((B, S, d), md)
+    lse = torch.empty((B, h, S), dtype=torch.float32, device="cuda")
+    pf.pf_op_attention(md.dtype, dq.data_ptr(), out.data_ptr(), B, S, h, dh, causal, lse.data_ptr())
+    torch.cuda.synchronize()
+    q64 = qkv.astype(np.float64)
+    q, k, v = (ot.split_heads(q64[..., i * d:(i + 1) * d], h) for i in range(3))
+    ref = ot.merge_heads(ot.attention_probs(q, k, causal) @ v)
+    got = dev.read_storage(out, md)
+    assert np.isfinite(got).all()
+    assert rel_err(got, ref) < TOL["bf16"] / 2
+    s = q @ k.transpose(0, 1, 3, 2) / np.sqrt(dh)
+    if causal:
+        s = np.where(np.triu(np.ones((S, S), dtype=bool), 1), -np.inf, s)
+    mx = s.max(-1)
+    ref_lse = mx + np.log(np.exp(s - mx[..., None]).sum(-1))
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() < 5e-2
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_embedding(dtype):
     pf, dev = _mods()
