@@ -18,6 +18,19 @@ namespace pf {
 namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
+
+// Compute units of the current device, rounded down to a multiple of 8 (the XCDs); cached per device.
+inline int compute_units() {
+  static int cached[64] = {};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+  if (cached[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 8) n = 256;
+    cached[dev] = n & ~7;
+  }
+  return cached[dev];
+}
 constexpr float LN2 = 0.6931471805599453f;
 
 typedef short v4s __attribute__((ext_vector_type(4)));
@@ -27,11 +40,17 @@ typedef __attribute__((address_space(3))) void* lds_void_ptr;
 typedef const __attribute__((address_space(3))) char* lds_char_ptr;
 
 // ------------------------------------------------------------------------------------------------
-template <int DH, int NW>
+// PERSIST: the grid holds as many workgroups as the CUs keep resident, and each walks the units (batch, head, block
+// of QB queries) v = blockIdx.x, blockIdx.x + gridDim.x, ...  A workgroup that starts from scratch spends several
+// microseconds before its first MFMA (launch, kernel arguments, Q, the first K/V tile), as long as four to eight
+// tiles take; here the next unit's first tile is copied into the free LDS buffer during the current unit's last tile
+// and its Q fragments are requested before the current unit's results are stored, and a workgroup's units can be
+// chosen so that their lengths even out.  Otherwise one workgroup per unit (the launcher says which form pays where).
+template <int DH, int NW, bool PERSIST>
 __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ out,
                                                             float* __restrict__ lse, int32_t S, int32_t h,
                                                             int32_t causal, float scale_log2e, int32_t nq,
-                                                            int32_t n_wg) {
+                                                            int32_t n_units, int32_t flip_odd_rounds) {
   constexpr int CPR = DH / 8;        // 16-byte chunks per row
   constexpr int KS = DH / 16;        // MFMA K steps over d_head
   constexpr int DT = DH / 32;        // 32-row tiles of O^T
@@ -46,41 +65,31 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 31, g = lane >> 5;
-  // Workgroup ids are dealt round-robin to the 8 XCDs; remapped so that each XCD gets a contiguous range of
-  // (batch, head, query block) units, the query blocks of one head run on one XCD and its L2 serves their
-  // repeated reads of that head's K and V.
-  const int unit = (int)xcd_contiguous(blockIdx.x, n_wg);
-  const int b = unit / (nq * h), hd = (unit / nq) % h;
-  // causal: a query block's work grows with its position, so the blocks of a head are handed out last one first;
-  // the workgroups that start last are then the short ones
-  const int q_blk = (causal ? nq - 1 - unit % nq : unit % nq) * QB;
   const int d = h * DH;
   const int64_t rs = 3 * (int64_t)d;                       // row stride of qkv
-  const bf16_t* base = qkv + (int64_t)b * S * rs + hd * DH;
-  const int q_row = q_blk + wave * 32 + lr;                // this lane's query
-
   // Rows are addressed by a 32-bit row number times the row stride, clamped to the last row of the sequence, so
   // that no load sits in a branch: a clamped row repeats the last row of the sequence, which the tile holds anyway,
   // and the scores of the keys past the end are masked, so their probabilities are 0.
   const uint32_t rs32 = (uint32_t)rs;
-  bf16x8 fq[KS];
-  {
-    const bf16_t* qp = base + (uint64_t)(uint32_t)(q_row < S ? q_row : S - 1) * rs32 + g * 8;
-#pragma unroll
-    for (int kk = 0; kk < KS; ++kk) fq[kk] = as_bf16x8(*(const uint4*)(qp + kk * 16));
-  }
 
-  f32x16 accO[DT];
-#pragma unroll
-  for (int i = 0; i < DT; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) accO[i][r] = 0.f;
-  int n_tiles = (S + 63) / 64;
-  if (causal) {
-    const int last_q = (q_blk + QB - 1 < S - 1) ? q_blk + QB - 1 : S - 1;
-    const int need = last_q / 64 + 1;
-    if (need < n_tiles) n_tiles = need;
-  }
+  // Unit v of round k = v / gridDim.x.  Workgroup ids are dealt round-robin to the 8 XCDs and the grid is a multiple
+  // of 8, so a workgroup stays on its XCD; xcd_contiguous gives each XCD a contiguous range of units, the query
+  // blocks of one head run on one XCD at about the same time and its L2 serves their repeated reads of that head's
+  // K and V.  Causal: a block's work grows with its position.  Within a round the blocks of a head are handed out
+  // longest first, and where a round's units are whole heads (the launcher checks) odd rounds hand them out in the
+  // opposite order, so that a workgroup that drew a long block in one round draws a short one in the next.
+  struct Unit { int b, hd, q_blk; };
+  auto unit_of = [&](int v) {
+    const int u = (int)xcd_contiguous(v, n_units);
+    int pos = u % nq;
+    if (flip_odd_rounds && ((v / (int)gridDim.x) & 1)) pos = nq - 1 - pos;
+    Unit r;
+    r.b = u / (nq * h);
+    r.hd = (u / nq) % h;
+    r.q_blk = (causal ? nq - 1 - pos : pos) * QB;
+    return r;
+  };
+  auto base_of = [&](const Unit& u) { return qkv + (int64_t)u.b * S * rs + u.hd * DH; };
 
   // Swizzles (XOR on the 16-byte chunk index of a row).  K is read as the MFMA "A" operand, one 16-byte chunk per
   // lane, 32 consecutive rows per half-wave: rows are spread over the banks by (row / 2) % 8 (d_head 64: two rows
@@ -99,7 +108,7 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
   const int st_col_k = d + (((lane % CPR) ^ swz_k(st_row)) << 3);
   const int st_col_v = 2 * d + (((lane % CPR) ^ swz_v(st_row)) << 3);
   const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(lds_void_ptr)smem);
-  auto stage = [&](int buf, int k0) {
+  auto stage = [&](int buf, const bf16_t* base, int k0) {
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
       constexpr int HALF = PER / 2;
@@ -112,6 +121,13 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
       const bf16_t* p = base + (uint64_t)(uint32_t)row * rs32 + (is_v ? st_col_v : st_col_k);
       lds_direct_load_1k(dst, p);
     }
+  };
+  bf16x8 fq[KS];
+  auto load_q = [&](const bf16_t* base, int q_blk) {
+    const int q_row = q_blk + wave * 32 + lr;
+    const bf16_t* qp = base + (uint64_t)(uint32_t)(q_row < S ? q_row : S - 1) * rs32 + g * 8;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) fq[kk] = as_bf16x8(*(const uint4*)(qp + kk * 16));
   };
 
   // V^T operand of O^T += V^T P^T for K step i (keys 16 i .. 16 i + 15) and d_head block dt: lane 16 G + p points
@@ -140,140 +156,174 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
     hi = __builtin_bit_cast(float, b);
   };
 
-  // m_ref is the reference point of the running sum and of O (scaled scores, log2 units).  It follows the running
-  // maximum lazily: it moves only when a lane's share of a tile's row sum against it exceeds 2^7, so most tiles
-  // compute no maximum and skip the rescaling of O; the result is the same up to rounding.  l_run is this lane's
-  // share of the row sum (32 of every 64 keys).
-  float m_ref = -INFINITY, l_run = 0.f;
-  // The first tile's copies go out while the Q fragments are still on their way (one memory latency, not two);
-  // the fragments are then waited for here, once: left pending, the compiler would wait for them in every
-  // iteration with a count that also holds back the copies issued just before.
-  stage(0, 0);
+  int gt = 0;   // tiles staged so far by this workgroup: tile t of a unit lives in buffer (gt + t) % 2
+  int v = blockIdx.x;
+  Unit un = unit_of(v);
+  const bf16_t* base = base_of(un);
+  // The first tile's copies go out while the Q fragments are still on their way (one memory latency, not two).
+  stage(0, base, 0);
+  load_q(base, un.q_blk);
+  for (;;) {
+    const int q_blk = un.q_blk;
+    const int q_row = q_blk + wave * 32 + lr;                // this lane's query
+    const int vn = v + (int)gridDim.x;
+    const bool more = PERSIST && vn < n_units;
+    Unit un_next = un;
+    if (more) un_next = unit_of(vn);
+    const bf16_t* base_next = base_of(un_next);
+    // the Q fragments are waited for here, once: left pending, the compiler would wait for them in every iteration
+    // with a count that also holds back the copies issued just before
 #pragma unroll
-  for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fq[kk]));
-  for (int kt = 0; kt < n_tiles; ++kt) {
-    const int k0 = kt * 64;
-    // tile kt has landed (every wave waits for its own copies, then the barrier), and everyone has left tile
-    // kt - 1, whose buffer tile kt + 1 takes over
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < n_tiles) stage((kt + 1) & 1, k0 + 64);
-    // a wave whose 32 queries all precede this tile has nothing to add (causal)
-    if (causal && k0 > q_blk + wave * 32 + 31) continue;
-    const char* sKb = smem + (kt & 1) * 2 * TILE;
-    lds_char_ptr sVb = (lds_char_ptr)(lds_void_ptr)smem + (kt & 1) * 2 * TILE;
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fq[kk]));
 
-    // S^T tile: 64 keys x 32 queries per wave; masked only in the tiles that touch the diagonal or the end of the
-    // sequence
-    f32x16 accS[2];
-    auto scores = [&] {
+    f32x16 accO[DT];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
+    for (int i = 0; i < DT; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) accS[ks][r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KS; ++kk)
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-          const int r = ks * 32 + lr, c = kk * 2 + g;
-          const uint4 fk = *(const uint4*)(sKb + r * ROWB + ((c ^ swz_k(r)) << 4));
-          accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fk), fq[kk], accS[ks], 0, 0, 0);
-        }
-      const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
-      if (need_mask) {
-#pragma unroll
+      for (int r = 0; r < 16; ++r) accO[i][r] = 0.f;
+    int n_tiles = (S + 63) / 64;
+    if (causal) {
+      const int last_q = (q_blk + QB - 1 < S - 1) ? q_blk + QB - 1 : S - 1;
+      const int need = last_q / 64 + 1;
+      if (need < n_tiles) n_tiles = need;
+    }
+    // m_ref is the reference point of the running sum and of O (scaled scores, log2 units).  It follows the running
+    // maximum lazily: it moves only when a lane's share of a tile's row sum against it exceeds 2^7, so most tiles
+    // compute no maximum and skip the rescaling of O; the result is the same up to rounding.  l_run is this lane's
+    // share of the row sum (32 of every 64 keys).
+    float m_ref = -INFINITY, l_run = 0.f;
+    for (int kt = 0; kt < n_tiles; ++kt) {
+      const int k0 = kt * 64;
+      // tile kt has landed (every wave waits for its own copies, then the barrier), and everyone has left the tile
+      // before it, whose buffer the next tile takes over: tile kt + 1 of this unit, or the first of the next unit
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (kt + 1 < n_tiles) stage((gt + kt + 1) & 1, base, k0 + 64);
+      else if (more) stage((gt + kt + 1) & 1, base_next, 0);
+      // a wave whose 32 queries all precede this tile has nothing to add (causal)
+      if (!(causal && k0 > q_blk + wave * 32 + 31)) {
+        const char* sKb = smem + ((gt + kt) & 1) * 2 * TILE;
+        lds_char_ptr sVb = (lds_char_ptr)(lds_void_ptr)smem + ((gt + kt) & 1) * 2 * TILE;
+
+      // S^T tile: 64 keys x 32 queries per wave; masked only in the tiles that touch the diagonal or the end of the
+      // sequence
+      f32x16 accS[2];
+      auto scores = [&] {
+  #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
+  #pragma unroll
+          for (int r = 0; r < 16; ++r) accS[ks][r] = 0.f;
+  #pragma unroll
+        for (int kk = 0; kk < KS; ++kk)
+  #pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            const int r = ks * 32 + lr, c = kk * 2 + g;
+            const uint4 fk = *(const uint4*)(sKb + r * ROWB + ((c ^ swz_k(r)) << 4));
+            accS[ks] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fk), fq[kk], accS[ks], 0, 0, 0);
+          }
+        const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
+        if (need_mask) {
+  #pragma unroll
+          for (int ks = 0; ks < 2; ++ks)
+  #pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+              if (key >= S || (causal && key > q_row)) accS[ks][r] = -INFINITY;
+            }
+        }
+      };
+      scores();
+      // The exponentials are taken against the reference point as it stands, without looking at the tile's maximum
+      // first; the lane's share of the row sum tells afterwards whether that was good enough.
+      const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
+      float ps4[4] = {0.f, 0.f, 0.f, 0.f};
+  #pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+  #pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m));
+          ps4[r & 3] += accS[ks][r];
+        }
+      float tot = (ps4[0] + ps4[1]) + (ps4[2] + ps4[3]);   // this lane's 32 of the tile's 64 keys
+      // Rare path: some query of the wave has no reference point yet (first tile), or its probabilities against the
+      // old one add up to more than 2^7 per lane (also inf or NaN): the scores are computed again, the reference point
+      // moves to the running maximum, O and the running sum are rescaled, and the exponentials are taken against the
+      // new reference point.
+      if (__any(!(tot <= 128.0f) || m_ref == -INFINITY)) {
+        scores();
+        float mx0 = fmaxf(accS[0][0], accS[1][0]), mx1 = fmaxf(accS[0][1], accS[1][1]);   // three-input maxima
+  #pragma unroll
+        for (int r = 2; r < 16; r += 2) {
+          mx0 = fmaxf(fmaxf(mx0, accS[0][r]), accS[1][r]);
+          mx1 = fmaxf(fmaxf(mx1, accS[0][r + 1]), accS[1][r + 1]);
+        }
+        float mlo, mhi;
+        halves(fmaxf(mx0, mx1), mlo, mhi);
+        const float m_new = fmaxf(m_ref, fmaxf(mlo, mhi) * scale_log2e);
+        const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);   // m_ref = -inf -> 0
+        l_run *= alpha;
+  #pragma unroll
+        for (int i = 0; i < DT; ++i)
+  #pragma unroll
+          for (int r = 0; r < 16; ++r) accO[i][r] *= alpha;
+        m_ref = m_new;
+        const float neg_m2 = (m_ref == -INFINITY) ? 0.f : -m_ref;
+        tot = 0.f;
+  #pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+  #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (key >= S || (causal && key > q_row)) accS[ks][r] = -INFINITY;
+            accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m2));
+            tot += accS[ks][r];
           }
       }
-    };
-    scores();
-    // The exponentials are taken against the reference point as it stands, without looking at the tile's maximum
-    // first; the lane's share of the row sum tells afterwards whether that was good enough.
-    const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
-    float ps4[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m));
-        ps4[r & 3] += accS[ks][r];
-      }
-    float tot = (ps4[0] + ps4[1]) + (ps4[2] + ps4[3]);   // this lane's 32 of the tile's 64 keys
-    // Rare path: some query of the wave has no reference point yet (first tile), or its probabilities against the
-    // old one add up to more than 2^7 per lane (also inf or NaN): the scores are computed again, the reference point
-    // moves to the running maximum, O and the running sum are rescaled, and the exponentials are taken against the
-    // new reference point.
-    if (__any(!(tot <= 128.0f) || m_ref == -INFINITY)) {
-      scores();
-      float mx0 = fmaxf(accS[0][0], accS[1][0]), mx1 = fmaxf(accS[0][1], accS[1][1]);   // three-input maxima
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) {
-        mx0 = fmaxf(fmaxf(mx0, accS[0][r]), accS[1][r]);
-        mx1 = fmaxf(fmaxf(mx1, accS[0][r + 1]), accS[1][r + 1]);
-      }
-      float mlo, mhi;
-      halves(fmaxf(mx0, mx1), mlo, mhi);
-      const float m_new = fmaxf(m_ref, fmaxf(mlo, mhi) * scale_log2e);
-      const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);   // m_ref = -inf -> 0
-      l_run *= alpha;
-#pragma unroll
-      for (int i = 0; i < DT; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) accO[i][r] *= alpha;
-      m_ref = m_new;
-      const float neg_m2 = (m_ref == -INFINITY) ? 0.f : -m_ref;
-      tot = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m2));
-          tot += accS[ks][r];
+      l_run += tot;   // per lane: the two halves of a query's sum meet after the last tile
+
+      // O^T += V^T P^T.  K step i covers keys 16i..16i+15; in operand slot (g, t) sits key
+      // 16i + 8*(t/4) + 4g + t%4, which is register 8*(i%2) + t of accS[i/2].
+  #pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        bf16x8 fp;
+  #pragma unroll
+        for (int t = 0; t < 8; ++t) fp[t] = (__bf16)accS[i >> 1][8 * (i & 1) + t];
+  #pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          lds_char_ptr vp = sVb + v_off[dt] + 16 * i * ROWB;
+          const v4s r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)vp);
+          const v4s r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(vp + 8 * ROWB));
+          v8s fv;
+          fv[0] = r0[0]; fv[1] = r0[1]; fv[2] = r0[2]; fv[3] = r0[3];
+          fv[4] = r1[0]; fv[5] = r1[1]; fv[6] = r1[2]; fv[7] = r1[3];
+          accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fv), fp, accO[dt], 0, 0, 0);
         }
-    }
-    l_run += tot;   // per lane: the two halves of a query's sum meet after the last tile
-
-    // O^T += V^T P^T.  K step i covers keys 16i..16i+15; in operand slot (g, t) sits key
-    // 16i + 8*(t/4) + 4g + t%4, which is register 8*(i%2) + t of accS[i/2].
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      bf16x8 fp;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) fp[t] = (__bf16)accS[i >> 1][8 * (i & 1) + t];
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        lds_char_ptr vp = sVb + v_off[dt] + 16 * i * ROWB;
-        const v4s r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)vp);
-        const v4s r1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)(vp + 8 * ROWB));
-        v8s fv;
-        fv[0] = r0[0]; fv[1] = r0[1]; fv[2] = r0[2]; fv[3] = r0[3];
-        fv[4] = r1[0]; fv[5] = r1[1]; fv[6] = r1[2]; fv[7] = r1[3];
-        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fv), fp, accO[dt], 0, 0, 0);
+      }
       }
     }
-  }
+    gt += n_tiles;
+    if (more) load_q(base_next, un_next.q_blk);   // on their way while this unit's results are stored
 
-  {
-    float llo, lhi;
-    halves(l_run, llo, lhi);
-    l_run = llo + lhi;
-  }
-  if (q_row < S) {
-    const float inv = (l_run > 0.f) ? 1.f / l_run : 0.f;
-    bf16_t* orow = out + ((int64_t)b * S + q_row) * d + hd * DH;
+    {
+      float llo, lhi;
+      halves(l_run, llo, lhi);
+      l_run = llo + lhi;
+    }
+    if (q_row < S) {
+      const float inv = (l_run > 0.f) ? 1.f / l_run : 0.f;
+      bf16_t* orow = out + ((int64_t)un.b * S + q_row) * d + un.hd * DH;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+      for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const float v[4] = {accO[dt][rg * 4] * inv, accO[dt][rg * 4 + 1] * inv, accO[dt][rg * 4 + 2] * inv,
-                            accO[dt][rg * 4 + 3] * inv};
-        store4(orow + dt * 32 + rg * 8 + g * 4, v);
-      }
-    if (lse && g == 0) lse[((int64_t)b * h + hd) * S + q_row] = m_ref * LN2 + __logf(l_run);
+        for (int rg = 0; rg < 4; ++rg) {
+          const float vv[4] = {accO[dt][rg * 4] * inv, accO[dt][rg * 4 + 1] * inv, accO[dt][rg * 4 + 2] * inv,
+                               accO[dt][rg * 4 + 3] * inv};
+          store4(orow + dt * 32 + rg * 8 + g * 4, vv);
+        }
+      if (lse && g == 0) lse[((int64_t)un.b * h + un.hd) * S + q_row] = m_ref * LN2 + __logf(l_run);
+    }
+    if (!more) break;
+    v = vn;
+    un = un_next;
+    base = base_next;
   }
 }
 
@@ -366,16 +416,29 @@ hipError_t attention_fwd(int32_t dtype, const void* qkv, void* out, float* lse, 
     // the causal 1024-token shape, -1.5 % on 512 tokens); d_head 128 with eight is 13 % slower (one workgroup per CU)
     constexpr int NW64 = 8, NW128 = 4;
     const int qb = 32 * (dh == 64 ? NW64 : NW128);
-    const int64_t nq = (S + qb - 1) / qb, n_wg = nq * h * B;
-    if (n_wg > 0x7fffffff) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)n_wg), block((unsigned)(2 * qb));
+    const int64_t nq = (S + qb - 1) / qb, n_units = nq * h * B;
+    if (n_units > 0x7fffffff) return hipErrorInvalidValue;
     const float sl = LOG2E / sqrtf((float)dh);
-    if (dh == 64)
-      hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, NW64>), grid, block, 0, stream, (const bf16_t*)qkv, (bf16_t*)out, lse,
-                         S, h, causal, sl, (int32_t)nq, (int32_t)n_wg);
-    else
-      hipLaunchKernelGGL((attn_fwd_bf16_kernel<128, NW128>), grid, block, 0, stream, (const bf16_t*)qkv, (bf16_t*)out,
-                         lse, S, h, causal, sl, (int32_t)nq, (int32_t)n_wg);
+    const dim3 block((unsigned)(2 * qb));
+    // The persistent form pays for causal d_head 128 (MI355X, same box: 116 -> 89 us on 64 heads of 2048 tokens,
+    // 140 -> 122 us on 256 heads of 1024): units of unequal length even out over a workgroup's rounds and the next
+    // unit's first loads hide behind the current one.  With equal units (not causal) the hardware's own dispatch
+    // of one workgroup per unit is 5 % faster, and with d_head 64 the persistent loop needs one register more than
+    // the 128 that four waves per SIMD allow.
+    const int64_t resident = 2 * (int64_t)compute_units();   // two workgroups per CU at a time (LDS)
+    if (dh == 128 && causal && n_units > resident) {
+      // odd rounds may hand a head's blocks out in the opposite order only if every round's share of an XCD's range
+      // is whole heads: the reversal then permutes units within the round
+      const int32_t flip = (n_units % (8 * nq) == 0 && (resident / 8) % nq == 0) ? 1 : 0;
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<128, NW128, true>), dim3((unsigned)resident), block, 0, stream,
+                         (const bf16_t*)qkv, (bf16_t*)out, lse, S, h, causal, sl, (int32_t)nq, (int32_t)n_units, flip);
+    } else if (dh == 64) {
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, NW64, false>), dim3((unsigned)n_units), block, 0, stream,
+                         (const bf16_t*)qkv, (bf16_t*)out, lse, S, h, causal, sl, (int32_t)nq, (int32_t)n_units, 0);
+    } else {
+      hipLaunchKernelGGL((attn_fwd_bf16_kernel<128, NW128, false>), dim3((unsigned)n_units), block, 0, stream,
+                         (const bf16_t*)qkv, (bf16_t*)out, lse, S, h, causal, sl, (int32_t)nq, (int32_t)n_units, 0);
+    }
     return hipGetLastError();
   }
   if (dtype == PF_DTYPE_BF16_) return launch_generic<bf16_t>(qkv, out, lse, B, S, h, dh, causal, stream);

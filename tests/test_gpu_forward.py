@@ -244,6 +244,39 @@ def test_attention(dtype, B, S, h, dh, causal):
     assert np.abs(lse.cpu().numpy() - ref_lse).max() < (2e-2 if dtype == "bf16" else 1e-4)
 
 
+@pytest.mark.parametrize("B,S,h", [(8, 1024, 16), (3, 900, 22)])
+def test_attention_with_more_units_than_resident_workgroups(B, S, h):
+    # Causal attention with d_head 128 on more (batch, head, query block) units than the GPU keeps workgroups
+    # resident: the kernel then walks several units per workgroup (the first case in rounds of whole heads, handed
+    # out in alternating order; the second with a ragged last block and rounds that split heads).  Sec. 5; compared
+    # with the plain softmax on every query of a sample of heads.
+    pf, dev = _mods()
+    md = _md("bf16")
+    dh, d = 128, h * 128
+    rng = np.random.default_rng(B * 100 + h)
+    qkv = _rand(rng, (B, S, 3 * d), "bf16", 1.2)
+    dq = dev.storage_tensor(qkv, md)
+    out = dev.empty_storage((B, S, d), md)
+    lse = torch.empty((B, h, S), dtype=torch.float32, device="cuda")
+    pf.pf_op_attention(md.dtype, dq.data_ptr(), out.data_ptr(), B, S, h, dh, True, lse.data_ptr())
+    torch.cuda.synchronize()
+    got = dev.read_storage(out, md).reshape(B, S, h, dh)
+    lse_got = lse.cpu().numpy()
+    assert np.isfinite(got).all()
+    heads = sorted({(0, 0), (B - 1, h - 1), (B // 2, h // 3), (B - 1, 0), (0, h - 1), (B // 2, h - 2)})
+    for b, i in heads:
+        q, k, v = (qkv[b, :, j * d + i * dh: j * d + (i + 1) * dh].astype(np.float64) for j in range(3))
+        s_ = q @ k.T / np.sqrt(dh)
+        s_ = np.where(np.triu(np.ones((S, S), dtype=bool), 1), -np.inf, s_)
+        mx = s_.max(-1, keepdims=True)
+        e = np.exp(s_ - mx)
+        ref = (e / e.sum(-1, keepdims=True)) @ v
+        assert rel_err(got[b, :, i, :], ref) < TOL["bf16"] / 2, (b, i)
+        assert np.abs(lse_got[b, i] - (mx[:, 0] + np.log(e.sum(-1)))).max() < 2e-2, (b, i)
+    # every other head: finite and not all zero (a unit nobody visited would be)
+    assert (np.abs(got).reshape(B, S, h, dh).max(axis=(1, 3)) > 0).all()
+
+
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("S,h,dh", [(300, 2, 64), (200, 2, 128)])
 def test_attention_when_the_softmax_reference_has_to_move(S, h, dh, causal):
