@@ -244,15 +244,16 @@ def test_attention(dtype, B, S, h, dh, causal):
     assert np.abs(lse.cpu().numpy() - ref_lse).max() < (2e-2 if dtype == "bf16" else 1e-4)
 
 
-@pytest.mark.parametrize("B,S,h", [(8, 1024, 16), (3, 900, 22)])
-def test_attention_with_more_units_than_resident_workgroups(B, S, h):
-    # Causal attention with d_head 128 on more (batch, head, query block) units than the GPU keeps workgroups
-    # resident: the kernel then walks several units per workgroup (the first case in rounds of whole heads, handed
-    # out in alternating order; the second with a ragged last block and rounds that split heads).  Sec. 5; compared
-    # with the plain softmax on every query of a sample of heads.
+@pytest.mark.parametrize("B,S,h,dh", [(8, 1024, 16, 128), (3, 900, 22, 128), (8, 1024, 16, 64), (4, 1024, 16, 128)])
+def test_attention_where_the_kernel_reorders_causal_blocks(B, S, h, dh):
+    # Causal attention at sizes where the kernel hands the query blocks out in an order of its own.  First two cases:
+    # d_head 128 on more (batch, head, query block) units than the GPU keeps workgroups resident, so that a workgroup
+    # walks several units (in rounds of whole heads, handed out in alternating order; then with a ragged last block
+    # and rounds that split heads).  Last two: exactly as many units as resident workgroups, the second half of each
+    # XCD's range reversed.  Sec. 5; compared with the plain softmax on every query of a sample of heads.
     pf, dev = _mods()
     md = _md("bf16")
-    dh, d = 128, h * 128
+    d = h * dh
     rng = np.random.default_rng(B * 100 + h)
     qkv = _rand(rng, (B, S, 3 * d), "bf16", 1.2)
     dq = dev.storage_tensor(qkv, md)
