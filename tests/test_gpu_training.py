@@ -415,7 +415,9 @@ def test_main_offload_argument_errors():
 # than a tile, a ragged multiple of the block; the other cases run on the generic kernels
 ATT_BWD = [("bf16", 2, 200, 3, 64), ("bf16", 1, 321, 2, 128), ("bf16", 2, 64, 2, 64), ("bf16", 1, 130, 2, 16),
            ("f32", 2, 100, 2, 32), ("f32", 1, 70, 1, 64), ("bf16", 1, 1, 1, 64), ("bf16", 1, 65, 1, 128),
-           ("bf16", 1, 129, 2, 64)]
+           ("bf16", 1, 129, 2, 64),
+           # sizes at which the causal kernels hand the blocks of every other group of 32 units out in reverse order
+           ("bf16", 2, 1024, 16, 64), ("bf16", 1, 2048, 16, 128)]
 
 
 @pytest.mark.parametrize("causal", [False, True])
