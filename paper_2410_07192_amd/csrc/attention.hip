@@ -214,13 +214,13 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
       // sequence
       f32x16 accS[2];
       auto scores = [&] {
-  #pragma unroll
+#pragma unroll
         for (int ks = 0; ks < 2; ++ks)
-  #pragma unroll
+#pragma unroll
           for (int r = 0; r < 16; ++r) accS[ks][r] = 0.f;
-  #pragma unroll
+#pragma unroll
         for (int kk = 0; kk < KS; ++kk)
-  #pragma unroll
+#pragma unroll
           for (int ks = 0; ks < 2; ++ks) {
             const int r = ks * 32 + lr, c = kk * 2 + g;
             const uint4 fk = *(const uint4*)(sKb + r * ROWB + ((c ^ swz_k(r)) << 4));
@@ -228,9 +228,9 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
           }
         const bool need_mask = (k0 + 63 >= S) || (causal && k0 + 63 > q_blk + wave * 32);
         if (need_mask) {
-  #pragma unroll
+#pragma unroll
           for (int ks = 0; ks < 2; ++ks)
-  #pragma unroll
+#pragma unroll
             for (int r = 0; r < 16; ++r) {
               const int key = k0 + ks * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
               if (key >= S || (causal && key > q_row)) accS[ks][r] = -INFINITY;
@@ -242,9 +242,9 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
       // first; the lane's share of the row sum tells afterwards whether that was good enough.
       const float neg_m = (m_ref == -INFINITY) ? 0.f : -m_ref;
       float ps4[4] = {0.f, 0.f, 0.f, 0.f};
-  #pragma unroll
+#pragma unroll
       for (int ks = 0; ks < 2; ++ks)
-  #pragma unroll
+#pragma unroll
         for (int r = 0; r < 16; ++r) {
           accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m));
           ps4[r & 3] += accS[ks][r];
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
       if (__any(!(tot <= 128.0f) || m_ref == -INFINITY)) {
         scores();
         float mx0 = fmaxf(accS[0][0], accS[1][0]), mx1 = fmaxf(accS[0][1], accS[1][1]);   // three-input maxima
-  #pragma unroll
+#pragma unroll
         for (int r = 2; r < 16; r += 2) {
           mx0 = fmaxf(fmaxf(mx0, accS[0][r]), accS[1][r]);
           mx1 = fmaxf(fmaxf(mx1, accS[0][r + 1]), accS[1][r + 1]);
@@ -267,16 +267,16 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
         const float m_new = fmaxf(m_ref, fmaxf(mlo, mhi) * scale_log2e);
         const float alpha = (m_new == -INFINITY) ? 1.0f : __builtin_amdgcn_exp2f(m_ref - m_new);   // m_ref = -inf -> 0
         l_run *= alpha;
-  #pragma unroll
+#pragma unroll
         for (int i = 0; i < DT; ++i)
-  #pragma unroll
+#pragma unroll
           for (int r = 0; r < 16; ++r) accO[i][r] *= alpha;
         m_ref = m_new;
         const float neg_m2 = (m_ref == -INFINITY) ? 0.f : -m_ref;
         tot = 0.f;
-  #pragma unroll
+#pragma unroll
         for (int ks = 0; ks < 2; ++ks)
-  #pragma unroll
+#pragma unroll
           for (int r = 0; r < 16; ++r) {
             accS[ks][r] = __builtin_amdgcn_exp2f(fmaf(accS[ks][r], scale_log2e, neg_m2));
             tot += accS[ks][r];
@@ -286,12 +286,12 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
 
       // O^T += V^T P^T.  K step i covers keys 16i..16i+15; in operand slot (g, t) sits key
       // 16i + 8*(t/4) + 4g + t%4, which is register 8*(i%2) + t of accS[i/2].
-  #pragma unroll
+#pragma unroll
       for (int i = 0; i < 4; ++i) {
         bf16x8 fp;
-  #pragma unroll
+#pragma unroll
         for (int t = 0; t < 8; ++t) fp[t] = (__bf16)accS[i >> 1][8 * (i & 1) + t];
-  #pragma unroll
+#pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
           lds_char_ptr vp = sVb + v_off[dt] + 16 * i * ROWB;
           const v4s r0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s_ptr)vp);
