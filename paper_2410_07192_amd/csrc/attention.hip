@@ -176,8 +176,11 @@ __global__ __launch_bounds__(64 * NW, (DH == 64 ? 16 : 8) / NW) void attn_fwd_bf
     Unit un_next = un;
     if (more) un_next = unit_of(vn);
     const bf16_t* base_next = base_of(un_next);
-    // the Q fragments are waited for here, once: left pending, the compiler would wait for them in every iteration
-    // with a count that also holds back the copies issued just before
+    // The Q fragments are waited for here, once: left pending, the compiler would wait for them in every iteration
+    // with a count that also holds back the copies issued just before.  After the first unit the previous unit's
+    // stores are younger than these loads; a count that lets younger stores stay in flight relies on stores and
+    // loads retiring in one order, so everything is waited for (the first tile's copies are needed next anyway).
+    if (PERSIST) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) asm volatile("" ::"v"(fq[kk]));
 
