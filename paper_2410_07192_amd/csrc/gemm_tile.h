@@ -587,25 +587,31 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_w4_kernel(
     const int64_t row = r <= last ? r : last;
     off[i] = (uint32_t)((row * K + c * 8) * 2);
   }
-  const char* const xbase = (const char*)(X + m0 * K);
-  const char* const wbase = (const char*)(W + n0 * K);
+  // Buffer loads: the tile's first row is the base of a raw buffer (no stride, no bounds to speak of: every offset
+  // stays below 2^31), the lane's offset a 32-bit register, the K step a scalar offset.
+  const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(X + m0 * K), 0, 0x7fffffff, 0x00020000);
+  const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(W + n0 * K), 0, 0x7fffffff, 0x00020000);
   auto gload = [&](auto ic, int64_t k0) {
     constexpr int i = decltype(ic)::value;
-    return *(const u32x4*)((i < GPW / 2 ? xbase : wbase) + k0 * 2 + (uint64_t)off[i]);
+    return __builtin_amdgcn_raw_buffer_load_b128(i < GPW / 2 ? xrsrc : wrsrc, (int)off[i], (int)(k0 * 2), 0);
   };
   const int wro = wave * 64 + lane;   // group g of a stage starts at uint4 index g * 64: this lane's place in group `wave`
-  int offW[TN], offX[TM], swW[TN], swX[TM];
+  // Fragment addresses without arithmetic in the loop.  Row r of a stage holds its 16-byte chunk c at position
+  // c ^ (r / 2) % 8, and the rows a lane reads are 32 apart, so every fragment of a lane has the same swizzle: the
+  // chunk of slice kk sits at ((kk ^ s1) * 2 + l0) with s1 and l0 fixed per lane.  One address per stage, operand and
+  // slice (sixteen registers); the 32-row blocks and nothing else go into the instructions' immediate offsets.
+  const uint4* fx_at[2][4];
+  const uint4* fw_at[2][4];
+  {
+    const int sw = (lr >> 1) & 7, s1 = sw >> 1, l0 = lk ^ (sw & 1);
 #pragma unroll
-  for (int a = 0; a < TN; ++a) {
-    const int r = (wn * TN + a) * 32 + lr;
-    offW[a] = BM * 8 + r * 8;
-    swW[a] = (r >> 1) & 7;
-  }
+    for (int st = 0; st < 2; ++st)
 #pragma unroll
-  for (int b = 0; b < TM; ++b) {
-    const int r = (wm * TM + b) * 32 + lr;
-    offX[b] = r * 8;
-    swX[b] = (r >> 1) & 7;
+      for (int kk = 0; kk < 4; ++kk) {
+        const int chunk = (kk ^ s1) * 2 + l0;
+        fx_at[st][kk] = smem + st * STAGE + ((wm * TM) * 32 + lr) * 8 + chunk;
+        fw_at[st][kk] = smem + st * STAGE + BM * 8 + ((wn * TN) * 32 + lr) * 8 + chunk;
+      }
   }
   f32x16 acc[TN][TM];
 #pragma unroll
@@ -615,13 +621,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_w4_kernel(
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
   bf16x8 fw[2][TN], fx[2][TM];
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  using I2 = std::integral_constant<int, 2>;
+  using I3 = std::integral_constant<int, 3>;
   // fragment j of a 16-wide slice, in the order the MFMAs first need them: W block 0, the four X blocks, W blocks 1..3
-  auto load_frag = [&](auto bufc, auto jc, const uint4* st, int kk) {
-    constexpr int buf = decltype(bufc)::value, j = decltype(jc)::value;
-    const int c = kk * 2 + lk;
-    if constexpr (j == 0) fw[buf][0] = as_bf16x8(st[offW[0] + (c ^ swW[0])]);
-    else if constexpr (j <= 4) fx[buf][j - 1] = as_bf16x8(st[offX[j - 1] + (c ^ swX[j - 1])]);
-    else fw[buf][j - 4] = as_bf16x8(st[offW[j - 4] + (c ^ swW[j - 4])]);
+  auto load_frag = [&](auto bufc, auto jc, auto stc, auto kkc) {
+    constexpr int buf = decltype(bufc)::value, j = decltype(jc)::value, st = decltype(stc)::value, kk = decltype(kkc)::value;
+    if constexpr (j == 0) fw[buf][0] = as_bf16x8(fw_at[st][kk][0]);
+    else if constexpr (j <= 4) fx[buf][j - 1] = as_bf16x8(fx_at[st][kk][(j - 1) * 256]);
+    else fw[buf][j - 4] = as_bf16x8(fw_at[st][kk][(j - 4) * 256]);
   };
   u32x4 R[GPW];
   constexpr int MF = TM * TN;   // 16 MFMAs per 16-wide slice of the K step
@@ -631,13 +640,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_w4_kernel(
   // then four times {write register quad q to the next stage, reload it for the stage after next}.  Slice 3: the last
   // four writes and reloads first, the barrier behind the eighth MFMA, then the first fragments of the next stage.
   // WR: stage kt + 1 exists (its groups wait in R); LD: stage kt + 2 exists.
-  auto slice = [&](auto kkc, auto wrc, auto ldc, const uint4* sc, uint4* sn, int64_t k_next2) {
-    constexpr int KK = decltype(kkc)::value, buf = KK & 1, nbuf = buf ^ 1;
+  auto slice = [&](auto kkc, auto wrc, auto ldc, auto curc, int64_t k_next2) {
+    constexpr int KK = decltype(kkc)::value, buf = KK & 1, nbuf = buf ^ 1, CUR = decltype(curc)::value;
+    uint4* const sn = smem + (CUR ^ 1) * STAGE;
     constexpr bool WR = decltype(wrc)::value, LD = decltype(ldc)::value;
     static_for<0, MF>([&](auto mi) {
+      // One wait per group instead of one per use (the compiler, which still places every wait that is needed,
+      // drops its own where these make them redundant): all eight fragments of this slice, read eight to sixteen
+      // instructions ago with four LDS stores behind them, at the slice's first MFMA; the four register quads about
+      // to be stored, loaded a K step ago with twelve younger loads behind them, at the first store.
+      if constexpr (mi == 0 && KK > 0) __builtin_amdgcn_s_waitcnt(0xc47f);                                   // lgkmcnt(4)
+      if constexpr (WR && LD && ((KK < 3 && mi == 8) || (KK == 3 && mi == 0))) __builtin_amdgcn_s_waitcnt(0x0f7c);   // vmcnt(12)
       if constexpr (KK < 3) {
         if constexpr (mi < 8) {
-          load_frag(std::integral_constant<int, nbuf>{}, mi, sc, KK + 1);
+          load_frag(std::integral_constant<int, nbuf>{}, mi, curc, std::integral_constant<int, (KK + 1) & 3>{});
         } else {
           constexpr int q = 4 * KK + (mi - 8) / 2;
           if constexpr ((mi & 1) == 0) {
@@ -657,7 +673,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_w4_kernel(
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
           }
-          if constexpr (WR) load_frag(std::integral_constant<int, nbuf>{}, std::integral_constant<int, mi - 8>{}, sn, 0);
+          if constexpr (WR) load_frag(std::integral_constant<int, nbuf>{}, std::integral_constant<int, mi - 8>{}, std::integral_constant<int, CUR ^ 1>{}, I0{});
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -666,34 +682,37 @@ __global__ __launch_bounds__(256) void gemm_bf16_nt_w4_kernel(
       __builtin_amdgcn_sched_barrier(0);
     });
   };
-  using I0 = std::integral_constant<int, 0>;
-  using I1 = std::integral_constant<int, 1>;
-  using I2 = std::integral_constant<int, 2>;
-  using I3 = std::integral_constant<int, 3>;
-  auto step = [&](auto wrc, auto ldc, int cur, int64_t k_next2) {
-    const uint4* sc = smem + cur * STAGE;
-    uint4* sn = smem + (cur ^ 1) * STAGE;
-    slice(I0{}, wrc, ldc, sc, sn, k_next2);
-    slice(I1{}, wrc, ldc, sc, sn, k_next2);
-    slice(I2{}, wrc, ldc, sc, sn, k_next2);
-    slice(I3{}, wrc, ldc, sc, sn, k_next2);
+  // The stage is a compile-time constant (its addresses are picked from registers, not computed), so even and odd K
+  // steps are separate instantiations.  Step kt works on stage (kt + nk) % 2: the last step is then always on stage
+  // 1 and the one before it on stage 0 whatever nk is, and only the very first step of an odd nk stands alone.
+  auto step = [&](auto wrc, auto ldc, auto curc, int64_t k_next2) {
+    slice(I0{}, wrc, ldc, curc, k_next2);
+    slice(I1{}, wrc, ldc, curc, k_next2);
+    slice(I2{}, wrc, ldc, curc, k_next2);
+    slice(I3{}, wrc, ldc, curc, k_next2);
   };
 
   const int64_t nk = K / 64;
-  // prologue: stage 0 through the registers into LDS, stage 1 into the registers
+  const int s0 = (int)(nk & 1);
+  // prologue: K step 0 through the registers into its stage, step 1 into the registers, the first fragments
   static_for<0, GPW>([&](auto i) { R[i] = gload(i, 0); });
-  static_for<0, GPW>([&](auto i) { *(u32x4*)(smem + wro + i * NW * 64) = R[i]; });
+  static_for<0, GPW>([&](auto i) { *(u32x4*)(smem + s0 * STAGE + wro + i * NW * 64) = R[i]; });
   if (nk > 1) static_for<0, GPW>([&](auto i) { R[i] = gload(i, 64); });
   __builtin_amdgcn_s_waitcnt(0xc07f);
   __builtin_amdgcn_s_barrier();
-  static_for<0, 8>([&](auto j) { load_frag(I0{}, j, smem, 0); });
+  if (s0) static_for<0, 8>([&](auto j) { load_frag(I0{}, j, I1{}, I0{}); });
+  else static_for<0, 8>([&](auto j) { load_frag(I0{}, j, I0{}, I0{}); });
   int64_t kt = 0;
-  for (; kt + 2 < nk; ++kt) step(std::true_type{}, std::true_type{}, (int)(kt & 1), (kt + 2) * 64);
-  if (kt + 1 < nk) {
-    step(std::true_type{}, std::false_type{}, (int)(kt & 1), 0);
-    ++kt;
+  if (nk >= 3 && s0) {
+    step(std::true_type{}, std::true_type{}, I1{}, 2 * 64);
+    kt = 1;
   }
-  step(std::false_type{}, std::false_type{}, (int)(kt & 1), 0);
+  for (; kt + 2 < nk; kt += 2) {
+    step(std::true_type{}, std::true_type{}, I0{}, (kt + 2) * 64);
+    step(std::true_type{}, std::true_type{}, I1{}, (kt + 3) * 64);
+  }
+  if (nk >= 2) step(std::true_type{}, std::false_type{}, I0{}, 0);
+  step(std::false_type{}, std::false_type{}, I1{}, 0);
 
   tile_epilogue<WGM, WGN, TM, TN, OutT, EPI>(acc, smem, C, M, N, ep, m0, n0);
 }
