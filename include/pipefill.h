@@ -257,7 +257,8 @@ int32_t pf_offload_plan(int32_t p, int32_t m, int32_t stage, int64_t tf_ns, int6
  * first_dur_ns (what is left of it; the fill fraction and the switch time apply to it as to any
  * bubble) instead of its dur_ns.  Later visits of that bubble, and the replication count, use
  * dur_ns.  first_dur_ns < 0: no such shortening (identical to pf_plan_bubbles).  A first chunk
- * that takes no node is an ordinary empty chunk. */
+ * that takes no node is an ordinary empty chunk; being shortened, it does not count among the
+ * consecutive empty chunks after which a node is declared to fit no bubble (PF_ERR_INFEASIBLE). */
 int32_t pf_plan_bubbles_from(const pf_bubble* bubbles, int32_t n_bubbles, const pf_node* F, int32_t nF,
                              int64_t fill_ppm, int64_t switch_ns, int32_t first_bubble,
                              int64_t first_dur_ns, pf_chunk* out, int32_t cap, int32_t* n_out,

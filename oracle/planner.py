@@ -25,7 +25,9 @@ Readings where the paper is silent (each is listed in the design notes):
     every bubble duration by fill_ppm/1e6 with floor division, and a fixed
     per-bubble switch cost may be subtracted;
   - a node that fits no bubble would make Algorithm 1 loop forever; here the
-    procedure stops with Infeasible after len(B) consecutive empty partitions;
+    procedure stops with Infeasible after len(B) consecutive empty partitions
+    (a first visit shortened by first_dur is not one of them: it says nothing
+    about what a whole bubble holds);
   - only bubbles flagged fillable take part; P[i] runs in the
     ((first + i) mod n)-th fillable bubble of cycle (first + i) div n.
 """
@@ -166,9 +168,11 @@ def partition_fill_job(bubbles, F, fill_ppm=1_000_000, first_bubble=0, switch_ns
         chunks.append(dict(bubble=idx[i], cycle=slot // n, node_begin=begin, node_end=pos,
                            dur=dur, mem=mem))
         if pos == begin:
-            empty_run += 1
-            if empty_run >= n:
-                raise Infeasible(pos % len(F))
+            # the shortened first visit says nothing about what a whole bubble holds: only full visits count
+            if not (first_dur is not None and len(chunks) == 1):
+                empty_run += 1
+                if empty_run >= n:
+                    raise Infeasible(pos % len(F))
         else:
             empty_run = 0
         i = (i + 1) % n

@@ -83,7 +83,10 @@ PlanResult plan_impl(const pf_bubble* B, int32_t nB, const pf_node* F, int32_t n
     ++r.n_chunks;
     if (cm > r.peak_mem) r.peak_mem = cm;
     if (pos == begin) {
-      if (++empty_run >= n) {          // a whole cycle took nothing: this node fits nowhere
+      // a whole cycle took nothing: this node fits nowhere.  The shortened first visit of a job handed over in the
+      // middle of a bubble says nothing about what a whole bubble holds and does not count.
+      const bool shortened = first_dur >= 0 && r.n_chunks == 1;
+      if (!shortened && ++empty_run >= n) {
         r.rc = PF_ERR_INFEASIBLE;
         r.bad_node = (int32_t)(pos % nF);
         return r;

@@ -119,6 +119,14 @@ def test_plan_with_a_shortened_first_bubble_bit_exact():
     F = [(7, 1), (9, 2), (5, 1)]
     assert pf.pf_plan_bubbles(bubbles, F, first_dur_ns=100) == pf.pf_plan_bubbles(bubbles, F)
     assert pf.pf_plan_bubbles(bubbles, F, first_dur_ns=40) != pf.pf_plan_bubbles(bubbles, F)
+    # one bubble per cycle, too little of it left for the first node: an empty first chunk, not an infeasible node
+    one = [dict(dur=10, free=9)]
+    got, k = pf.pf_plan_bubbles(one, [(4, 1), (4, 1)], first_dur_ns=3)
+    assert (got, k) == op.partition_fill_job([dict(dur=10, free=9, fillable=1)], [(4, 1), (4, 1)], first_dur=3)
+    assert [(c["cycle"], c["node_begin"], c["node_end"]) for c in got] == [(0, 0, 0), (1, 0, 2)]
+    with pytest.raises(pf.PipeFillError) as g:
+        pf.pf_plan_bubbles(one, [(12, 1)], first_dur_ns=3)
+    assert g.value.code == pf.PF_ERR_INFEASIBLE
 
 
 def test_plan_on_the_benchmark_schedule():

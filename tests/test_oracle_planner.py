@@ -394,6 +394,14 @@ def test_job_arriving_in_the_middle_of_a_bubble():
     chunks, k = op.partition_fill_job(B, F, first_dur=0)
     assert [(c["bubble"], c["node_begin"], c["node_end"]) for c in chunks] == [(0, 0, 0), (1, 0, 2), (0, 2, 4)]
     assert chunks[2]["cycle"] == 1                      # the second visit of bubble 0 has its full length
+    # One bubble per cycle and too little of it left for the first node: the shortened visit stays empty and the job
+    # starts with the next, whole bubble (4, 8 < 10); it is not a sign that the node fits nowhere.  A node that
+    # does fit nowhere (12 in bubbles of 10) still is.
+    one = [dict(dur=10, free=9, fillable=1)]
+    chunks, k = op.partition_fill_job(one, [(4, 1), (4, 1)], first_dur=3)
+    assert k == 1 and [(c["cycle"], c["node_begin"], c["node_end"]) for c in chunks] == [(0, 0, 0), (1, 0, 2)]
+    with pytest.raises(op.Infeasible):
+        op.partition_fill_job(one, [(12, 1)], first_dur=3)
     # the fill fraction and the switch time apply to the shortened visit too: floor(5 * 0.9) - 1 = 3 -> one node
     chunks, _ = op.partition_fill_job(B, F, 900_000, 0, 1, first_dur=5)
     assert (chunks[0]["node_begin"], chunks[0]["node_end"]) == (0, 1)
