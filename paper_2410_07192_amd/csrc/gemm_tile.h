@@ -219,7 +219,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TN][TM], uint4* smem
     static_assert(!(EPI & E_DACT) || EPI == E_DACT, "GELU' multiplies the plain product only");
     const bool aligned16 = ((N & 7) == 0) && ((((uintptr_t)C | (uintptr_t)ep.resid | (uintptr_t)ep.preact_out |
                                                  (uintptr_t)ep.dact_in) & 15) == 0);
-    if (interior && aligned16) {
+    if (interior && aligned16 && N <= (1 << 21)) {
       constexpr int SLOTS = BN / 8, NT = 64 * NW, PER = BM * BN / 8 / NT;
       // 16-byte slot of a row, moved per row so that the lanes of a wave (32 rows, same column group) spread
       // over the banks: XOR when the slot count is a power of two, rotation otherwise
@@ -228,6 +228,45 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TN][TM], uint4* smem
         else return (slot + row) % SLOTS;
       };
       uint2* st8 = (uint2*)smem;
+      // Piece i of a thread on the way out (and of the residual on the way in): 16 bytes of row i * RP + r0 when the
+      // threads of a workgroup cover whole rows.  The tile's corner is the base of a raw buffer, the thread's place a
+      // 32-bit offset computed once, the rows of piece i a scalar offset (N <= 2^21 keeps all of it below 2^31): no
+      // 64-bit vector arithmetic per piece, which is what a lone wave per SIMD has least of.
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      constexpr bool ROWWISE = NT % SLOTS == 0;
+      constexpr int RP = ROWWISE ? NT / SLOTS : 1;
+      const int r0 = tid / SLOTS, slot0 = tid % SLOTS;
+      const int voff = (int)((r0 * N + slot0 * 8) * 2);
+      auto tile_rsrc = [&](const void* p) {
+        return __builtin_amdgcn_make_buffer_rsrc((void*)((const bf16_t*)p + m0 * N + n0), 0, 0x7fffffff, 0x00020000);
+      };
+      auto lds_at = [&](int i) {
+        if constexpr (ROWWISE) {
+          const int row = i * RP + r0;
+          return row * SLOTS + swz(slot0, row);
+        } else {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          return row * SLOTS + swz(slot, row);
+        }
+      };
+      auto piece_load = [&](__amdgpu_buffer_rsrc_t rs, const void* p, int i) -> uint4 {
+        if constexpr (ROWWISE) {
+          const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, (int)(i * RP * N * 2), 0);
+          return make_uint4(v[0], v[1], v[2], v[3]);
+        } else {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          return *(const uint4*)((const bf16_t*)p + (m0 + row) * N + n0 + slot * 8);
+        }
+      };
+      auto piece_store = [&](__amdgpu_buffer_rsrc_t rs, void* p, int i, uint4 v) {
+        if constexpr (ROWWISE) {
+          const u32x4 w = {v.x, v.y, v.z, v.w};
+          __builtin_amdgcn_raw_buffer_store_b128(w, rs, voff, (int)(i * RP * N * 2), 0);
+        } else {
+          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
+          *(uint4*)((bf16_t*)p + (m0 + row) * N + n0 + slot * 8) = v;
+        }
+      };
       if constexpr (EPI & E_DACT) {
         // tile of the saved pre-activation: eight 16-byte pieces per thread at a time (more would not fit beside
         // the accumulators), then every lane picks up the values of its own accumulator elements
@@ -315,11 +354,9 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TN][TM], uint4* smem
         stage_tile(std::false_type{});
         __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_s_barrier();
+        const __amdgpu_buffer_rsrc_t prsrc = tile_rsrc(ep.preact_out);
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-          *(uint4*)((bf16_t*)ep.preact_out + (m0 + row) * N + n0 + slot * 8) = smem[row * SLOTS + swz(slot, row)];
-        }
+        for (int i = 0; i < PER; ++i) piece_store(prsrc, ep.preact_out, i, smem[lds_at(i)]);
         __builtin_amdgcn_s_waitcnt(0xc07f);
         __builtin_amdgcn_s_barrier();
       }
@@ -327,28 +364,22 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TN][TM], uint4* smem
       // accumulators go through bias / GELU / LDS
       constexpr int EARLY = PER < 8 ? PER : 8;   // more would not fit beside the accumulators
       uint4 rres[(EPI & E_RESID) ? PER : 1];
+      const __amdgpu_buffer_rsrc_t rrsrc = tile_rsrc((EPI & E_RESID) ? ep.resid : (const void*)C);
       if constexpr (EPI & E_RESID) {
 #pragma unroll
-        for (int i = 0; i < EARLY; ++i) {
-          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
-        }
+        for (int i = 0; i < EARLY; ++i) rres[i] = piece_load(rrsrc, ep.resid, i);
       }
       stage_tile(std::integral_constant<bool, (EPI & E_GELU) != 0>{});
       if constexpr (EPI & E_RESID) {   // the accumulators are dead now: the rest of the residual tile
 #pragma unroll
-        for (int i = EARLY; i < PER; ++i) {
-          const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-          rres[i] = *(const uint4*)((const bf16_t*)ep.resid + (m0 + row) * N + n0 + slot * 8);
-        }
+        for (int i = EARLY; i < PER; ++i) rres[i] = piece_load(rrsrc, ep.resid, i);
       }
       __builtin_amdgcn_s_waitcnt(0xc07f);
       __builtin_amdgcn_s_barrier();
+      const __amdgpu_buffer_rsrc_t crsrc = tile_rsrc(C);
 #pragma unroll
       for (int i = 0; i < PER; ++i) {
-        const int q = i * NT + tid, row = q / SLOTS, slot = q % SLOTS;
-        uint4 v = smem[row * SLOTS + swz(slot, row)];
-        const int64_t off = (m0 + row) * N + n0 + slot * 8;
+        uint4 v = smem[lds_at(i)];
         if constexpr (EPI & E_RESID) {
           const uint4 r = rres[i];
           const uint32_t vw[4] = {v.x, v.y, v.z, v.w}, rw[4] = {r.x, r.y, r.z, r.w};
@@ -361,7 +392,7 @@ __device__ __forceinline__ void tile_epilogue(f32x16 (&acc)[TN][TM], uint4* smem
           }
           v = make_uint4(ow[0], ow[1], ow[2], ow[3]);
         }
-        *(uint4*)((bf16_t*)C + off) = v;
+        piece_store(crsrc, C, i, v);
       }
       return;
     }
